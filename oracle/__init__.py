@@ -1,0 +1,170 @@
+"""ctypes front end of the CPU oracle (oracle/fff_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this
+package.  It knows nothing of the HIP library and shares no code with it.
+Arrays are numpy: float32, float64, or uint16 holding bf16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fff_oracle.c")
+_LIB = os.path.join(_HERE, "libfff_oracle.so")
+
+ACT_RELU = 0
+ACT_GELU = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (OpenMP over tokens)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+                               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_double
+        _lib.fff_oracle_forward_hard.argtypes = [vp] * 7 + [i32, i32, i32, i64, i64, i64, i32, vp, vp, vp]
+        _lib.fff_oracle_leaf_forward.argtypes = [vp] * 6 + [i32, i32, i32, i64, i64, i64, i32, vp]
+        _lib.fff_oracle_forward_soft.argtypes = [vp] * 7 + [i32, i32, i32, i64, i64, i64, i32, f64, vp, vp]
+        _lib.fff_oracle_bucket.argtypes = [vp, i64, i32, vp, vp, vp]
+        for n in ("training_size", "inference_size"):
+            f = getattr(_lib, "fff_oracle_" + n)
+            f.argtypes, f.restype = [i32, i32, i32], i64
+        for n in ("training_width", "inference_width"):
+            f = getattr(_lib, "fff_oracle_" + n)
+            f.argtypes, f.restype = [i32, i32], i64
+    return _lib
+
+
+def _dtype_code(arrs) -> int:
+    kinds = {a.dtype for a in arrs if a is not None}
+    if kinds == {np.dtype(np.float32)}:
+        return 0
+    if kinds == {np.dtype(np.uint16)}:
+        return 1
+    if kinds == {np.dtype(np.float64)}:
+        return 2
+    raise TypeError("oracle inputs must all be float32, all float64, or all uint16 (bf16 bits): %s" % kinds)
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a):
+    return None if a is None else np.ascontiguousarray(a)
+
+
+def _shapes(x, leaf_w1, leaf_w2, depth, leaf_width):
+    T, D = x.shape
+    NL = 1 << depth
+    assert leaf_w1.shape == (NL, leaf_width, D), (leaf_w1.shape, (NL, leaf_width, D))
+    assert leaf_w2.shape[:2] == (NL, leaf_width)
+    return T, D, leaf_w2.shape[2]
+
+
+def forward_hard(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, leaf_width, act,
+                 want_out: bool = True) -> Tuple[Optional[np.ndarray], np.ndarray, np.ndarray]:
+    """Forward_I.  Returns (out [T,O] fp64 or None, leaf_idx [T] int32, margin [T] fp64)."""
+    x, leaf_w1, leaf_b1, leaf_w2, leaf_b2 = map(_c, (x, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    T, D, O = _shapes(x, leaf_w1, leaf_w2, depth, leaf_width)
+    if depth == 0:
+        node_w = np.zeros((0, D), x.dtype)
+        node_b = np.zeros((0,), x.dtype)
+    node_w, node_b = _c(node_w), _c(node_b)
+    assert node_w.shape == ((1 << depth) - 1, D) and node_b.shape == ((1 << depth) - 1,)
+    assert leaf_b1.shape == (1 << depth, leaf_width) and leaf_b2.shape == (1 << depth, O)
+    dt = _dtype_code((x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    out = np.empty((T, O), np.float64) if want_out else None
+    idx = np.empty((T,), np.int32)
+    margin = np.empty((T,), np.float64)
+    rc = _load().fff_oracle_forward_hard(_p(x), _p(node_w), _p(node_b), _p(leaf_w1), _p(leaf_b1),
+                                         _p(leaf_w2), _p(leaf_b2), depth, leaf_width, act, T, D, O,
+                                         dt, _p(out), _p(idx), _p(margin))
+    if rc:
+        raise ValueError("fff_oracle_forward_hard: bad arguments (%d)" % rc)
+    return out, idx, margin
+
+
+def leaf_forward(x, leaf_w1, leaf_b1, leaf_w2, leaf_b2, leaf_idx, depth, leaf_width, act) -> np.ndarray:
+    """The leaf network of the given leaf, per token.  Returns out [T,O] fp64."""
+    x, leaf_w1, leaf_b1, leaf_w2, leaf_b2 = map(_c, (x, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    T, D, O = _shapes(x, leaf_w1, leaf_w2, depth, leaf_width)
+    leaf_idx = np.ascontiguousarray(leaf_idx, dtype=np.int32)
+    assert leaf_idx.shape == (T,)
+    dt = _dtype_code((x, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    out = np.empty((T, O), np.float64)
+    rc = _load().fff_oracle_leaf_forward(_p(x), _p(leaf_w1), _p(leaf_b1), _p(leaf_w2), _p(leaf_b2),
+                                         _p(leaf_idx), depth, leaf_width, act, T, D, O, dt, _p(out))
+    if rc:
+        raise ValueError("fff_oracle_leaf_forward: bad arguments (%d)" % rc)
+    return out
+
+
+def forward_soft(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, leaf_width, act,
+                 node_scale: float = 1.0) -> Tuple[np.ndarray, np.ndarray]:
+    """Forward_T.  Returns (out [T,O] fp64, mixture weights [T, 2^d] fp64)."""
+    x, leaf_w1, leaf_b1, leaf_w2, leaf_b2 = map(_c, (x, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    T, D, O = _shapes(x, leaf_w1, leaf_w2, depth, leaf_width)
+    if depth == 0:
+        node_w = np.zeros((0, D), x.dtype)
+        node_b = np.zeros((0,), x.dtype)
+    node_w, node_b = _c(node_w), _c(node_b)
+    dt = _dtype_code((x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    out = np.empty((T, O), np.float64)
+    mix = np.empty((T, 1 << depth), np.float64)
+    rc = _load().fff_oracle_forward_soft(_p(x), _p(node_w), _p(node_b), _p(leaf_w1), _p(leaf_b1),
+                                         _p(leaf_w2), _p(leaf_b2), depth, leaf_width, act, T, D, O,
+                                         dt, float(node_scale), _p(out), _p(mix))
+    if rc:
+        raise ValueError("fff_oracle_forward_soft: bad arguments (%d)" % rc)
+    return out, mix
+
+
+def bucket(leaf_idx, depth) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """(count [2^d], offset [2^d + 1], perm [T]) of the per-leaf token lists."""
+    leaf_idx = np.ascontiguousarray(leaf_idx, dtype=np.int32)
+    T, NL = leaf_idx.shape[0], 1 << depth
+    count = np.empty((NL,), np.int32)
+    offset = np.empty((NL + 1,), np.int32)
+    perm = np.empty((T,), np.int32)
+    rc = _load().fff_oracle_bucket(_p(leaf_idx), T, depth, _p(count), _p(offset), _p(perm))
+    if rc:
+        raise ValueError("fff_oracle_bucket: leaf index out of range (%d)" % rc)
+    return count, offset, perm
+
+
+def training_size(depth, node_size, leaf_size):
+    return int(_load().fff_oracle_training_size(depth, node_size, leaf_size))
+
+
+def inference_size(depth, node_size, leaf_size):
+    return int(_load().fff_oracle_inference_size(depth, node_size, leaf_size))
+
+
+def training_width(depth, leaf_size):
+    return int(_load().fff_oracle_training_width(depth, leaf_size))
+
+
+def inference_width(depth, leaf_size):
+    return int(_load().fff_oracle_inference_width(depth, leaf_size))
+
+
+def num_threads() -> int:
+    return int(_load().fff_oracle_num_threads())
