@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of hard-routed FFF inference on one MI355X.
+
+One "step" is one call of fff_forward_hard over a whole batch of synthetic
+tokens (tree descent, bucketing, leaf networks, output rows), inputs already
+resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C4]
+
+Beside the headline tokens/s the line carries: the roofline position of the
+dominant kernel (algorithmic bytes per launch / its average duration measured
+with HIP events recorded on the call's stream inside the library), the same
+for every stage and for the whole path, the CPU oracle timed on this host, and
+an equal-training-width dense feedforward on the same GPU for the speedup.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+
+def algorithmic_bytes(w, ref_idx):
+    """Bytes the method itself must move: x once, out once, leaf_idx, and every
+    node row / leaf block that some token actually touches, once."""
+    import numpy as np
+    s = 2 if w.dtype == 1 else 4
+    T, D, O, L, d = w.T, w.D, w.O, w.leaf_width, w.depth
+    leaves = np.unique(ref_idx)
+    nodes = set()
+    cur = leaves.astype(np.int64)
+    for m in range(d - 1, -1, -1):           # parents of the touched leaves, level by level
+        cur = np.unique(cur >> 1)
+        nodes.update(((1 << m) - 1 + cur).tolist())
+    u_node, u_leaf = len(nodes), int(leaves.size)
+    node_bytes = u_node * (D * s + s)
+    leaf_bytes = u_leaf * (L * D * s + L * s + L * O * s + O * s)
+    return {
+        "u_node": u_node, "u_leaf": u_leaf,
+        "path": T * D * s + T * O * s + 4 * T + node_bytes + leaf_bytes,
+        "descent": T * D * s + 4 * T + node_bytes,
+        "bucketing": 4 * T + 4 * T,                     # leaf_idx in, perm out
+        "leaf": T * D * s + T * O * s + 8 * T + leaf_bytes,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C4", help="workload: C1 C2 C2c C3 C4 C5")
+    ap.add_argument("--sets", type=int, default=0, help="distinct x/out buffer sets to rotate (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-stage-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import fff_workloads as W
+    import paper_2308_14711_amd as F
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    F.lib()   # fail loudly here if the HIP library is missing
+
+    w = W.config(args.config, keep_f32=False)
+    tdt = torch.bfloat16 if w.dtype == W.DTYPE_BF16 else torch.float32
+
+    def up(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    dev = {k: up(w.device_array(k)) for k in W.TENSORS}
+    nw = dev["node_w"] if w.depth else None
+    nb = dev["node_b"] if w.depth else None
+
+    # Rotate distinct x/out buffers so that a working set smaller than the 256 MB
+    # last-level cache is not served from it: every set holds the same tokens.
+    es = 2 if w.dtype == W.DTYPE_BF16 else 4
+    per_set = w.T * (w.D + w.O) * es
+    nsets = args.sets or max(1, min(8, int(np.ceil(1.2e9 / max(per_set, 1)))))
+    xs = [dev["x"]] + [dev["x"].clone() for _ in range(nsets - 1)]
+    outs = [torch.empty((w.T, w.O), dtype=tdt, device="cuda") for _ in range(nsets)]
+    idx = torch.empty((w.T,), dtype=torch.int32, device="cuda")
+    F.fff_reserve_workspace(w.T, w.depth)
+
+    def step(i):
+        j = i % nsets
+        F.fff_forward_hard(xs[j], nw, nb, dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"], dev["leaf_b2"],
+                           w.depth, w.leaf_width, w.act, outs[j], idx)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = w.T * args.steps / (t1 - t0)
+
+    # routing of the oracle: which nodes and leaves are touched (host side, for the byte model)
+    import oracle
+    ins = [np.ascontiguousarray(w.device_array(k)) for k in W.TENSORS]
+    t2 = time.perf_counter()
+    ref_out, ref_idx, margin = oracle.forward_hard(*ins, w.depth, w.leaf_width, w.act,
+                                                   want_out=not args.no_cpu_baseline)
+    t3 = time.perf_counter()
+    alg = algorithmic_bytes(w, ref_idx)
+
+    # per-stage durations: HIP events recorded by the library on the call's stream
+    stages = {}
+    if not args.no_stage_timing:
+        F.fff_set_option("stage_timing", 1)
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        d_ms, b_ms, l_ms, calls = F.fff_stage_times()
+        F.fff_set_option("stage_timing", 0)
+        for name, ms in (("descent", d_ms), ("bucketing", b_ms), ("leaf", l_ms)):
+            avg = ms / max(calls, 1)
+            gbs = alg[name] / (avg * 1e-3) / 1e9 if avg > 0 else 0.0
+            stages[name] = {"avg_ms": round(avg, 5), "alg_bytes": alg[name], "GBps": round(gbs, 1),
+                            "frac": round(gbs / HBM_PEAK_GBS, 4)}
+    dom = max(stages, key=lambda k: stages[k]["avg_ms"]) if stages else None
+    roofline = None
+    if dom:
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": stages[dom]["GBps"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": stages[dom]["frac"], "traffic": None}
+    path_gbs = alg["path"] / (ms_per_step * 1e-3) / 1e9
+
+    # parity spot check of the timed configuration against the oracle
+    got_idx = idx.cpu().numpy()
+    mism = np.nonzero(got_idx != ref_idx)[0]
+    parity = {"idx_mismatch": int(mism.size),
+              "idx_mismatch_outside_margin": int((margin[mism] >= 1e-4).sum()),
+              "margin_tokens": int((margin < 1e-4).sum())}
+    if ref_out is not None:
+        got = outs[(args.steps - 1) % nsets].float().cpu().numpy().astype(np.float64)
+        keep = got_idx == ref_idx
+        scale = np.maximum(np.abs(ref_out[keep]).max(axis=1), 1e-30)
+        parity["max_rel_row_err"] = float((np.abs(got[keep] - ref_out[keep]).max(axis=1) / scale).max())
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = {"value": round(w.T / (t3 - t2), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": "all %d tokens of %s, one pass, fp64, OpenMP over tokens" % (w.T, w.name),
+               "seconds": round(t3 - t2, 3)}
+
+    dense = None
+    if not args.no_dense and (1 << w.depth) * w.leaf_width <= 8192:
+        H = (1 << w.depth) * w.leaf_width          # equal training width
+        W1 = dev["leaf_w1"].reshape(H, w.D)
+        B1 = dev["leaf_b1"].reshape(H)
+        W2 = dev["leaf_w2"].reshape(H, w.O)
+        B2 = dev["leaf_b2"][0]
+        act = torch.nn.functional.gelu if w.act == W.ACT_GELU else torch.relu
+
+        def dense_step(j):
+            h = act(torch.addmm(B1, xs[j], W1.t()))
+            torch.addmm(B2, h, W2, out=outs[j])
+
+        for i in range(max(3, args.warmup // 4)):
+            dense_step(i % nsets)
+        torch.cuda.synchronize()
+        n = max(10, args.steps // 4)
+        t4 = time.perf_counter()
+        for i in range(n):
+            dense_step(i % nsets)
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - t4) * 1e3 / n
+        dense = {"hidden": H, "ms_per_step": round(dense_ms, 4), "speedup": round(dense_ms / ms_per_step, 2),
+                 "impl": "torch addmm + activation + addmm, same dtype"}
+
+    line = {
+        "metric": "fff_hard_inference_tokens_per_s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == W.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (w.name, w.note), "T": w.T, "D": w.D, "O": w.O, "depth": w.depth,
+                   "leaf_width": w.leaf_width, "act": "gelu" if w.act else "relu", "buffer_sets": nsets,
+                   "seed": 0},
+        "roofline": roofline,
+        "path": {"alg_bytes": alg["path"], "GBps": round(path_gbs, 1), "frac": round(path_gbs / HBM_PEAK_GBS, 4),
+                 "u_node": alg["u_node"], "u_leaf": alg["u_leaf"]},
+        "stages": stages,
+        "cpu_baseline": cpu,
+        "dense_ff": dense,
+        "parity": parity,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -39,30 +39,58 @@ def _stream(seed: int, tag: str, sub: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[(seed << 8) | _TAGS[tag], sub]))
 
 
-def bf16_round(a: np.ndarray) -> np.ndarray:
+def _round_chunk(c32: np.ndarray, tmp: np.ndarray, out16: np.ndarray) -> None:
+    """bf16 round-to-nearest-even of the uint32 view ``c32`` into ``out16``,
+    using ``tmp`` (uint32, same length) as scratch; nothing is allocated."""
+    np.right_shift(c32, np.uint32(16), out=tmp)
+    np.bitwise_and(tmp, np.uint32(1), out=tmp)
+    np.add(tmp, np.uint32(0x7FFF), out=tmp)
+    np.add(tmp, c32, out=tmp)
+    np.right_shift(tmp, np.uint32(16), out=tmp)
+    np.copyto(out16, tmp, casting="unsafe")
+
+
+def bf16_round(a: np.ndarray, chunk: int = 1 << 22) -> np.ndarray:
     """fp32 array -> uint16 bf16 bit patterns, round to nearest even."""
-    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
-    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
-    return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.reshape(-1).view(np.uint32)
+    out = np.empty(u.shape, dtype=np.uint16)
+    tmp = np.empty((min(chunk, max(u.size, 1)),), dtype=np.uint32)
+    for i in range(0, u.size, chunk):
+        c = u[i:i + chunk]
+        _round_chunk(c, tmp[:c.size], out[i:i + chunk])
+    return out.reshape(a.shape)
 
 
 def bf16_widen(bits: np.ndarray) -> np.ndarray:
     """uint16 bf16 bit patterns -> the same values as fp32 (exact)."""
-    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    out = np.empty(bits.shape, dtype=np.uint32)
+    np.copyto(out, bits, casting="unsafe")
+    np.left_shift(out, np.uint32(16), out=out)
+    return out.view(np.float32)
 
 
-def _uniform(seed, tag, shape, bound, chunk_rows=4096):
-    """U(-bound, bound) in fp32, drawn in row chunks to bound peak memory."""
+def _uniform(seed, tag, shape, bound, as_bf16_bits=False, chunk=1 << 22):
+    """U(-bound, bound) drawn in fp32 in fixed-size chunks of one stream.
+    Returns fp32 values, or (``as_bf16_bits``) their bf16 roundings as uint16
+    without ever holding the fp32 tensor."""
     shape = tuple(int(s) for s in shape)
-    out = np.empty(shape, dtype=np.float32)
-    flat = out.reshape(shape[0], -1) if len(shape) > 1 else out.reshape(-1, 1)
-    n0 = flat.shape[0]
+    n = int(np.prod(shape))
     g = _stream(seed, tag)
-    for r0 in range(0, n0, chunk_rows):
-        r1 = min(n0, r0 + chunk_rows)
-        blk = g.random((r1 - r0, flat.shape[1]), dtype=np.float32)
-        flat[r0:r1] = (blk * np.float32(2.0) - np.float32(1.0)) * np.float32(bound)
-    return out
+    two_b, b = np.float32(2.0 * bound), np.float32(bound)
+    out = np.empty((n,), dtype=np.uint16 if as_bf16_bits else np.float32)
+    buf = np.empty((min(chunk, max(n, 1)),), dtype=np.float32)
+    tmp = np.empty(buf.shape, dtype=np.uint32) if as_bf16_bits else None
+    for i in range(0, n, chunk):
+        blk = buf[:min(chunk, n - i)]
+        g.random(out=blk, dtype=np.float32)
+        np.multiply(blk, two_b, out=blk)
+        np.subtract(blk, b, out=blk)
+        if as_bf16_bits:
+            _round_chunk(blk.view(np.uint32), tmp[:blk.size], out[i:i + blk.size])
+        else:
+            out[i:i + blk.size] = blk
+    return out.reshape(shape)
 
 
 def _normal(seed, tag, shape, sigma=1.0):
@@ -106,18 +134,6 @@ class Workload:
 TENSORS = ("x", "node_w", "node_b", "leaf_w1", "leaf_b1", "leaf_w2", "leaf_b2")
 
 
-def _finish(w: Workload, keep_f32: bool = True) -> Workload:
-    if w.dtype == DTYPE_BF16:
-        for k in TENSORS:
-            b = bf16_round(w.f32[k])
-            w.bits[k] = b
-            if keep_f32:
-                w.f32[k] = bf16_widen(b).reshape(w.f32[k].shape)
-            else:
-                del w.f32[k]
-    return w
-
-
 def make_layer(name, T, D, O, depth, leaf_width, act, dtype, seed=0,
                x_dist="normal", node_b="uniform", leaf_b="uniform",
                keep_f32=True, note="") -> Workload:
@@ -130,44 +146,61 @@ def make_layer(name, T, D, O, depth, leaf_width, act, dtype, seed=0,
     "centred0.1" (N(0,0.1) minus half the row sum of node_w, which centres the
     logit of U(0,1) inputs), or "zipf" (see ``zipf_node_bias``).
     ``leaf_b``: "zero" or "uniform" (bound 1/sqrt(fan_in) of its layer).
+    ``keep_f32`` = False drops the fp32 copies of a bf16 workload (the oracle
+    reads bf16 bit patterns directly), which matters for the largest one.
     """
     NN, NL = (1 << depth) - 1, 1 << depth
     w = Workload(name, T, D, O, depth, leaf_width, act, dtype, note=note)
-    f = w.f32
+    bf = dtype == DTYPE_BF16
+
+    def put(key, arr, is_bits=False):
+        """Store a tensor: fp32 workloads keep fp32; bf16 workloads keep the
+        rounded bits and (optionally) the widened values."""
+        if not bf:
+            w.f32[key] = arr
+            return
+        bits = arr if is_bits else bf16_round(arr)
+        w.bits[key] = bits
+        if keep_f32 or key == "node_w":
+            w.f32[key] = bf16_widen(bits)
+
+    def uni(key, shape, bound):
+        put(key, _uniform(seed, key, shape, bound, as_bf16_bits=bf), is_bits=bf)
+
     if x_dist == "normal":
-        f["x"] = _normal(seed, "x", (T, D))
+        put("x", _normal(seed, "x", (T, D)))
     elif x_dist == "uniform01":
-        f["x"] = _stream(seed, "x").random((T, D), dtype=np.float32)
+        put("x", _stream(seed, "x").random((T, D), dtype=np.float32))
     else:
         raise ValueError(x_dist)
     bD = 1.0 / np.sqrt(D)
     bL = 1.0 / np.sqrt(leaf_width)
-    f["node_w"] = _uniform(seed, "node_w", (NN, D), bD)
-    f["leaf_w1"] = _uniform(seed, "leaf_w1", (NL, leaf_width, D), bD)
-    f["leaf_w2"] = _uniform(seed, "leaf_w2", (NL, leaf_width, O), bL)
+    uni("node_w", (NN, D), bD)
+    uni("leaf_w1", (NL, leaf_width, D), bD)
+    uni("leaf_w2", (NL, leaf_width, O), bL)
     if leaf_b == "zero":
-        f["leaf_b1"] = np.zeros((NL, leaf_width), np.float32)
-        f["leaf_b2"] = np.zeros((NL, O), np.float32)
+        put("leaf_b1", np.zeros((NL, leaf_width), np.float32))
+        put("leaf_b2", np.zeros((NL, O), np.float32))
     else:
-        f["leaf_b1"] = _uniform(seed, "leaf_b1", (NL, leaf_width), bD)
-        f["leaf_b2"] = _uniform(seed, "leaf_b2", (NL, O), bL)
-    if dtype == DTYPE_BF16:
-        # biases that are built from node_w must see the rounded rows
-        f["node_w"] = bf16_widen(bf16_round(f["node_w"])).reshape(NN, D)
+        uni("leaf_b1", (NL, leaf_width), bD)
+        uni("leaf_b2", (NL, O), bL)
+    nw = w.f32["node_w"]           # for bf16: the rounded rows, as the biases must see them
     if node_b == "zero":
-        f["node_b"] = np.zeros((NN,), np.float32)
+        put("node_b", np.zeros((NN,), np.float32))
     elif node_b == "uniform":
-        f["node_b"] = _uniform(seed, "node_b", (NN,), bD)
+        uni("node_b", (NN,), bD)
     elif node_b == "normal0.1":
-        f["node_b"] = _normal(seed, "node_b", (NN,), 0.1)
+        put("node_b", _normal(seed, "node_b", (NN,), 0.1))
     elif node_b == "centred0.1":
-        f["node_b"] = (_normal(seed, "node_b", (NN,), 0.1)
-                       - 0.5 * f["node_w"].sum(axis=1, dtype=np.float64)).astype(np.float32)
+        put("node_b", (_normal(seed, "node_b", (NN,), 0.1)
+                       - 0.5 * nw.sum(axis=1, dtype=np.float64)).astype(np.float32))
     elif node_b == "zipf":
-        f["node_b"] = zipf_node_bias(f["node_w"], depth, seed)
+        put("node_b", zipf_node_bias(nw, depth, seed))
     else:
         raise ValueError(node_b)
-    return _finish(w, keep_f32)
+    if bf and not keep_f32:
+        w.f32.pop("node_w", None)
+    return w
 
 
 def zipf_node_bias(node_w: np.ndarray, depth: int, seed: int, s: float = 1.1,

@@ -1,0 +1,175 @@
+/*
+ * fff.h -- C ABI of the MI355X (gfx950) library for hard-routed inference of
+ * Fast Feedforward (FFF) layers.
+ *
+ * An FFF of depth d and leaf size l (Definition, Section "Algorithm") is a
+ * balanced binary tree of 2^d - 1 node neurons over 2^d leaf networks, each a
+ * <D, l, O> feedforward block.  Inference (Forward_I of Algorithm 1) walks one
+ * root-to-leaf path per token -- at each node the logit w.x + b is compared
+ * with 0 (output c >= 1/2 goes to child 2n+1, else 2n; paragraph "Inference
+ * complexity" describes exactly this multiply-accumulate / compare / advance
+ * loop) -- and evaluates only the leaf it arrives at.
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers to dense row-major arrays owned
+ *     by the caller.  The library reads inputs, fully overwrites outputs, and
+ *     keeps no reference to either after the enqueued work has run.
+ *   - `dtype` selects the element type of every floating tensor of the call:
+ *     FFF_F32 (float) or FFF_BF16 (bfloat16 bit patterns, 2 bytes).  All
+ *     accumulation is fp32; bf16 outputs are rounded to nearest even.
+ *   - Node rows are in heap order: node N_{m,n} is row 2^m - 1 + n, its
+ *     children are rows 2i+1 (taken when logit < 0) and 2i+2 (logit >= 0, ties
+ *     and -0.0 included; a NaN logit compares false and goes to 2i+1).
+ *   - leaf_idx[t] is the position n of the leaf N_{d,n} that token t reaches:
+ *     the d decisions read as a binary number, root decision first.
+ *   - Leaf k computes h = act(W1[k] x + b1[k]), y = W2[k]^T h + b2[k], with
+ *     W1 [l, D] and W2 [l, O]: per neuron its D input weights, then its O
+ *     output weights (the paper's "one set of neurons that has both input and
+ *     output weights").
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only
+ *     enqueue work on it and return; they never synchronise the device.
+ *   - Every call returns an fff_status.  Arguments are checked on the host
+ *     before any HIP call is made: a bad argument returns its error code and
+ *     enqueues nothing.  Nothing throws or aborts.
+ *   - The library keeps one workspace per device (bucket tables, work lists).
+ *     It is grown with hipMalloc when a call needs more than is there (never
+ *     shrunk), so calls on one device must not overlap in time, and a caller
+ *     that cannot tolerate an allocation mid-stream calls
+ *     fff_reserve_workspace first.
+ */
+#ifndef FFF_H
+#define FFF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FFF_OK = 0,
+    FFF_ERR_NULL = 1,        /* a required pointer is NULL */
+    FFF_ERR_SHAPE = 2,       /* sizes inconsistent or out of the supported range */
+    FFF_ERR_DTYPE = 3,       /* unknown dtype */
+    FFF_ERR_RANGE = 4,       /* depth / leaf_width / T out of range */
+    FFF_ERR_UNSUPPORTED = 5, /* unknown activation or option */
+    FFF_ERR_WORKSPACE = 6,   /* workspace could not be allocated */
+    FFF_ERR_DEVICE = 7,      /* a HIP call failed (see fff_last_device_error) */
+    FFF_ERR_ALIAS = 8        /* out overlaps x */
+} fff_status;
+
+typedef enum { FFF_F32 = 0, FFF_BF16 = 1 } fff_dtype;
+
+/* The paper does not name the leaf activation; ReLU and exact GELU
+ * v * Phi(v) = 0.5 v (1 + erf(v / sqrt 2)) are offered. */
+typedef enum { FFF_ACT_RELU = 0, FFF_ACT_GELU = 1 } fff_act;
+
+#define FFF_MAX_DEPTH 24
+
+/*
+ * Forward_I of Algorithm 1 for T tokens: tree descent, per-leaf bucketing,
+ * leaf networks, outputs written back in token order.
+ *
+ *   x        [T, D]                 tokens
+ *   node_w   [2^depth - 1, D]       node neurons, heap order (ignored, may be NULL, when depth == 0)
+ *   node_b   [2^depth - 1]
+ *   leaf_w1  [2^depth, leaf_width, D]
+ *   leaf_b1  [2^depth, leaf_width]
+ *   leaf_w2  [2^depth, leaf_width, O]
+ *   leaf_b2  [2^depth, O]
+ *   depth    0..FFF_MAX_DEPTH; leaf_width >= 1; act: fff_act
+ *   out      [T, O]  same dtype as x, every row written exactly once; must not overlap x
+ *   leaf_idx [T] int32, or NULL if the caller does not want the regions
+ *   stream   hipStream_t
+ *   T >= 0 (T == 0 is FFF_OK and enqueues nothing), D >= 1, O >= 1, dtype: fff_dtype
+ *
+ * Errors: FFF_ERR_NULL, FFF_ERR_RANGE (depth, leaf_width, T), FFF_ERR_SHAPE
+ * (D, O < 1, or T * max(D, O), 2^depth * leaf_width * max(D, O) beyond 2^40
+ * elements), FFF_ERR_DTYPE, FFF_ERR_UNSUPPORTED (act), FFF_ERR_ALIAS,
+ * FFF_ERR_WORKSPACE, FFF_ERR_DEVICE.
+ */
+int fff_forward_hard(const void* x, const void* node_w, const void* node_b,
+                     const void* leaf_w1, const void* leaf_b1,
+                     const void* leaf_w2, const void* leaf_b2,
+                     int depth, int leaf_width, int act,
+                     void* out, int32_t* leaf_idx, void* stream,
+                     int64_t T, int64_t D, int64_t O, int dtype);
+
+/*
+ * The stages of fff_forward_hard on their own (same conventions, same
+ * kernels); used by tests and profiles.
+ *
+ * fff_descend: the tree walk of Forward_I alone; writes leaf_idx [T].
+ */
+int fff_descend(const void* x, const void* node_w, const void* node_b, int depth,
+                int32_t* leaf_idx, void* stream, int64_t T, int64_t D, int dtype);
+
+/*
+ * fff_bucket: per-leaf token lists from leaf_idx [T] (values in [0, 2^depth);
+ * behaviour is undefined otherwise).  count [2^depth]; offset [2^depth + 1] =
+ * exclusive prefix sum of count; perm [T] = token ids grouped by leaf, in
+ * ascending token order inside a leaf (stable).  Any of the three outputs may
+ * be NULL.  Not part of the paper's method: it only lets tokens of one leaf
+ * share one read of that leaf's weights.
+ */
+int fff_bucket(const int32_t* leaf_idx, int64_t T, int depth,
+               int32_t* count, int32_t* offset, int32_t* perm, void* stream);
+
+/*
+ * fff_leaf_forward: the leaf networks alone, token t evaluated at leaf
+ * leaf_idx[t] (device array, values in [0, 2^depth)); buckets tokens
+ * internally.  Writes out [T, O].
+ */
+int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1,
+                     const void* leaf_w2, const void* leaf_b2, const int32_t* leaf_idx,
+                     int depth, int leaf_width, int act, void* out, void* stream,
+                     int64_t T, int64_t D, int64_t O, int dtype);
+
+/* Bytes of workspace a call with these sizes uses on the current device. */
+size_t fff_workspace_bytes(int64_t T, int depth);
+
+/* Make sure the current device's workspace holds at least fff_workspace_bytes(T, depth)
+ * (allocates now, so that later calls with sizes up to these do not). */
+int fff_reserve_workspace(int64_t T, int depth);
+
+/* Free the workspaces of all devices (call with no work in flight). */
+int fff_release_workspace(void);
+
+/*
+ * Tuning and test switches (process-wide; not thread-safe against running calls).
+ *   "leaf_path"      0 = choose per bucket (default), 1 = every token through the
+ *                    gather path, 2 = every bucket through the MFMA tile path
+ *                    (bf16 only; silently the gather path otherwise)
+ *   "gemm_min_rows"  smallest bucket handed to the MFMA tile path (default 8)
+ *   "fused_max_T"    T up to which one fused launch replaces the staged path (0 = never)
+ *   "bucketing"      1 (default) = the leaf kernel visits tokens grouped by leaf,
+ *                    0 = in token order (no bucketing stage)
+ *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages
+ *                    (read them with fff_stage_times); 0 (default) = off
+ * Unknown names or negative values return FFF_ERR_UNSUPPORTED.
+ */
+int fff_set_option(const char* name, int64_t value);
+int fff_get_option(const char* name, int64_t* value);
+
+/*
+ * Waits for, sums and clears the stage events recorded since the last call:
+ * ms[0..2] = total milliseconds of descent, bucketing and leaf kernel (with
+ * output rows), *calls = number of fff_forward_hard calls summed.  Blocks
+ * until those calls have finished.
+ */
+int fff_stage_times(double* ms, int64_t* calls);
+
+/* Human-readable name of a status code (static string). */
+const char* fff_status_string(int status);
+
+/* Text of the last HIP error seen on this thread's calls ("" if none). */
+const char* fff_last_device_error(void);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int fff_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFF_H */

@@ -1,0 +1,383 @@
+// C ABI of the FFF library: argument checks (host only, before any HIP call),
+// per-device workspace, and the sequence of kernel launches of Forward_I
+// (Algorithm 1): descent -> bucketing -> leaf networks with fused output rows.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/fff.h"
+#include "fff_internal.h"
+
+namespace fff {
+namespace {
+
+thread_local std::string g_last_error;
+
+struct DeviceWs {
+    void* base = nullptr;
+    size_t bytes = 0;
+};
+constexpr int kMaxDevices = 64;
+DeviceWs g_ws[kMaxDevices];
+std::mutex g_mu;
+
+struct Options {
+    int64_t leaf_path = 0;       // 0 auto, 1 gather only, 2 tiles only
+    int64_t gemm_min_rows = 8;
+    int64_t fused_max_T = 0;
+    int64_t bucketing = 1;       // 0: leaf kernel visits tokens in token order
+    int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
+} g_opt;
+
+// Events recorded around the stages of fff_forward_hard while "stage_timing" is on:
+// four per call (start, after descent, after bucketing, after the leaf kernel).
+std::vector<hipEvent_t> g_stage_events;
+
+void stage_mark(hipStream_t s) {
+    if (!g_opt.stage_timing) return;
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    if (hipEventRecord(e, s) != hipSuccess) {
+        (void)hipEventDestroy(e);
+        return;
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_stage_events.push_back(e);
+}
+
+constexpr int64_t kAlignWords = 64;            // 256-byte regions
+constexpr int64_t kMaxMatrixWords = 8 << 20;   // per-chunk histogram budget (32 MiB)
+constexpr int64_t kCtrlWords = 64;
+
+int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    int64_t n_chunks, max_tiles;
+    int64_t o_ctrl, o_leaf, o_rank, o_perm, o_count, o_offset, o_tileoff, o_matrix, o_tiles, total;
+};
+
+Layout layout_for(int64_t T, int depth) {
+    Layout l;
+    const int64_t NL = (int64_t)1 << depth;
+    const int64_t per_round = (T + kChunkTokens - 1) / kChunkTokens;
+    int64_t c = kMaxMatrixWords / NL;
+    if (c < 1) c = 1;
+    if (c > per_round) c = per_round;
+    if (c < 1) c = 1;
+    l.n_chunks = c;
+    l.max_tiles = (T + kTileRows - 1) / kTileRows + (NL < T ? NL : T);
+    int64_t o = 0;
+    auto take = [&](int64_t words) { int64_t at = o; o += round_up(words, kAlignWords); return at; };
+    l.o_ctrl = take(kCtrlWords);
+    l.o_leaf = take(T);
+    l.o_rank = take(T);
+    l.o_perm = take(T);
+    l.o_count = take(NL);
+    l.o_offset = take(NL + 1);
+    l.o_tileoff = take(NL + 1);
+    l.o_matrix = take(c * NL);
+    l.o_tiles = take(2 * l.max_tiles);
+    l.total = o;
+    return l;
+}
+
+int set_device_error(hipError_t e, const char* what) {
+    g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+    return FFF_ERR_DEVICE;
+}
+
+// Grows the current device's workspace if needed and carves it for (T, depth).
+int get_workspace(int64_t T, int depth, Workspace* ws, Layout* lay) {
+    *lay = layout_for(T, depth);
+    const size_t need = (size_t)lay->total * sizeof(int32_t);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return set_device_error(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) {
+        g_last_error = "device ordinal out of range";
+        return FFF_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceWs& d = g_ws[dev];
+    if (d.bytes < need) {
+        if (d.base) {
+            e = hipFree(d.base);   // waits for work that may still use it
+            d.base = nullptr;
+            d.bytes = 0;
+            if (e != hipSuccess) return set_device_error(e, "hipFree(workspace)");
+        }
+        void* p = nullptr;
+        e = hipMalloc(&p, need);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            g_last_error = std::string("hipMalloc(workspace): ") + hipGetErrorString(e);
+            return FFF_ERR_WORKSPACE;
+        }
+        e = hipMemset(p, 0, kCtrlWords * sizeof(int32_t));   // ticket counters start at zero
+        if (e != hipSuccess) {
+            (void)hipFree(p);
+            return set_device_error(e, "hipMemset(workspace)");
+        }
+        d.base = p;
+        d.bytes = need;
+    }
+    int32_t* b = (int32_t*)d.base;
+    ws->ctrl = b + lay->o_ctrl;
+    ws->leaf_idx = b + lay->o_leaf;
+    ws->rank = b + lay->o_rank;
+    ws->perm = b + lay->o_perm;
+    ws->count = b + lay->o_count;
+    ws->offset = b + lay->o_offset;
+    ws->tile_off = b + lay->o_tileoff;
+    ws->chunk_cnt = b + lay->o_matrix;
+    ws->tiles = b + lay->o_tiles;
+    ws->n_chunks = lay->n_chunks;
+    ws->max_tiles = lay->max_tiles;
+    return FFF_OK;
+}
+
+constexpr int64_t kMaxElems = (int64_t)1 << 40;
+constexpr int64_t kMaxTokens = ((int64_t)1 << 31) - 1024;
+constexpr int kMaxLeafWidth = 4096;
+
+int check_common(int depth, int64_t T, int64_t D, int dtype) {
+    if (dtype != FFF_F32 && dtype != FFF_BF16) return FFF_ERR_DTYPE;
+    if (depth < 0 || depth > FFF_MAX_DEPTH) return FFF_ERR_RANGE;
+    if (T < 0 || T > kMaxTokens) return FFF_ERR_RANGE;
+    if (D < 1 || D > kMaxElems) return FFF_ERR_SHAPE;
+    if (T * D > kMaxElems || ((int64_t)1 << depth) * D > kMaxElems) return FFF_ERR_SHAPE;
+    return FFF_OK;
+}
+
+int check_leaf(int depth, int leaf_width, int act, int64_t T, int64_t D, int64_t O) {
+    if (leaf_width < 1 || leaf_width > kMaxLeafWidth) return FFF_ERR_RANGE;
+    if (O < 1 || O > kMaxElems) return FFF_ERR_SHAPE;
+    const int64_t m = D > O ? D : O;
+    if (T * O > kMaxElems || ((int64_t)1 << depth) * leaf_width > kMaxElems / m) return FFF_ERR_SHAPE;
+    if (act != FFF_ACT_RELU && act != FFF_ACT_GELU) return FFF_ERR_UNSUPPORTED;
+    return FFF_OK;
+}
+
+bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + (uintptr_t)bbytes && b0 < a0 + (uintptr_t)abytes;
+}
+
+// Shapes the 16-byte vector kernels take: rows of D (and the token rows of x) aligned.
+bool fast_shape(const Problem& p) {
+    const int64_t per = p.bf16 ? 8 : 4;
+    return vec_ok(p.x, p.D, p.bf16) && (p.depth == 0 || vec_ok(p.node_w, p.D, p.bf16)) &&
+           vec_ok(p.leaf_w1, p.D, p.bf16) && p.D / per <= 1024 && p.L <= 64;
+}
+
+int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& ws, hipStream_t s,
+                   bool timed = false) {
+    hipError_t e;
+    if (!g_opt.bucketing) {
+        if (timed) stage_mark(s);
+        e = launch_leaf_gather(p, leaf_idx, nullptr, s);
+        if (timed) stage_mark(s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "leaf kernel launch");
+    }
+    const int64_t NL = (int64_t)1 << p.depth;
+    if ((e = launch_zero(ws.chunk_cnt, round_up(ws.n_chunks * NL, 4), s)) != hipSuccess)
+        return set_device_error(e, "zero kernel launch");
+    if ((e = launch_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, s)) != hipSuccess)
+        return set_device_error(e, "bucket kernel launch");
+    if (timed) stage_mark(s);
+    if ((e = launch_leaf_gather(p, leaf_idx, ws.perm, s)) != hipSuccess)
+        return set_device_error(e, "leaf kernel launch");
+    if (timed) stage_mark(s);
+    return FFF_OK;
+}
+
+}  // namespace
+}  // namespace fff
+
+using namespace fff;
+
+extern "C" {
+
+int fff_forward_hard(const void* x, const void* node_w, const void* node_b, const void* leaf_w1,
+                     const void* leaf_b1, const void* leaf_w2, const void* leaf_b2, int depth,
+                     int leaf_width, int act, void* out, int32_t* leaf_idx, void* stream, int64_t T,
+                     int64_t D, int64_t O, int dtype) {
+    int rc = check_common(depth, T, D, dtype);
+    if (rc == FFF_OK) rc = check_leaf(depth, leaf_width, act, T, D, O);
+    if (rc != FFF_OK) return rc;
+    if (T == 0) return FFF_OK;
+    if (!x || !leaf_w1 || !leaf_b1 || !leaf_w2 || !leaf_b2 || !out) return FFF_ERR_NULL;
+    if (depth > 0 && (!node_w || !node_b)) return FFF_ERR_NULL;
+    const int64_t es = dtype == FFF_BF16 ? 2 : 4;
+    if (overlaps(x, T * D * es, out, T * O * es)) return FFF_ERR_ALIAS;
+
+    Problem p{x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, leaf_idx,
+              T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
+    hipStream_t s = (hipStream_t)stream;
+    g_last_error.clear();
+
+    if (!fast_shape(p) || T <= g_opt.fused_max_T) {
+        hipError_t e = launch_fused_generic(p, leaf_idx, s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "fused kernel launch");
+    }
+    Workspace ws;
+    Layout lay;
+    if ((rc = get_workspace(T, depth, &ws, &lay)) != FFF_OK) return rc;
+    int32_t* li = leaf_idx ? leaf_idx : ws.leaf_idx;
+    stage_mark(s);
+    hipError_t e = launch_descend(p, li, s);
+    if (e != hipSuccess) return set_device_error(e, "descent kernel launch");
+    stage_mark(s);
+    return run_leaf_stage(p, li, ws, s, true);
+}
+
+int fff_descend(const void* x, const void* node_w, const void* node_b, int depth, int32_t* leaf_idx,
+                void* stream, int64_t T, int64_t D, int dtype) {
+    int rc = check_common(depth, T, D, dtype);
+    if (rc != FFF_OK) return rc;
+    if (T == 0) return FFF_OK;
+    if (!x || !leaf_idx) return FFF_ERR_NULL;
+    if (depth > 0 && (!node_w || !node_b)) return FFF_ERR_NULL;
+    Problem p{x, node_w, node_b, nullptr, nullptr, nullptr, nullptr, nullptr, leaf_idx,
+              T, D, 1, depth, 1, 0, dtype == FFF_BF16};
+    g_last_error.clear();
+    hipError_t e = launch_descend(p, leaf_idx, (hipStream_t)stream);
+    return e == hipSuccess ? FFF_OK : set_device_error(e, "descent kernel launch");
+}
+
+int fff_bucket(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, int32_t* offset,
+               int32_t* perm, void* stream) {
+    if (depth < 0 || depth > FFF_MAX_DEPTH || T < 0 || T > kMaxTokens) return FFF_ERR_RANGE;
+    if (T > 0 && !leaf_idx) return FFF_ERR_NULL;
+    g_last_error.clear();
+    Workspace ws;
+    Layout lay;
+    int rc = get_workspace(T, depth, &ws, &lay);
+    if (rc != FFF_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if ((e = launch_zero(ws.chunk_cnt, round_up(ws.n_chunks * ((int64_t)1 << depth), 4), s)) != hipSuccess)
+        return set_device_error(e, "zero kernel launch");
+    if ((e = launch_bucket(leaf_idx, T, depth, ws, count, offset, perm, s)) != hipSuccess)
+        return set_device_error(e, "bucket kernel launch");
+    return FFF_OK;
+}
+
+int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1, const void* leaf_w2,
+                     const void* leaf_b2, const int32_t* leaf_idx, int depth, int leaf_width, int act,
+                     void* out, void* stream, int64_t T, int64_t D, int64_t O, int dtype) {
+    int rc = check_common(depth, T, D, dtype);
+    if (rc == FFF_OK) rc = check_leaf(depth, leaf_width, act, T, D, O);
+    if (rc != FFF_OK) return rc;
+    if (T == 0) return FFF_OK;
+    if (!x || !leaf_w1 || !leaf_b1 || !leaf_w2 || !leaf_b2 || !out || !leaf_idx) return FFF_ERR_NULL;
+    const int64_t es = dtype == FFF_BF16 ? 2 : 4;
+    if (overlaps(x, T * D * es, out, T * O * es)) return FFF_ERR_ALIAS;
+    Problem p{x, nullptr, nullptr, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, nullptr,
+              T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
+    g_last_error.clear();
+    Workspace ws;
+    Layout lay;
+    if ((rc = get_workspace(T, depth, &ws, &lay)) != FFF_OK) return rc;
+    return run_leaf_stage(p, leaf_idx, ws, (hipStream_t)stream);
+}
+
+size_t fff_workspace_bytes(int64_t T, int depth) {
+    if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH) return 0;
+    return (size_t)layout_for(T, depth).total * sizeof(int32_t);
+}
+
+int fff_reserve_workspace(int64_t T, int depth) {
+    if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH) return FFF_ERR_RANGE;
+    g_last_error.clear();
+    Workspace ws;
+    Layout lay;
+    return get_workspace(T, depth, &ws, &lay);
+}
+
+int fff_release_workspace(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    int cur = 0;
+    if (hipGetDevice(&cur) != hipSuccess) return FFF_ERR_DEVICE;
+    int rc = FFF_OK;
+    for (int d = 0; d < kMaxDevices; ++d) {
+        if (!g_ws[d].base) continue;
+        if (hipSetDevice(d) != hipSuccess || hipFree(g_ws[d].base) != hipSuccess) rc = FFF_ERR_DEVICE;
+        g_ws[d].base = nullptr;
+        g_ws[d].bytes = 0;
+    }
+    (void)hipSetDevice(cur);
+    return rc;
+}
+
+static int64_t* option_slot(const char* name) {
+    if (!name) return nullptr;
+    if (!std::strcmp(name, "leaf_path")) return &g_opt.leaf_path;
+    if (!std::strcmp(name, "gemm_min_rows")) return &g_opt.gemm_min_rows;
+    if (!std::strcmp(name, "fused_max_T")) return &g_opt.fused_max_T;
+    if (!std::strcmp(name, "bucketing")) return &g_opt.bucketing;
+    if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
+    return nullptr;
+}
+
+int fff_set_option(const char* name, int64_t value) {
+    int64_t* s = option_slot(name);
+    if (!s || value < 0) return FFF_ERR_UNSUPPORTED;
+    *s = value;
+    return FFF_OK;
+}
+
+int fff_get_option(const char* name, int64_t* value) {
+    int64_t* s = option_slot(name);
+    if (!s) return FFF_ERR_UNSUPPORTED;
+    if (!value) return FFF_ERR_NULL;
+    *value = *s;
+    return FFF_OK;
+}
+
+int fff_stage_times(double* ms, int64_t* calls) {
+    if (!ms || !calls) return FFF_ERR_NULL;
+    std::vector<hipEvent_t> ev;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        ev.swap(g_stage_events);
+    }
+    ms[0] = ms[1] = ms[2] = 0.0;
+    *calls = 0;
+    int rc = FFF_OK;
+    for (size_t i = 0; i + 3 < ev.size(); i += 4) {
+        if (hipEventSynchronize(ev[i + 3]) != hipSuccess) { rc = FFF_ERR_DEVICE; break; }
+        float d[3];
+        bool ok = true;
+        for (int k = 0; k < 3; ++k) ok = ok && hipEventElapsedTime(&d[k], ev[i + k], ev[i + k + 1]) == hipSuccess;
+        if (!ok) { rc = FFF_ERR_DEVICE; break; }
+        for (int k = 0; k < 3; ++k) ms[k] += d[k];
+        *calls += 1;
+    }
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    return rc;
+}
+
+const char* fff_status_string(int status) {
+    switch (status) {
+        case FFF_OK: return "ok";
+        case FFF_ERR_NULL: return "a required pointer is NULL";
+        case FFF_ERR_SHAPE: return "sizes are inconsistent or out of the supported range";
+        case FFF_ERR_DTYPE: return "unknown dtype";
+        case FFF_ERR_RANGE: return "depth, leaf_width or T out of range";
+        case FFF_ERR_UNSUPPORTED: return "unknown activation or option";
+        case FFF_ERR_WORKSPACE: return "workspace allocation failed";
+        case FFF_ERR_DEVICE: return "a HIP call failed";
+        case FFF_ERR_ALIAS: return "out overlaps x";
+        default: return "unknown status";
+    }
+}
+
+const char* fff_last_device_error(void) { return g_last_error.c_str(); }
+
+int fff_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,203 @@
+// K2 -- per-leaf token lists: histogram, prefix scan, stable scatter.
+//
+// Not in the paper (its implementation indexes weights per token); the lists
+// only let the tokens of one leaf share a single read of that leaf's weights.
+// Integer work throughout, and the result does not depend on scheduling:
+//
+//   rank    tokens are cut into chunks of 256 consecutive ids.  A block ranks
+//           each token among the same-leaf tokens that precede it in its chunk
+//           and stores the chunk's per-leaf totals in M[leaf][chunk].
+//   scan    one wave per leaf turns M[leaf][*] into an exclusive prefix along
+//           the chunks and emits count[leaf]; the block that finishes last
+//           scans count[] into offset[] (and the per-leaf tile offsets).
+//   scatter perm[offset[leaf] + M[leaf][chunk] + rank] = token -- ascending
+//           token order inside a leaf by construction, no atomics on the
+//           positions.
+//
+// M must be zero on entry (launch_zero) because a chunk touches only the
+// leaves it contains.
+#include "fff_device.h"
+#include "fff_internal.h"
+
+namespace fff {
+
+__device__ __forceinline__ int32_t load_l2(const int32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(int4* __restrict__ p, int64_t n4) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256)
+        p[i] = make_int4(0, 0, 0, 0);
+}
+
+hipError_t launch_zero(int32_t* p, int64_t n, hipStream_t s) {
+    // n is a multiple of 4 and p 16-byte aligned by construction of the workspace
+    const int64_t n4 = n / 4;
+    if (n4 == 0) return hipSuccess;
+    int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    zero_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((int4*)p, n4);
+    return hipGetLastError();
+}
+
+// One block per chunk of `rounds` * 256 tokens; M row stride = n_chunks.
+__global__ __launch_bounds__(256) void bucket_rank_kernel(const int32_t* __restrict__ leaf_idx, int64_t T,
+                                                          int rounds, int64_t n_chunks,
+                                                          int32_t* __restrict__ rank,
+                                                          int32_t* __restrict__ M) {
+    __shared__ int32_t s_leaf[kChunkTokens];
+    const int tid = threadIdx.x;
+    const int64_t chunk = blockIdx.x;
+    for (int r = 0; r < rounds; ++r) {
+        const int64_t t = (chunk * rounds + r) * kChunkTokens + tid;
+        const int32_t leaf = t < T ? leaf_idx[t] : -1;
+        s_leaf[tid] = leaf;
+        __syncthreads();
+        int before = 0, after = 0;
+        const int4* s4 = (const int4*)s_leaf;
+#pragma unroll 4
+        for (int j4 = 0; j4 < kChunkTokens / 4; ++j4) {
+            const int4 v = s4[j4];     // same address in every lane: a broadcast read
+            const int j = j4 * 4;
+            before += (v.x == leaf && j + 0 < tid) + (v.y == leaf && j + 1 < tid) +
+                      (v.z == leaf && j + 2 < tid) + (v.w == leaf && j + 3 < tid);
+            after += (v.x == leaf && j + 0 > tid) + (v.y == leaf && j + 1 > tid) +
+                     (v.z == leaf && j + 2 > tid) + (v.w == leaf && j + 3 > tid);
+        }
+        int32_t* cell = M + (int64_t)(leaf >= 0 ? leaf : 0) * n_chunks + chunk;
+        int32_t base = 0;
+        if (leaf >= 0) {
+            // totals of earlier rounds of this chunk (written by this block, read back through L2)
+            if (r > 0) base = load_l2(cell);
+            rank[t] = base + before;
+        }
+        __syncthreads();               // every reader of the cell and of s_leaf is done
+        if (leaf >= 0 && after == 0)
+            __hip_atomic_store(cell, base + before + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (rounds > 1) {
+            __threadfence();
+            __syncthreads();
+        }
+    }
+}
+
+__device__ __forceinline__ int32_t wave_incl_scan(int32_t v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int32_t o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive scan of count[0..n) into offset[0..n], and of the per-leaf tile
+// counts into tile_off[0..n]; run by one block of 1024 threads.
+__device__ void block_scan_counts(const int32_t* __restrict__ count, int64_t n, int tile_rows,
+                                  int32_t* __restrict__ offset, int32_t* __restrict__ tile_off,
+                                  int32_t* __restrict__ ctrl) {
+    __shared__ int32_t s_tot[2][16];
+    __shared__ int32_t s_carry[2];
+    const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+    if (tid < 2) s_carry[tid] = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < n; base += 1024) {
+        const int64_t j = base + tid;
+        const int32_t c = j < n ? load_l2(count + j) : 0;
+        const int32_t nt = (c + tile_rows - 1) / tile_rows;
+        const int32_t ic = wave_incl_scan(c, lane);
+        const int32_t it = wave_incl_scan(nt, lane);
+        if (lane == kWave - 1) { s_tot[0][wv] = ic; s_tot[1][wv] = it; }
+        __syncthreads();
+        int32_t pc = s_carry[0], pt = s_carry[1];
+        for (int w = 0; w < wv; ++w) { pc += s_tot[0][w]; pt += s_tot[1][w]; }
+        if (j < n) {
+            if (offset) offset[j] = pc + ic - c;
+            if (tile_off) tile_off[j] = pt + it - nt;
+        }
+        __syncthreads();
+        if (tid == 1023) { s_carry[0] = pc + ic; s_carry[1] = pt + it; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (offset) offset[n] = s_carry[0];
+        if (tile_off) tile_off[n] = s_carry[1];
+        ctrl[1] = s_carry[1];          // number of tiles
+    }
+}
+
+// 16 waves per block, one leaf per wave: M[leaf][*] -> exclusive prefix along chunks.
+__global__ __launch_bounds__(1024) void bucket_scan_kernel(int32_t* __restrict__ M, int64_t n_leaves,
+                                                           int64_t n_chunks, int tile_rows,
+                                                           int32_t* __restrict__ count,
+                                                           int32_t* __restrict__ offset,
+                                                           int32_t* __restrict__ tile_off,
+                                                           int32_t* __restrict__ ctrl) {
+    __shared__ int s_last;
+    const int lane = threadIdx.x % kWave;
+    const int64_t leaf = (int64_t)blockIdx.x * 16 + threadIdx.x / kWave;
+    if (leaf < n_leaves) {
+        int32_t* row = M + leaf * n_chunks;
+        int32_t carry = 0;
+        for (int64_t c0 = 0; c0 < n_chunks; c0 += kWave) {
+            const int64_t c = c0 + lane;
+            const int32_t v = c < n_chunks ? row[c] : 0;
+            const int32_t inc = wave_incl_scan(v, lane);
+            if (c < n_chunks) row[c] = carry + inc - v;
+            carry += __shfl(inc, kWave - 1, kWave);
+        }
+        if (lane == 0) __hip_atomic_store(count + leaf, carry, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // the block that arrives last sees every count and scans them
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int ticket = atomicAdd(ctrl, 1);
+        s_last = ticket == (int)gridDim.x - 1;
+    }
+    __syncthreads();
+    if (s_last) {
+        __threadfence();
+        block_scan_counts(count, n_leaves, tile_rows, offset, tile_off, ctrl);
+        if (threadIdx.x == 0) ctrl[0] = 0;   // ready for the next call
+    }
+}
+
+__global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __restrict__ leaf_idx,
+                                                             const int32_t* __restrict__ rank, int64_t T,
+                                                             int rounds, int64_t n_chunks,
+                                                             const int32_t* __restrict__ M,
+                                                             const int32_t* __restrict__ offset,
+                                                             int32_t* __restrict__ perm) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= T) return;
+    const int64_t leaf = leaf_idx[t];
+    const int64_t chunk = t / ((int64_t)kChunkTokens * rounds);
+    const int32_t pos = offset[leaf] + M[leaf * n_chunks + chunk] + rank[t];
+    perm[pos] = (int32_t)t;
+}
+
+hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,
+                         int32_t* count, int32_t* offset, int32_t* perm, hipStream_t s) {
+    const int64_t NL = (int64_t)1 << depth;
+    const int64_t per_round = (T + kChunkTokens - 1) / kChunkTokens;
+    const int rounds = (int)((per_round + ws.n_chunks - 1) / ws.n_chunks);
+    hipError_t e;
+    if (T > 0) {
+        const int64_t blocks = (per_round + rounds - 1) / rounds;
+        bucket_rank_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(leaf_idx, T, rounds, ws.n_chunks,
+                                                                       ws.rank, ws.chunk_cnt);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    bucket_scan_kernel<<<dim3((unsigned)((NL + 15) / 16)), dim3(1024), 0, s>>>(
+        ws.chunk_cnt, NL, ws.n_chunks, kTileRows, count ? count : ws.count, offset ? offset : ws.offset,
+        ws.tile_off, ws.ctrl);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (T > 0 && perm) {
+        bucket_scatter_kernel<<<dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s>>>(
+            leaf_idx, ws.rank, T, rounds, ws.n_chunks, ws.chunk_cnt, offset ? offset : ws.offset, perm);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace fff

@@ -1,0 +1,100 @@
+// Device-side helpers shared by the FFF kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fff {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// Two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    __bf16 b = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, b);
+}
+
+// acc + a.lo*b.lo + a.hi*b.hi on packed bf16 pairs, fp32 accumulate.
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                           __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
+// 16 bytes of a row: 4 floats or 8 bf16.
+template <bool BF16> struct Elem;
+template <> struct Elem<false> {
+    typedef float type;
+    static constexpr int kPerVec = 4;
+    static __device__ __forceinline__ float dot(const uint4& a, const uint4& b, float acc) {
+        acc = fmaf(__uint_as_float(a.x), __uint_as_float(b.x), acc);
+        acc = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), acc);
+        acc = fmaf(__uint_as_float(a.z), __uint_as_float(b.z), acc);
+        acc = fmaf(__uint_as_float(a.w), __uint_as_float(b.w), acc);
+        return acc;
+    }
+    static __device__ __forceinline__ float load(const void* p, int64_t i) { return ((const float*)p)[i]; }
+    static __device__ __forceinline__ void store(void* p, int64_t i, float v) { ((float*)p)[i] = v; }
+};
+template <> struct Elem<true> {
+    typedef uint16_t type;
+    static constexpr int kPerVec = 8;
+    static __device__ __forceinline__ float dot(const uint4& a, const uint4& b, float acc) {
+        acc = dot2_bf16(a.x, b.x, acc);
+        acc = dot2_bf16(a.y, b.y, acc);
+        acc = dot2_bf16(a.z, b.z, acc);
+        acc = dot2_bf16(a.w, b.w, acc);
+        return acc;
+    }
+    static __device__ __forceinline__ float load(const void* p, int64_t i) { return bf16_to_f32(((const uint16_t*)p)[i]); }
+    static __device__ __forceinline__ void store(void* p, int64_t i, float v) { ((uint16_t*)p)[i] = f32_to_bf16(v); }
+};
+
+// v from the lane `n` places further along this lane's 16-lane row (wrapping).
+template <int N> __device__ __forceinline__ float row_rotate(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
+}
+
+// Sum over the LANES consecutive lanes this lane belongs to (LANES = 16 or 64);
+// every lane of the group ends with the same bits: each step adds the same two
+// partial sums in both lanes of a pair, and fp32 addition commutes.
+template <int LANES> __device__ __forceinline__ float group_sum(float v) {
+    v += row_rotate<8>(v);
+    v += row_rotate<4>(v);
+    v += row_rotate<2>(v);
+    v += row_rotate<1>(v);
+    if (LANES == 64) {
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
+    }
+    return v;
+}
+
+__device__ __forceinline__ float activate(float v, int act) {
+    if (act == 0) return fmaxf(v, 0.0f);
+    return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+}
+
+// Streaming 16-byte load (tokens are read once; keep them out of the way of the weights).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
+    const u32x4_t u = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(u, (u32x4_t*)p);
+}
+
+}  // namespace fff

@@ -1,0 +1,62 @@
+// Host-side declarations shared by the translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fff {
+
+// One FFF call, as validated by the C ABI.
+struct Problem {
+    const void* x;
+    const void* node_w;
+    const void* node_b;
+    const void* leaf_w1;
+    const void* leaf_b1;
+    const void* leaf_w2;
+    const void* leaf_b2;
+    void* out;
+    int32_t* leaf_idx;
+    int64_t T, D, O;
+    int depth, L, act;
+    bool bf16;
+};
+
+// Per-device scratch, carved out of one allocation (all int32 words).
+struct Workspace {
+    int32_t* leaf_idx;   // [T]      when the caller passes none
+    int32_t* rank;       // [T]      rank of a token among same-leaf tokens of its chunk
+    int32_t* perm;       // [T]      token ids grouped by leaf
+    int32_t* count;      // [NL]
+    int32_t* offset;     // [NL + 1]
+    int32_t* tile_off;   // [NL + 1] exclusive prefix of per-leaf tile counts
+    int32_t* chunk_cnt;  // [C, NL]  per-chunk histograms, then per-chunk bases
+    int32_t* tiles;      // [max_tiles, 2] (leaf, first slot) per tile
+    int32_t* ctrl;       // [16]     ticket counters and totals
+    int64_t n_chunks;
+    int64_t max_tiles;
+};
+
+constexpr int kChunkTokens = 256;   // tokens per bucketing chunk
+constexpr int kTileRows = 16;       // rows of one MFMA tile
+
+bool vec_ok(const void* p, int64_t row_elems, bool bf16);
+
+// K1: tree descent.  leaf_idx[t] for all t.
+hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+
+// K2: bucketing.  Needs ws.chunk_cnt zeroed on entry; leaves it dirty.
+hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,
+                         int32_t* count, int32_t* offset, int32_t* perm, hipStream_t s);
+hipError_t launch_zero(int32_t* p, int64_t n, hipStream_t s);
+
+// K3 + K4: leaf networks and output rows.
+//   order == nullptr: slot i is token i.  Otherwise slot i is token order[i].
+hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order,
+                              hipStream_t s);
+hipError_t launch_leaf_tiles(const Problem& p, const Workspace& ws, int gemm_min_rows, int force_path,
+                             hipStream_t s);
+
+// Whole forward pass in one launch, one token per lane group (any shape).
+hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+
+}  // namespace fff

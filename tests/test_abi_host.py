@@ -1,0 +1,90 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol include/fff.h declares, and rejects bad arguments before touching
+the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2308_14711_amd as F
+    return F.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "fff.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(fff_[a-z_]+)\s*\(", header))
+    assert {"fff_forward_hard", "fff_descend", "fff_bucket", "fff_leaf_forward", "fff_workspace_bytes",
+            "fff_status_string"} <= names
+    for n in sorted(names):
+        assert hasattr(L, n), "library does not export %s" % n
+
+
+def test_status_strings(L):
+    import paper_2308_14711_amd as F
+    seen = {F.fff_status_string(i) for i in range(9)}
+    assert len(seen) == 9 and "ok" in seen
+    assert F.fff_status_string(99) == "unknown status"
+    assert F.fff_version() >= 100
+
+
+def test_workspace_size_is_monotone(L):
+    import paper_2308_14711_amd as F
+    a = F.fff_workspace_bytes(1000, 4)
+    b = F.fff_workspace_bytes(100000, 4)
+    c = F.fff_workspace_bytes(100000, 12)
+    assert 0 < a < b < c
+    assert F.fff_workspace_bytes(-1, 3) == 0 and F.fff_workspace_bytes(10, 25) == 0
+    assert F.fff_workspace_bytes(1 << 20, 24) < (1 << 30)
+
+
+def _call(lib_, **kw):
+    P = ctypes.c_void_p
+    a = dict(x=P(256), node_w=P(512), node_b=P(768), w1=P(1024), b1=P(1280), w2=P(1536), b2=P(1792),
+             depth=3, L=4, act=0, out=P(1 << 40), idx=None, stream=None, T=8, D=64, O=16, dtype=0)
+    a.update(kw)
+    return lib_.fff_forward_hard(a["x"], a["node_w"], a["node_b"], a["w1"], a["b1"], a["w2"], a["b2"],
+                              a["depth"], a["L"], a["act"], a["out"], a["idx"], a["stream"],
+                              a["T"], a["D"], a["O"], a["dtype"])
+
+
+def test_bad_arguments_are_rejected_on_the_host(L):
+    """None of these reaches a HIP call (there is no GPU in this test)."""
+    OK, NULL, SHAPE, DTYPE, RANGE, UNSUP, ALIAS = 0, 1, 2, 3, 4, 5, 8
+    assert _call(L, T=0) == OK                       # empty batch: nothing to do
+    assert _call(L, x=None) == NULL
+    assert _call(L, out=None) == NULL
+    assert _call(L, node_w=None) == NULL             # depth > 0 needs nodes
+    assert _call(L, b2=None) == NULL
+    assert _call(L, depth=-1) == RANGE
+    assert _call(L, depth=25) == RANGE
+    assert _call(L, L=0) == RANGE
+    assert _call(L, L=5000) == RANGE
+    assert _call(L, T=-3) == RANGE
+    assert _call(L, D=0) == SHAPE
+    assert _call(L, O=0) == SHAPE
+    assert _call(L, T=1 << 30, D=1 << 20) == SHAPE
+    assert _call(L, dtype=2) == DTYPE
+    assert _call(L, act=7) == UNSUP
+    assert _call(L, out=ctypes.c_void_p(256 + 64)) == ALIAS
+    assert L.fff_descend(None, None, None, 2, None, None, 4, 8, 0) == NULL
+    assert L.fff_descend(None, None, None, 2, None, None, 0, 8, 0) == OK
+    assert L.fff_bucket(None, 5, 3, None, None, None, None) == NULL
+    assert L.fff_bucket(None, 5, 30, None, None, None, None) == RANGE
+    assert L.fff_leaf_forward(None, None, None, None, None, None, 2, 1, 0, None, None, 3, 8, 8, 1) == NULL
+
+
+def test_options(L):
+    import paper_2308_14711_amd as F
+    assert F.fff_get_option("bucketing") == 1
+    F.fff_set_option("bucketing", 0)
+    assert F.fff_get_option("bucketing") == 0
+    F.fff_set_option("bucketing", 1)
+    with pytest.raises(F.FffError):
+        F.fff_set_option("no_such_option", 1)

@@ -1,0 +1,195 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs, element by element."""
+import numpy as np
+import pytest
+
+import fff_workloads as W
+import oracle
+from fff_testlib import check_against_oracle, oracle_inputs, out_to_f64, run_forward, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _log(name, stats):
+    print("\n[parity] %s: %s" % (name, stats), flush=True)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C2c", "C3", "C4"])
+def test_named_workloads(name):
+    print("\n[case] workload %s seed 0" % name, flush=True)
+    w = W.config(name)
+    out, idx = run_forward(w)
+    _log(name, check_against_oracle(w, out, idx))
+
+
+SMALL = [
+    # name,               T,   D,   O, depth, L, act,        dtype
+    ("d0_f32",            70,  64,  12, 0, 3, W.ACT_RELU, W.DTYPE_F32),
+    ("d1_bf16",           65,  64,  16, 1, 2, W.ACT_GELU, W.DTYPE_BF16),
+    ("one_token",         1,   128, 8,  4, 4, W.ACT_GELU, W.DTYPE_F32),
+    ("ragged_63",         63,  256, 24, 5, 8, W.ACT_GELU, W.DTYPE_BF16),
+    ("ragged_257",        257, 96,  40, 3, 5, W.ACT_RELU, W.DTYPE_BF16),
+    ("odd_dims_generic",  130, 50,  7,  4, 3, W.ACT_GELU, W.DTYPE_F32),
+    ("odd_dims_bf16",     99,  77,  9,  3, 2, W.ACT_RELU, W.DTYPE_BF16),
+    ("wide_leaf_64",      40,  64,  32, 2, 64, W.ACT_GELU, W.DTYPE_F32),
+    ("wide_leaf_65",      40,  64,  32, 2, 65, W.ACT_GELU, W.DTYPE_F32),
+    ("deep_sparse",       300, 128, 64, 12, 2, W.ACT_GELU, W.DTYPE_BF16),
+    ("big_rows_f32",      50,  2048, 16, 3, 2, W.ACT_RELU, W.DTYPE_F32),
+    ("big_rows_bf16",     50,  8192, 64, 2, 1, W.ACT_GELU, W.DTYPE_BF16),
+    ("huge_rows_generic", 9,   8200, 8,  2, 1, W.ACT_RELU, W.DTYPE_BF16),
+    ("vit_like_small",    777, 768, 768, 4, 8, W.ACT_GELU, W.DTYPE_BF16),
+    ("bert_like_small",   1000, 768, 768, 6, 1, W.ACT_GELU, W.DTYPE_BF16),
+    ("skew_like_small",   515, 4096, 4096, 7, 4, W.ACT_GELU, W.DTYPE_BF16),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_small_and_edge_shapes(case):
+    name, T, D, O, depth, L, act, dtype = case
+    print("\n[case] %s T=%d D=%d O=%d depth=%d L=%d dtype=%d seed 5" % (name, T, D, O, depth, L, dtype), flush=True)
+    w = W.make_layer(name, T, D, O, depth, L, act, dtype, seed=5,
+                     node_b="zipf" if name.startswith("skew") else "uniform")
+    out, idx = run_forward(w)
+    _log(name, check_against_oracle(w, out, idx))
+
+
+def test_empty_batch_is_a_noop():
+    import torch
+    import paper_2308_14711_amd as F
+    w = W.make_layer("e", 4, 64, 8, 2, 2, W.ACT_RELU, W.DTYPE_F32, seed=1)
+    dev = to_device(w)
+    x0 = dev["x"][:0].contiguous()
+    out = torch.empty((0, 8), device="cuda")
+    F.fff_forward_hard(x0, dev["node_w"], dev["node_b"], dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"],
+                       dev["leaf_b2"], 2, 2, W.ACT_RELU, out, None)
+    torch.cuda.synchronize()
+
+
+def test_all_tokens_in_one_leaf():
+    """Zero node weights: every logit is +0, ties go right, every token lands in the last leaf."""
+    print("\n[case] one_leaf", flush=True)
+    w = W.make_layer("one_leaf", 500, 128, 32, 5, 4, W.ACT_GELU, W.DTYPE_BF16, seed=2)
+    for k in ("node_w", "node_b"):
+        w.f32[k][...] = 0
+        w.bits[k][...] = 0
+    out, idx = run_forward(w)
+    assert (idx.cpu().numpy() == 31).all()
+    stats = check_against_oracle(w, out, idx)
+    assert stats["idx_mismatch"] == 0
+
+
+def test_every_leaf_gets_exactly_one_token():
+    """Axis-aligned nodes (level m splits on axis m at 0) and tokens whose signs spell their index."""
+    print("\n[case] one_token_per_leaf", flush=True)
+    depth, D = 6, 64
+    T = 1 << depth
+    w = W.make_layer("perleaf", T, D, 16, depth, 2, W.ACT_RELU, W.DTYPE_F32, seed=3, node_b="zero")
+    w.f32["node_w"][...] = 0
+    for m in range(depth):
+        w.f32["node_w"][(1 << m) - 1:(1 << (m + 1)) - 1, m] = 1.0
+    bits = (np.arange(T)[:, None] >> (depth - 1 - np.arange(depth))[None, :]) & 1
+    w.f32["x"][:, :depth] = np.where(bits == 1, 0.5, -0.5) * (1 + np.arange(depth))
+    rng = np.random.default_rng(0)
+    p = rng.permutation(T)
+    w.f32["x"] = np.ascontiguousarray(w.f32["x"][p])
+    out, idx = run_forward(w)
+    assert np.array_equal(idx.cpu().numpy(), p.astype(np.int32))
+    _log("perleaf", check_against_oracle(w, out, idx))
+
+
+def test_leaf_idx_is_optional():
+    w = W.make_layer("noidx", 300, 128, 48, 4, 4, W.ACT_GELU, W.DTYPE_BF16, seed=4)
+    out, _ = run_forward(w, want_idx=False)
+    _log("noidx", check_against_oracle(w, out, None))
+
+
+def test_reruns_are_bit_identical_and_tokens_permute():
+    import torch
+    w = W.make_layer("det", 3000, 256, 128, 6, 4, W.ACT_GELU, W.DTYPE_BF16, seed=6)
+    dev = to_device(w)
+    o1, i1 = run_forward(w, dev)
+    o2, i2 = run_forward(w, dev)
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(i1, i2)
+    p = torch.randperm(w.T, device="cuda", generator=torch.Generator(device="cuda").manual_seed(0))
+    dev2 = dict(dev)
+    dev2["x"] = dev["x"][p].contiguous()
+    o3, i3 = run_forward(w, dev2)
+    assert torch.equal(o3.view(torch.int16), o1[p].view(torch.int16)) and torch.equal(i3, i1[p])
+
+
+def test_runs_on_a_side_stream():
+    import torch
+    w = W.make_layer("stream", 600, 128, 64, 5, 2, W.ACT_RELU, W.DTYPE_F32, seed=7)
+    dev = to_device(w)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        out, idx = run_forward(w, dev, stream=s)
+    _log("stream", check_against_oracle(w, out, idx))
+
+
+# ---- stages on their own ------------------------------------------------------
+
+@pytest.mark.parametrize("depth,T,kind", [(0, 10, "u"), (3, 1, "u"), (3, 1000, "u"), (8, 5000, "zipf"),
+                                          (11, 65536, "u"), (15, 16384, "zipf"), (20, 10000, "u"),
+                                          (6, 4096, "one")])
+def test_bucket_stage_is_bit_exact(depth, T, kind):
+    import torch
+    import paper_2308_14711_amd as F
+    print("\n[case] bucket depth=%d T=%d %s" % (depth, T, kind), flush=True)
+    rng = np.random.default_rng(depth * 1000 + T)
+    NL = 1 << depth
+    if kind == "u":
+        li = rng.integers(0, NL, T).astype(np.int32)
+    elif kind == "zipf":
+        li = (rng.zipf(1.1, T) % NL).astype(np.int32)
+    else:
+        li = np.full(T, NL - 1, np.int32)
+    count, offset, perm = oracle.bucket(li, depth)
+    d_li = torch.from_numpy(li).cuda()
+    d_count = torch.full((NL,), -1, dtype=torch.int32, device="cuda")
+    d_offset = torch.full((NL + 1,), -1, dtype=torch.int32, device="cuda")
+    d_perm = torch.full((T,), -1, dtype=torch.int32, device="cuda")
+    for _ in range(2):      # twice: the workspace must come back clean
+        F.fff_bucket(d_li, depth, d_count, d_offset, d_perm)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_count.cpu().numpy(), count)
+        assert np.array_equal(d_offset.cpu().numpy(), offset)
+        assert np.array_equal(d_perm.cpu().numpy(), perm)
+
+
+def test_descend_and_leaf_stages():
+    import torch
+    import paper_2308_14711_amd as F
+    w = W.make_layer("stages", 900, 256, 64, 7, 4, W.ACT_GELU, W.DTYPE_BF16, seed=8)
+    dev = to_device(w)
+    ins = oracle_inputs(w)
+    _, ref_idx, margin = oracle.forward_hard(*ins, w.depth, w.leaf_width, w.act, want_out=False)
+    idx = torch.empty((w.T,), dtype=torch.int32, device="cuda")
+    F.fff_descend(dev["x"], dev["node_w"], dev["node_b"], w.depth, idx)
+    torch.cuda.synchronize()
+    gi = idx.cpu().numpy()
+    assert np.array_equal(gi[margin >= 1e-4], ref_idx[margin >= 1e-4])
+    # the leaf stage at leaves that have nothing to do with the tree
+    forced = ((np.arange(w.T) * 37) % w.n_leaves).astype(np.int32)
+    out = torch.empty((w.T, w.O), dtype=torch.bfloat16, device="cuda")
+    F.fff_leaf_forward(dev["x"], dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"], dev["leaf_b2"],
+                       torch.from_numpy(forced).cuda(), w.depth, w.leaf_width, w.act, out)
+    torch.cuda.synchronize()
+    ref = oracle.leaf_forward(ins[0], ins[3], ins[4], ins[5], ins[6], forced, w.depth, w.leaf_width, w.act)
+    got = out_to_f64(out)
+    err = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+    assert err.max() <= 2e-2
+
+
+@pytest.mark.parametrize("opt", [("bucketing", 0), ("fused_max_T", 1 << 30)])
+def test_alternative_paths_agree_with_the_oracle(opt):
+    import paper_2308_14711_amd as F
+    w = W.make_layer("paths", 2000, 256, 128, 6, 4, W.ACT_GELU, W.DTYPE_BF16, seed=9)
+    old = F.fff_get_option(opt[0])
+    F.fff_set_option(*opt)
+    try:
+        out, idx = run_forward(w)
+    finally:
+        F.fff_set_option(opt[0], old)
+    _log("paths %s" % (opt,), check_against_oracle(w, out, idx))
