@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C4", help="workload: C1 C2 C2c C3 C4 C5")
     ap.add_argument("--sets", type=int, default=0, help="distinct x/out buffer sets to rotate (0 = auto)")
+    ap.add_argument("--opt", action="append", default=[], help="library option name=value (repeatable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
@@ -75,6 +76,9 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     F.lib()   # fail loudly here if the HIP library is missing
+    for kv in args.opt:
+        k, v = kv.split("=")
+        F.fff_set_option(k, int(v))
 
     w = W.config(args.config, keep_f32=False)
     tdt = torch.bfloat16 if w.dtype == W.DTYPE_BF16 else torch.float32
@@ -118,10 +122,15 @@ def main():
     # routing of the oracle: which nodes and leaves are touched (host side, for the byte model)
     import oracle
     ins = [np.ascontiguousarray(w.device_array(k)) for k in W.TENSORS]
-    t2 = time.perf_counter()
     ref_out, ref_idx, margin = oracle.forward_hard(*ins, w.depth, w.leaf_width, w.act,
                                                    want_out=not args.no_cpu_baseline)
-    t3 = time.perf_counter()
+    cpu_passes, cpu_s = 0, 0.0
+    if not args.no_cpu_baseline:       # the oracle as it stands, whole batch, repeated for about 3 s
+        t2 = time.perf_counter()
+        while cpu_passes < 1 or (time.perf_counter() - t2 < 3.0 and cpu_passes < 50):
+            oracle.forward_hard(*ins, w.depth, w.leaf_width, w.act)
+            cpu_passes += 1
+        cpu_s = time.perf_counter() - t2
     alg = algorithmic_bytes(w, ref_idx)
 
     # per-stage durations: HIP events recorded by the library on the call's stream
@@ -159,9 +168,10 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = {"value": round(w.T / (t3 - t2), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": "all %d tokens of %s, one pass, fp64, OpenMP over tokens" % (w.T, w.name),
-               "seconds": round(t3 - t2, 3)}
+        cpu = {"value": round(w.T * cpu_passes / cpu_s, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": "all %d tokens of %s, %d passes, fp64, OpenMP over tokens" % (w.T, w.name, cpu_passes),
+               "seconds": round(cpu_s, 3)}
 
     dense = None
     if not args.no_dense and (1 << w.depth) * w.leaf_width <= 8192:
@@ -195,7 +205,7 @@ def main():
         "dtype": "bf16" if w.dtype == W.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (w.name, w.note), "T": w.T, "D": w.D, "O": w.O, "depth": w.depth,
                    "leaf_width": w.leaf_width, "act": "gelu" if w.act else "relu", "buffer_sets": nsets,
-                   "seed": 0},
+                   "seed": 0, "options": args.opt},
         "roofline": roofline,
         "path": {"alg_bytes": alg["path"], "GBps": round(path_gbs, 1), "frac": round(path_gbs / HBM_PEAK_GBS, 4),
                  "u_node": alg["u_node"], "u_leaf": alg["u_leaf"]},

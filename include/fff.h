@@ -142,7 +142,10 @@ int fff_release_workspace(void);
  *                    gather path, 2 = every bucket through the MFMA tile path
  *                    (bf16 only; silently the gather path otherwise)
  *   "gemm_min_rows"  smallest bucket handed to the MFMA tile path (default 8)
- *   "fused_max_T"    T up to which one fused launch replaces the staged path (0 = never)
+ *   "path"           0 = choose by shape (default), 1 = one fused launch (walk, leaf
+ *                    network and output row per token; leaf_width <= 8), 2 = staged
+ *                    (descent, bucketing, leaf kernel), 3 = the element-wise fallback
+ *                    kernel; a path the shape does not allow falls back to one it does
  *   "bucketing"      1 (default) = the leaf kernel visits tokens grouped by leaf,
  *                    0 = in token order (no bucketing stage)
  *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages

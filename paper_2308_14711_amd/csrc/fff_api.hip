@@ -25,9 +25,9 @@ DeviceWs g_ws[kMaxDevices];
 std::mutex g_mu;
 
 struct Options {
+    int64_t path = 0;            // 0 auto, 1 fused walk, 2 staged, 3 generic one-wave-per-token
     int64_t leaf_path = 0;       // 0 auto, 1 gather only, 2 tiles only
     int64_t gemm_min_rows = 8;
-    int64_t fused_max_T = 0;
     int64_t bucketing = 1;       // 0: leaf kernel visits tokens in token order
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
 } g_opt;
@@ -166,11 +166,25 @@ bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes) {
     return a0 < b0 + (uintptr_t)bbytes && b0 < a0 + (uintptr_t)abytes;
 }
 
-// Shapes the 16-byte vector kernels take: rows of D (and the token rows of x) aligned.
-bool fast_shape(const Problem& p) {
-    const int64_t per = p.bf16 ? 8 : 4;
-    return vec_ok(p.x, p.D, p.bf16) && (p.depth == 0 || vec_ok(p.node_w, p.D, p.bf16)) &&
-           vec_ok(p.leaf_w1, p.D, p.bf16) && p.D / per <= 1024 && p.L <= 64;
+// Shapes the staged path's 16-byte vector kernels take.
+bool staged_shape_ok(const Problem& p) {
+    return walk_shape_ok(p) && vec_ok(p.leaf_w1, p.D, p.bf16) && p.L <= 64;
+}
+
+enum { kPathAuto = 0, kPathFused = 1, kPathStaged = 2, kPathGeneric = 3 };
+
+// One launch that keeps the token row in registers from the root to the output
+// row wins while a leaf is narrow (its weights are a few rows per token, like a
+// few more tree levels); wider leaves want tokens grouped so that a leaf's
+// weights are read once per group.
+int choose_path(const Problem& p) {
+    const bool fused_ok = fused_shape_ok(p), staged_ok = staged_shape_ok(p);
+    if (g_opt.path == kPathFused && fused_ok) return kPathFused;
+    if (g_opt.path == kPathStaged && staged_ok) return kPathStaged;
+    if (g_opt.path == kPathGeneric || (!fused_ok && !staged_ok)) return kPathGeneric;
+    if (!staged_ok) return kPathFused;
+    if (!fused_ok) return kPathStaged;
+    return (p.L <= 2 || p.T <= 8192) ? kPathFused : kPathStaged;
 }
 
 int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& ws, hipStream_t s,
@@ -219,9 +233,18 @@ int fff_forward_hard(const void* x, const void* node_w, const void* node_b, cons
     hipStream_t s = (hipStream_t)stream;
     g_last_error.clear();
 
-    if (!fast_shape(p) || T <= g_opt.fused_max_T) {
+    const int path = choose_path(p);
+    if (path == kPathGeneric) {
         hipError_t e = launch_fused_generic(p, leaf_idx, s);
-        return e == hipSuccess ? FFF_OK : set_device_error(e, "fused kernel launch");
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "generic kernel launch");
+    }
+    if (path == kPathFused) {
+        stage_mark(s);
+        hipError_t e = launch_walk_fused(p, leaf_idx, s);
+        stage_mark(s);
+        stage_mark(s);
+        stage_mark(s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "fused walk kernel launch");
     }
     Workspace ws;
     Layout lay;
@@ -282,7 +305,7 @@ int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1, co
     Workspace ws;
     Layout lay;
     if ((rc = get_workspace(T, depth, &ws, &lay)) != FFF_OK) return rc;
-    return run_leaf_stage(p, leaf_idx, ws, (hipStream_t)stream);
+    return run_leaf_stage(p, leaf_idx, ws, (hipStream_t)stream);   // falls back per shape inside
 }
 
 size_t fff_workspace_bytes(int64_t T, int depth) {
@@ -317,7 +340,7 @@ static int64_t* option_slot(const char* name) {
     if (!name) return nullptr;
     if (!std::strcmp(name, "leaf_path")) return &g_opt.leaf_path;
     if (!std::strcmp(name, "gemm_min_rows")) return &g_opt.gemm_min_rows;
-    if (!std::strcmp(name, "fused_max_T")) return &g_opt.fused_max_T;
+    if (!std::strcmp(name, "path")) return &g_opt.path;
     if (!std::strcmp(name, "bucketing")) return &g_opt.bucketing;
     if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
     return nullptr;

@@ -41,8 +41,12 @@ constexpr int kTileRows = 16;       // rows of one MFMA tile
 
 bool vec_ok(const void* p, int64_t row_elems, bool bf16);
 
-// K1: tree descent.  leaf_idx[t] for all t.
+// K1: tree descent.  leaf_idx[t] for all t (any shape: falls back to element loads).
 hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+// Descent + leaf network + output row in one launch; needs fused_shape_ok(p).
+hipError_t launch_walk_fused(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+bool walk_shape_ok(const Problem& p);
+bool fused_shape_ok(const Problem& p);
 
 // K2: bucketing.  Needs ws.chunk_cnt zeroed on entry; leaves it dirty.
 hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,

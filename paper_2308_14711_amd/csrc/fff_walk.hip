@@ -1,0 +1,350 @@
+// K1 (and, fused, K3 + K4 for narrow leaves) -- the root-to-leaf walk of
+// Forward_I (Algorithm 1): d node neurons per token, each a dot product plus
+// bias followed by "logit >= 0 -> child 2n+1, else 2n", then optionally the
+// leaf network of the leaf reached, written to the token's output row.
+//
+// Layout of the work
+//   - A token is owned by a group of LPT consecutive lanes (one 16-lane DPP row,
+//     or the whole wave for long rows); a group carries TPG tokens at once so
+//     that TPG independent row fetches are in flight per lane.
+//   - The token row is read once from HBM (16 bytes per lane, consecutive lanes
+//     on consecutive addresses, streaming hint) and stays in registers for all
+//     levels and for the leaf's hidden neurons.
+//   - The rows of the top `top` levels of the tree (2^top - 1 rows, the ones
+//     every token keeps hitting) are staged in LDS once per block; deeper rows,
+//     which few tokens share, are fetched from L2/HBM.
+//   - Partial dot products are reduced inside the group with DPP row rotations.
+//   - Blocks are persistent: a block strides over token tiles, so the LDS
+//     staging is paid once per block, not once per tile.
+#include "fff_device.h"
+#include "fff_internal.h"
+
+namespace fff {
+
+constexpr int kFusedMaxLeafWidth = 8;
+
+// xv . row, where row[v] is fetched by LOAD(v)
+template <bool BF16, int LPT, int NV, typename LoadRow>
+__device__ __forceinline__ float row_dot(const uint4 (&xv)[NV], int sub, int nvec, LoadRow load) {
+    uint4 wv[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int v = sub + i * LPT;
+        wv[i] = v < nvec ? load(v) : make_uint4(0, 0, 0, 0);
+    }
+    float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        if (i & 1) acc1 = Elem<BF16>::dot(xv[i], wv[i], acc1);
+        else acc0 = Elem<BF16>::dot(xv[i], wv[i], acc0);
+    }
+    return acc0 + acc1;
+}
+
+template <bool BF16> __device__ __forceinline__ void unpack_vec(const uint4& v, float* f);
+template <> __device__ __forceinline__ void unpack_vec<false>(const uint4& v, float* f) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+}
+template <> __device__ __forceinline__ void unpack_vec<true>(const uint4& v, float* f) {
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+template <bool BF16> __device__ __forceinline__ uint4 pack_vec(const float* f);
+template <> __device__ __forceinline__ uint4 pack_vec<false>(const float* f) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+}
+template <> __device__ __forceinline__ uint4 pack_vec<true>(const float* f) {
+    return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                      pack_bf16x2(f[6], f[7]));
+}
+
+struct WalkArgs {
+    const uint4* x;
+    const uint4* node_w;
+    const void* node_b;
+    const uint4* w1;
+    const void* b1;
+    const void* w2;
+    const void* b2;
+    void* out;
+    int32_t* leaf_idx;   // may be null when FUSED
+    int64_t T, O;
+    int depth, top, nvec, L, act, out_vec;
+};
+
+// FUSED = false: writes leaf_idx only.  FUSED = true: also the leaf network (L <= 8).
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED>
+__global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
+    extern __shared__ uint4 lds[];                 // [(2^top - 1) * nvec] rows, then (2^top - 1) biases
+    constexpr int kGroups = kWalkBlock / LPT;
+    constexpr int VE = Elem<BF16>::kPerVec;
+    const int nvec = a.nvec;
+    const int n_top = (1 << a.top) - 1;
+    float* lds_bias = (float*)(lds + (int64_t)n_top * nvec);
+
+    for (int i = threadIdx.x; i < n_top * nvec; i += kWalkBlock) lds[i] = a.node_w[i];
+    for (int i = threadIdx.x; i < n_top; i += kWalkBlock) lds_bias[i] = Elem<BF16>::load(a.node_b, i);
+    __syncthreads();
+
+    const int sub = threadIdx.x % LPT;
+    const int g = threadIdx.x / LPT;
+    const int64_t tile = (int64_t)kGroups * TPG;
+    const int n_nodes = (1 << a.depth) - 1;
+
+    for (int64_t base = (int64_t)blockIdx.x * tile; base < a.T; base += (int64_t)gridDim.x * tile) {
+        int64_t t[TPG];
+        bool live[TPG];
+        uint4 xv[TPG][NV];
+#pragma unroll
+        for (int k = 0; k < TPG; ++k) {
+            const int64_t tt = base + (int64_t)g * TPG + k;
+            live[k] = tt < a.T;
+            t[k] = live[k] ? tt : a.T - 1;
+            const uint4* xrow = a.x + t[k] * nvec;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int v = sub + i * LPT;
+                xv[k][i] = v < nvec ? load_stream(xrow + v) : make_uint4(0, 0, 0, 0);
+            }
+        }
+        int node[TPG];
+#pragma unroll
+        for (int k = 0; k < TPG; ++k) node[k] = 0;
+
+        // levels whose rows sit in LDS
+        for (int m = 0; m < a.top; ++m) {
+            float s[TPG];
+#pragma unroll
+            for (int k = 0; k < TPG; ++k) {
+                const uint4* row = lds + (int64_t)node[k] * nvec;
+                s[k] = row_dot<BF16, LPT, NV>(xv[k], sub, nvec, [&](int v) { return row[v]; });
+            }
+#pragma unroll
+            for (int k = 0; k < TPG; ++k) {
+                const float logit = group_sum<LPT>(s[k]) + lds_bias[node[k]];
+                node[k] = 2 * node[k] + 1 + (logit >= 0.0f ? 1 : 0);
+            }
+        }
+        // deeper levels: one row fetch per token per level, TPG of them in flight
+        for (int m = a.top; m < a.depth; ++m) {
+            float s[TPG], bias[TPG];
+#pragma unroll
+            for (int k = 0; k < TPG; ++k) {
+                const uint4* row = a.node_w + (int64_t)node[k] * nvec;
+                bias[k] = Elem<BF16>::load(a.node_b, node[k]);
+                s[k] = row_dot<BF16, LPT, NV>(xv[k], sub, nvec, [&](int v) { return row[v]; });
+            }
+#pragma unroll
+            for (int k = 0; k < TPG; ++k) {
+                const float logit = group_sum<LPT>(s[k]) + bias[k];
+                node[k] = 2 * node[k] + 1 + (logit >= 0.0f ? 1 : 0);
+            }
+        }
+        int64_t leaf[TPG];
+#pragma unroll
+        for (int k = 0; k < TPG; ++k) {
+            leaf[k] = node[k] - n_nodes;
+            if (a.leaf_idx && live[k] && sub == 0) a.leaf_idx[t[k]] = (int32_t)leaf[k];
+        }
+        if (!FUSED) continue;
+
+        // hidden neurons of the leaf reached: h[r] = act(W1[leaf][r] . x + b1[leaf][r])
+        float h[TPG][kFusedMaxLeafWidth];
+#pragma unroll
+        for (int r = 0; r < kFusedMaxLeafWidth; ++r) {
+            if (r < a.L) {
+                float s[TPG], bias[TPG];
+#pragma unroll
+                for (int k = 0; k < TPG; ++k) {
+                    const uint4* row = a.w1 + (leaf[k] * a.L + r) * nvec;
+                    bias[k] = Elem<BF16>::load(a.b1, leaf[k] * a.L + r);
+                    s[k] = row_dot<BF16, LPT, NV>(xv[k], sub, nvec, [&](int v) { return row[v]; });
+                }
+#pragma unroll
+                for (int k = 0; k < TPG; ++k) h[k][r] = activate(group_sum<LPT>(s[k]) + bias[k], a.act);
+            } else {
+#pragma unroll
+                for (int k = 0; k < TPG; ++k) h[k][r] = 0.f;
+            }
+        }
+        // output row: y[o] = sum_r h[r] W2[leaf][r][o] + b2[leaf][o]
+#pragma unroll
+        for (int k = 0; k < TPG; ++k) {
+            if (!live[k]) continue;
+            if (a.out_vec) {
+                const int ovec = (int)(a.O / VE);
+                const uint4* w2v = (const uint4*)a.w2 + leaf[k] * a.L * ovec;
+                const uint4* b2v = (const uint4*)a.b2 + leaf[k] * ovec;
+                uint4* orow = (uint4*)a.out + t[k] * ovec;
+                for (int ov = sub; ov < ovec; ov += LPT) {
+                    float acc[VE], wf[VE];
+                    unpack_vec<BF16>(b2v[ov], acc);
+#pragma unroll
+                    for (int r = 0; r < kFusedMaxLeafWidth; ++r) {
+                        if (r < a.L) {
+                            unpack_vec<BF16>(w2v[(int64_t)r * ovec + ov], wf);
+#pragma unroll
+                            for (int e = 0; e < VE; ++e) acc[e] = fmaf(h[k][r], wf[e], acc[e]);
+                        }
+                    }
+                    store_stream(orow + ov, pack_vec<BF16>(acc));
+                }
+            } else {
+                for (int64_t o = sub; o < a.O; o += LPT) {
+                    float acc = Elem<BF16>::load(a.b2, leaf[k] * a.O + o);
+#pragma unroll
+                    for (int r = 0; r < kFusedMaxLeafWidth; ++r)
+                        if (r < a.L) acc = fmaf(h[k][r], Elem<BF16>::load(a.w2, (leaf[k] * a.L + r) * a.O + o), acc);
+                    Elem<BF16>::store(a.out, t[k] * a.O + o, acc);
+                }
+            }
+        }
+    }
+}
+
+// Any D, any alignment: one wave per token, element-wise loads.
+template <bool BF16>
+__global__ __launch_bounds__(256) void descend_generic_kernel(const void* __restrict__ x,
+                                                              const void* __restrict__ node_w,
+                                                              const void* __restrict__ node_b,
+                                                              int depth, int64_t T, int64_t D,
+                                                              int32_t* __restrict__ leaf_idx) {
+    const int lane = threadIdx.x % kWave;
+    const int64_t t = (int64_t)blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    if (t >= T) return;
+    int node = 0;
+    for (int m = 0; m < depth; ++m) {
+        float acc = 0.f;
+        for (int64_t j = lane; j < D; j += kWave)
+            acc = fmaf(Elem<BF16>::load(x, t * D + j), Elem<BF16>::load(node_w, (int64_t)node * D + j), acc);
+        const float logit = group_sum<64>(acc) + Elem<BF16>::load(node_b, node);
+        node = 2 * node + 1 + (logit >= 0.0f ? 1 : 0);
+    }
+    if (lane == 0) leaf_idx[t] = node - ((1 << depth) - 1);
+}
+
+// D % (16 bytes of elements) == 0 and all row starts 16-byte aligned.
+bool vec_ok(const void* p, int64_t row_elems, bool bf16) {
+    const int per = bf16 ? 8 : 4;
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && row_elems % per == 0;
+}
+
+namespace {
+
+struct DeviceInfo {
+    int cus = 0;
+    size_t lds_per_block = 0;
+};
+
+DeviceInfo device_info() {
+    static DeviceInfo info[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DeviceInfo{256, 64 * 1024};
+    if (info[dev].cus == 0) {
+        hipDeviceProp_t p;
+        if (hipGetDeviceProperties(&p, dev) == hipSuccess) {
+            info[dev].cus = p.multiProcessorCount > 0 ? p.multiProcessorCount : 256;
+            info[dev].lds_per_block = p.sharedMemPerBlockOptin > 0 ? p.sharedMemPerBlockOptin : p.sharedMemPerBlock;
+        } else {
+            (void)hipGetLastError();
+            info[dev] = DeviceInfo{256, 64 * 1024};
+        }
+    }
+    return info[dev];
+}
+
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED>
+hipError_t run_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+    constexpr int kGroups = kWalkBlock / LPT;
+    const DeviceInfo di = device_info();
+    const int64_t tile = (int64_t)kGroups * TPG;
+    int64_t blocks = (p.T + tile - 1) / tile;
+    if (blocks > di.cus) blocks = di.cus;
+    const int64_t tokens_per_block = (p.T + blocks - 1) / blocks;
+    // stage the top levels while a block handles at least two tokens per staged row and they fit
+    const int64_t row_bytes = p.D * (BF16 ? 2 : 4);
+    size_t lds_cap = di.lds_per_block;
+    if (lds_cap > 144 * 1024) lds_cap = 144 * 1024;
+    int top = 0;
+    while (top < p.depth) {
+        const int64_t rows = ((int64_t)1 << (top + 1)) - 1;
+        if (rows * 2 > tokens_per_block || (size_t)(rows * (row_bytes + 4)) > lds_cap) break;
+        ++top;
+    }
+    const size_t lds_bytes = (size_t)(((int64_t)1 << top) - 1) * (row_bytes + 4);
+    auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED>;
+    if (lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    WalkArgs a;
+    a.x = (const uint4*)p.x;
+    a.node_w = (const uint4*)p.node_w;
+    a.node_b = p.node_b;
+    a.w1 = (const uint4*)p.leaf_w1;
+    a.b1 = p.leaf_b1;
+    a.w2 = p.leaf_w2;
+    a.b2 = p.leaf_b2;
+    a.out = p.out;
+    a.leaf_idx = leaf_idx;
+    a.T = p.T;
+    a.O = p.O;
+    a.depth = p.depth;
+    a.top = top;
+    a.nvec = (int)(p.D / Elem<BF16>::kPerVec);
+    a.L = p.L;
+    a.act = p.act;
+    a.out_vec = FUSED && vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
+    kern<<<dim3((unsigned)blocks), dim3(kWalkBlock), lds_bytes, s>>>(a);
+    return hipGetLastError();
+}
+
+template <bool BF16, bool FUSED>
+hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+    const int64_t nvec = p.D / Elem<BF16>::kPerVec;
+    // (lanes per token, 16-byte vectors per lane, tokens per group, block size): blocks of 1024
+    // threads leave 128 VGPRs per lane, blocks of 512 leave 256 for the long-row variants
+    if (nvec <= 16) return run_walk<BF16, 16, 1, 4, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 32) return run_walk<BF16, 16, 2, 2, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 64) return run_walk<BF16, 16, 4, 2, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 96) return run_walk<BF16, 16, 6, 2, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 128) return run_walk<BF16, 16, 8, 2, 512, FUSED>(p, leaf_idx, s);
+    if (nvec <= 256) return run_walk<BF16, 64, 4, 2, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 512) return run_walk<BF16, 64, 8, 2, 512, FUSED>(p, leaf_idx, s);
+    return run_walk<BF16, 64, 16, 1, 512, FUSED>(p, leaf_idx, s);
+}
+
+}  // namespace
+
+bool walk_shape_ok(const Problem& p) {
+    const int64_t per = p.bf16 ? 8 : 4;
+    return vec_ok(p.x, p.D, p.bf16) && (p.depth == 0 || vec_ok(p.node_w, p.D, p.bf16)) && p.D / per <= 1024;
+}
+
+bool fused_shape_ok(const Problem& p) {
+    return walk_shape_ok(p) && vec_ok(p.leaf_w1, p.D, p.bf16) && p.L <= kFusedMaxLeafWidth;
+}
+
+hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+    if (p.T == 0) return hipSuccess;
+    if (walk_shape_ok(p))
+        return p.bf16 ? dispatch_walk<true, false>(p, leaf_idx, s) : dispatch_walk<false, false>(p, leaf_idx, s);
+    const int64_t blocks = (p.T + 3) / 4;
+    if (p.bf16)
+        descend_generic_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(p.x, p.node_w, p.node_b, p.depth,
+                                                                                 p.T, p.D, leaf_idx);
+    else
+        descend_generic_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(p.x, p.node_w, p.node_b, p.depth,
+                                                                                  p.T, p.D, leaf_idx);
+    return hipGetLastError();
+}
+
+// Descent, leaf network and output row in one launch (needs fused_shape_ok).
+hipError_t launch_walk_fused(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+    if (p.T == 0) return hipSuccess;
+    return p.bf16 ? dispatch_walk<true, true>(p, leaf_idx, s) : dispatch_walk<false, true>(p, leaf_idx, s);
+}
+
+}  // namespace fff

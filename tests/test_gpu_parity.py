@@ -182,7 +182,7 @@ def test_descend_and_leaf_stages():
     assert err.max() <= 2e-2
 
 
-@pytest.mark.parametrize("opt", [("bucketing", 0), ("fused_max_T", 1 << 30)])
+@pytest.mark.parametrize("opt", [("bucketing", 0), ("path", 1), ("path", 2), ("path", 3)])
 def test_alternative_paths_agree_with_the_oracle(opt):
     import paper_2308_14711_amd as F
     w = W.make_layer("paths", 2000, 256, 128, 6, 4, W.ACT_GELU, W.DTYPE_BF16, seed=9)
