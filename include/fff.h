@@ -138,16 +138,17 @@ int fff_release_workspace(void);
 
 /*
  * Tuning and test switches (process-wide; not thread-safe against running calls).
- *   "leaf_path"      0 = choose per bucket (default), 1 = every token through the
- *                    gather path, 2 = every bucket through the MFMA tile path
- *                    (bf16 only; silently the gather path otherwise)
- *   "gemm_min_rows"  smallest bucket handed to the MFMA tile path (default 8)
+ *   "leaf_path"      staged path only: 0 = MFMA tile kernel when the shape allows it
+ *                    (bf16, leaf_width <= 16, D % 8 == 0, O % 4 == 0), else the gather
+ *                    kernel (default); 1 = always the gather kernel
  *   "path"           0 = choose by shape (default), 1 = one fused launch (walk, leaf
  *                    network and output row per token; leaf_width <= 8), 2 = staged
  *                    (descent, bucketing, leaf kernel), 3 = the element-wise fallback
  *                    kernel; a path the shape does not allow falls back to one it does
  *   "bucketing"      1 (default) = the leaf kernel visits tokens grouped by leaf,
  *                    0 = in token order (no bucketing stage)
+ *   "bucket_kernel"  0 = choose by size (default), 1 = the one-launch bucketing kernel when
+ *                    the sizes allow it, 2 = always the chunk-matrix kernels
  *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages
  *                    (read them with fff_stage_times); 0 (default) = off
  * Unknown names or negative values return FFF_ERR_UNSUPPORTED.

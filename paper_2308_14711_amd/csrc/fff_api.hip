@@ -26,10 +26,10 @@ std::mutex g_mu;
 
 struct Options {
     int64_t path = 0;            // 0 auto, 1 fused walk, 2 staged, 3 generic one-wave-per-token
-    int64_t leaf_path = 0;       // 0 auto, 1 gather only, 2 tiles only
-    int64_t gemm_min_rows = 8;
+    int64_t leaf_path = 0;       // 0 auto (MFMA tiles when the shape allows), 1 gather kernel only
     int64_t bucketing = 1;       // 0: leaf kernel visits tokens in token order
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
+    int64_t bucket_kernel = 0;   // 0 auto, 1 one-launch kernel, 2 chunk-matrix kernels
 } g_opt;
 
 // Events recorded around the stages of fff_forward_hard while "stage_timing" is on:
@@ -187,6 +187,22 @@ int choose_path(const Problem& p) {
     return (p.L <= 2 || p.T <= 8192) ? kPathFused : kPathStaged;
 }
 
+// K2 with whichever kernel set takes the sizes; outputs may be null (then workspace arrays are used).
+int run_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws, int32_t* count,
+               int32_t* offset, int32_t* perm, hipStream_t s) {
+    hipError_t e;
+    if (g_opt.bucket_kernel != 2 && bucket_onepass_ok(T, depth)) {
+        e = launch_bucket_onepass(leaf_idx, T, depth, count, offset, perm, s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
+    }
+    const int64_t NL = (int64_t)1 << depth;
+    if ((e = launch_zero(ws.chunk_cnt, round_up(ws.n_chunks * NL, 4), s)) != hipSuccess)
+        return set_device_error(e, "zero kernel launch");
+    if ((e = launch_bucket(leaf_idx, T, depth, ws, count, offset, perm, s)) != hipSuccess)
+        return set_device_error(e, "bucket kernel launch");
+    return FFF_OK;
+}
+
 int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& ws, hipStream_t s,
                    bool timed = false) {
     hipError_t e;
@@ -196,14 +212,14 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
         if (timed) stage_mark(s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "leaf kernel launch");
     }
-    const int64_t NL = (int64_t)1 << p.depth;
-    if ((e = launch_zero(ws.chunk_cnt, round_up(ws.n_chunks * NL, 4), s)) != hipSuccess)
-        return set_device_error(e, "zero kernel launch");
-    if ((e = launch_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, s)) != hipSuccess)
-        return set_device_error(e, "bucket kernel launch");
+    const int rc = run_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, s);
+    if (rc != FFF_OK) return rc;
     if (timed) stage_mark(s);
-    if ((e = launch_leaf_gather(p, leaf_idx, ws.perm, s)) != hipSuccess)
-        return set_device_error(e, "leaf kernel launch");
+    if (g_opt.leaf_path != 1 && tiles_shape_ok(p))
+        e = launch_leaf_tiles(p, leaf_idx, ws.perm, s);
+    else
+        e = launch_leaf_gather(p, leaf_idx, ws.perm, s);
+    if (e != hipSuccess) return set_device_error(e, "leaf kernel launch");
     if (timed) stage_mark(s);
     return FFF_OK;
 }
@@ -280,13 +296,7 @@ int fff_bucket(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, in
     Layout lay;
     int rc = get_workspace(T, depth, &ws, &lay);
     if (rc != FFF_OK) return rc;
-    hipStream_t s = (hipStream_t)stream;
-    hipError_t e;
-    if ((e = launch_zero(ws.chunk_cnt, round_up(ws.n_chunks * ((int64_t)1 << depth), 4), s)) != hipSuccess)
-        return set_device_error(e, "zero kernel launch");
-    if ((e = launch_bucket(leaf_idx, T, depth, ws, count, offset, perm, s)) != hipSuccess)
-        return set_device_error(e, "bucket kernel launch");
-    return FFF_OK;
+    return run_bucket(leaf_idx, T, depth, ws, count, offset, perm, (hipStream_t)stream);
 }
 
 int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1, const void* leaf_w2,
@@ -339,10 +349,14 @@ int fff_release_workspace(void) {
 static int64_t* option_slot(const char* name) {
     if (!name) return nullptr;
     if (!std::strcmp(name, "leaf_path")) return &g_opt.leaf_path;
-    if (!std::strcmp(name, "gemm_min_rows")) return &g_opt.gemm_min_rows;
     if (!std::strcmp(name, "path")) return &g_opt.path;
+    if (!std::strcmp(name, "walk_tpg")) return &g_walk_tuning.tpg;
+    if (!std::strcmp(name, "walk_block")) return &g_walk_tuning.block;
+    if (!std::strcmp(name, "walk_top")) return &g_walk_tuning.top;
+    if (!std::strcmp(name, "walk_bpc")) return &g_walk_tuning.bpc;
     if (!std::strcmp(name, "bucketing")) return &g_opt.bucketing;
     if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
+    if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
     return nullptr;
 }
 

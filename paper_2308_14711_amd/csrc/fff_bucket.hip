@@ -16,6 +16,16 @@
 //
 // M must be zero on entry (launch_zero) because a chunk touches only the
 // leaves it contains.
+//
+// For trees of moderate size (2^depth <= 2^19 leaves, T <= 2^21 tokens) all
+// three steps run as ONE launch with no global intermediate and no atomics on
+// global memory (bucket_onepass_kernel): a block owns a contiguous range of
+// leaves and reads the whole leaf_idx array twice.  Pass 1 counts, per wave
+// (each wave owns a contiguous token range), the tokens of every owned leaf
+// and the tokens of all lower-numbered leaves; an in-LDS scan turns that into
+// the owned leaves' global offsets and each wave's starting position inside
+// every leaf.  Pass 2 walks the same tokens in the same order and writes
+// perm; same-leaf tokens of one 64-token batch are ranked with ballots.
 #include "fff_device.h"
 #include "fff_internal.h"
 
@@ -174,6 +184,134 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
     const int64_t chunk = t / ((int64_t)kChunkTokens * rounds);
     const int32_t pos = offset[leaf] + M[leaf * n_chunks + chunk] + rank[t];
     perm[pos] = (int32_t)t;
+}
+
+
+constexpr int kOnepassWaves = 16;
+constexpr int kOnepassMaxLeavesPerBlock = 512;
+constexpr int kAhead = 16;
+
+__device__ __forceinline__ uint64_t lanes_below(int lane) { return lane == 0 ? 0ull : (~0ull >> (64 - lane)); }
+
+__global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __restrict__ leaf_idx, int64_t T,
+                                                              int64_t n_leaves, int per_block,
+                                                              int32_t* __restrict__ count,
+                                                              int32_t* __restrict__ offset,
+                                                              int32_t* __restrict__ perm) {
+    extern __shared__ int32_t sm[];
+    int32_t* cnt = sm;                                       // [16][per_block] per-wave counts, then bases
+    int32_t* lbase = sm + kOnepassWaves * per_block;         // [per_block] start of each owned leaf
+    int32_t* below = lbase + per_block;                      // [16] tokens of lower leaves, per wave
+    int32_t* wsum = below + kOnepassWaves;                   // [16] scratch of the block scan
+    const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
+    const int64_t lo = (int64_t)blockIdx.x * per_block;
+    const int64_t hi = lo + per_block < n_leaves ? lo + per_block : n_leaves;
+    const int n_own = (int)(hi - lo);
+
+    for (int i = tid; i < kOnepassWaves * per_block; i += 1024) cnt[i] = 0;
+    __syncthreads();
+
+    // token range of this wave: whole 64-token batches
+    const int64_t batches = (T + kWave - 1) / kWave;
+    const int64_t per_wave = (batches + kOnepassWaves - 1) / kOnepassWaves;
+    const int64_t b_beg = per_wave * w, b_end = b_beg + per_wave < batches ? b_beg + per_wave : batches;
+    int32_t* my_cnt = cnt + w * per_block;
+
+    // kAhead independent loads per lane are in flight before any is used
+    int32_t n_below = 0;
+    for (int64_t b = b_beg; b < b_end; b += kAhead) {
+        int32_t lf[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int64_t t = (b + u) * kWave + lane;
+            lf[u] = (b + u < b_end && t < T) ? leaf_idx[t] : 0x7fffffff;
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            n_below += lf[u] < lo ? 1 : 0;
+            if (lf[u] >= lo && lf[u] < hi) atomicAdd(&my_cnt[lf[u] - lo], 1);
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) n_below += __shfl_xor(n_below, d, kWave);
+    if (lane == 0) below[w] = n_below;
+    __syncthreads();
+
+    // per owned leaf: exclusive prefix over the waves (token order), and the leaf's total
+    int32_t total = 0;
+    if (tid < n_own) {
+        for (int ww = 0; ww < kOnepassWaves; ++ww) {
+            const int32_t v = cnt[ww * per_block + tid];
+            cnt[ww * per_block + tid] = total;
+            total += v;
+        }
+    }
+    // exclusive scan of the totals over the owned leaves (per_block <= 512 <= 1024 threads)
+    int32_t inc = total;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int32_t o = __shfl_up(inc, d, kWave);
+        if (lane >= d) inc += o;
+    }
+    if (lane == kWave - 1) wsum[w] = inc;
+    __syncthreads();
+    int32_t before = 0, n_below_all = 0;
+    for (int ww = 0; ww < kOnepassWaves; ++ww) {
+        if (ww < w) before += wsum[ww];
+        n_below_all += below[ww];
+    }
+    if (tid < n_own) {
+        const int32_t start = n_below_all + before + inc - total;
+        lbase[tid] = start;
+        if (offset) offset[lo + tid] = start;
+        if (count) count[lo + tid] = total;
+    }
+    if (offset && hi == n_leaves && tid == 0) offset[n_leaves] = (int32_t)T;
+    __syncthreads();
+    if (!perm) return;
+
+    // pass 2: same tokens, same order; positions are start of leaf + tokens of earlier
+    // waves + tokens seen so far by this wave + rank inside the batch
+    for (int64_t b = b_beg; b < b_end; b += kAhead) {
+        int32_t lf[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int64_t t = (b + u) * kWave + lane;
+            lf[u] = (b + u < b_end && t < T) ? leaf_idx[t] : 0x7fffffff;
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const bool own = lf[u] >= lo && lf[u] < hi;
+            uint64_t pending = __ballot(own);
+            while (pending) {
+                const int first = __ffsll((unsigned long long)pending) - 1;
+                const int32_t leaf = __shfl(lf[u], first, kWave);
+                const uint64_t grp = __ballot(own && lf[u] == leaf);
+                const int local = leaf - (int32_t)lo;
+                int32_t seen = 0;
+                if (lane == first) seen = atomicAdd(&my_cnt[local], __popcll(grp));
+                seen = __shfl(seen, first, kWave);
+                if ((grp >> lane) & 1ull)
+                    perm[lbase[local] + seen + __popcll(grp & lanes_below(lane))] = (int32_t)((b + u) * kWave + lane);
+                pending &= ~grp;
+            }
+        }
+    }
+}
+
+// true when the one-launch kernel takes (T, depth)
+bool bucket_onepass_ok(int64_t T, int depth) { return depth <= 19 && T <= ((int64_t)1 << 21); }
+
+hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count,
+                                 int32_t* offset, int32_t* perm, hipStream_t s) {
+    const int64_t NL = (int64_t)1 << depth;
+    int64_t per_block = (NL + 255) / 256;
+    if (per_block > kOnepassMaxLeavesPerBlock) per_block = kOnepassMaxLeavesPerBlock;
+    const int64_t blocks = (NL + per_block - 1) / per_block;
+    const size_t lds = sizeof(int32_t) * (size_t)(kOnepassWaves * per_block + per_block + 2 * kOnepassWaves);
+    bucket_onepass_kernel<<<dim3((unsigned)blocks), dim3(1024), lds, s>>>(leaf_idx, T, NL, (int)per_block, count,
+                                                                          offset, perm);
+    return hipGetLastError();
 }
 
 hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,

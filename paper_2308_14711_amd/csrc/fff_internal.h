@@ -45,6 +45,14 @@ bool vec_ok(const void* p, int64_t row_elems, bool bf16);
 hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 // Descent + leaf network + output row in one launch; needs fused_shape_ok(p).
 hipError_t launch_walk_fused(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+// Experiment switches of the walk kernel (0 = the built-in choice).
+struct WalkTuning {
+    int64_t tpg = 0;     // tokens per lane group
+    int64_t block = 0;   // threads per block
+    int64_t top = 0;     // k + 1 forces at most k LDS-staged levels
+    int64_t bpc = 0;     // persistent blocks per compute unit
+};
+extern WalkTuning g_walk_tuning;
 bool walk_shape_ok(const Problem& p);
 bool fused_shape_ok(const Problem& p);
 
@@ -52,13 +60,18 @@ bool fused_shape_ok(const Problem& p);
 hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,
                          int32_t* count, int32_t* offset, int32_t* perm, hipStream_t s);
 hipError_t launch_zero(int32_t* p, int64_t n, hipStream_t s);
+// K2 in one launch (no workspace besides the outputs); any output may be null.
+bool bucket_onepass_ok(int64_t T, int depth);
+hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count,
+                                 int32_t* offset, int32_t* perm, hipStream_t s);
 
 // K3 + K4: leaf networks and output rows.
 //   order == nullptr: slot i is token i.  Otherwise slot i is token order[i].
 hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order,
                               hipStream_t s);
-hipError_t launch_leaf_tiles(const Problem& p, const Workspace& ws, int gemm_min_rows, int force_path,
-                             hipStream_t s);
+// MFMA tile path over tokens grouped by leaf (perm); needs tiles_shape_ok(p).
+bool tiles_shape_ok(const Problem& p);
+hipError_t launch_leaf_tiles(const Problem& p, const int32_t* leaf_idx, const int32_t* perm, hipStream_t s);
 
 // Whole forward pass in one launch, one token per lane group (any shape).
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);

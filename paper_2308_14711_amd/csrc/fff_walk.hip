@@ -254,13 +254,18 @@ DeviceInfo device_info() {
     return info[dev];
 }
 
+}  // namespace
+WalkTuning g_walk_tuning;
+namespace {
+
 template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED>
 hipError_t run_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     constexpr int kGroups = kWalkBlock / LPT;
     const DeviceInfo di = device_info();
     const int64_t tile = (int64_t)kGroups * TPG;
     int64_t blocks = (p.T + tile - 1) / tile;
-    if (blocks > di.cus) blocks = di.cus;
+    const int64_t cap = (int64_t)di.cus * (g_walk_tuning.bpc > 0 ? g_walk_tuning.bpc : 1);
+    if (blocks > cap) blocks = cap;
     const int64_t tokens_per_block = (p.T + blocks - 1) / blocks;
     // stage the top levels while a block handles at least two tokens per staged row and they fit
     const int64_t row_bytes = p.D * (BF16 ? 2 : 4);
@@ -272,6 +277,7 @@ hipError_t run_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
         if (rows * 2 > tokens_per_block || (size_t)(rows * (row_bytes + 4)) > lds_cap) break;
         ++top;
     }
+    if (g_walk_tuning.top > 0 && g_walk_tuning.top - 1 < top) top = (int)g_walk_tuning.top - 1;
     const size_t lds_bytes = (size_t)(((int64_t)1 << top) - 1) * (row_bytes + 4);
     auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED>;
     if (lds_bytes > 48 * 1024) {
@@ -309,7 +315,16 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     if (nvec <= 16) return run_walk<BF16, 16, 1, 4, 1024, FUSED>(p, leaf_idx, s);
     if (nvec <= 32) return run_walk<BF16, 16, 2, 2, 1024, FUSED>(p, leaf_idx, s);
     if (nvec <= 64) return run_walk<BF16, 16, 4, 2, 1024, FUSED>(p, leaf_idx, s);
-    if (nvec <= 96) return run_walk<BF16, 16, 6, 2, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 96) {
+        const int64_t tpg = g_walk_tuning.tpg, blk = g_walk_tuning.block;
+        if (tpg == 1 && blk == 512) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
+        if (tpg == 1) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
+        if (tpg == 2 && blk == 512) return run_walk<BF16, 16, 6, 2, 512, FUSED>(p, leaf_idx, s);
+        if (tpg == 4 && blk == 512) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
+        if (tpg == 3 && blk == 512) return run_walk<BF16, 16, 6, 3, 512, FUSED>(p, leaf_idx, s);
+        if (tpg == 4 && blk == 256) return run_walk<BF16, 16, 6, 4, 256, FUSED>(p, leaf_idx, s);
+        return run_walk<BF16, 16, 6, 2, 1024, FUSED>(p, leaf_idx, s);
+    }
     if (nvec <= 128) return run_walk<BF16, 16, 8, 2, 512, FUSED>(p, leaf_idx, s);
     if (nvec <= 256) return run_walk<BF16, 64, 4, 2, 1024, FUSED>(p, leaf_idx, s);
     if (nvec <= 512) return run_walk<BF16, 64, 8, 2, 512, FUSED>(p, leaf_idx, s);

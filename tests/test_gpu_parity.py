@@ -40,16 +40,32 @@ SMALL = [
     ("vit_like_small",    777, 768, 768, 4, 8, W.ACT_GELU, W.DTYPE_BF16),
     ("bert_like_small",   1000, 768, 768, 6, 1, W.ACT_GELU, W.DTYPE_BF16),
     ("skew_like_small",   515, 4096, 4096, 7, 4, W.ACT_GELU, W.DTYPE_BF16),
+
+
+    ("tiles_L1",          700, 96,  132, 5, 1, W.ACT_GELU, W.DTYPE_BF16),
+    ("tiles_L2",          333, 40,  12,  6, 2, W.ACT_RELU, W.DTYPE_BF16),
+    ("tiles_L3",          401, 72,  68,  4, 3, W.ACT_GELU, W.DTYPE_BF16),
+    ("tiles_L5",          250, 64,  64,  3, 5, W.ACT_GELU, W.DTYPE_BF16),
+    ("tiles_L16",         300, 128, 200, 2, 16, W.ACT_RELU, W.DTYPE_BF16),
+    ("tiles_sparse",      200, 64,  64,  10, 4, W.ACT_GELU, W.DTYPE_BF16),
+    ("gather_L17",        150, 64,  64,  3, 17, W.ACT_GELU, W.DTYPE_BF16),
 ]
 
 
+@pytest.mark.parametrize("path", [0, 2], ids=["auto", "staged"])
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
-def test_small_and_edge_shapes(case):
+def test_small_and_edge_shapes(case, path):
+    import paper_2308_14711_amd as F
     name, T, D, O, depth, L, act, dtype = case
-    print("\n[case] %s T=%d D=%d O=%d depth=%d L=%d dtype=%d seed 5" % (name, T, D, O, depth, L, dtype), flush=True)
+    print("\n[case] %s T=%d D=%d O=%d depth=%d L=%d dtype=%d seed 5 path=%d" % (name, T, D, O, depth, L, dtype, path),
+          flush=True)
     w = W.make_layer(name, T, D, O, depth, L, act, dtype, seed=5,
                      node_b="zipf" if name.startswith("skew") else "uniform")
-    out, idx = run_forward(w)
+    F.fff_set_option("path", path)
+    try:
+        out, idx = run_forward(w)
+    finally:
+        F.fff_set_option("path", 0)
     _log(name, check_against_oracle(w, out, idx))
 
 
@@ -132,11 +148,13 @@ def test_runs_on_a_side_stream():
 
 @pytest.mark.parametrize("depth,T,kind", [(0, 10, "u"), (3, 1, "u"), (3, 1000, "u"), (8, 5000, "zipf"),
                                           (11, 65536, "u"), (15, 16384, "zipf"), (20, 10000, "u"),
-                                          (6, 4096, "one")])
-def test_bucket_stage_is_bit_exact(depth, T, kind):
+                                          (6, 4096, "one"), (19, 70001, "zipf"), (10, 300000, "u")])
+@pytest.mark.parametrize("kernel", [1, 2])
+def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
     import torch
     import paper_2308_14711_amd as F
-    print("\n[case] bucket depth=%d T=%d %s" % (depth, T, kind), flush=True)
+    print("\n[case] bucket depth=%d T=%d %s kernel=%d" % (depth, T, kind, kernel), flush=True)
+    F.fff_set_option("bucket_kernel", kernel)
     rng = np.random.default_rng(depth * 1000 + T)
     NL = 1 << depth
     if kind == "u":
@@ -150,12 +168,15 @@ def test_bucket_stage_is_bit_exact(depth, T, kind):
     d_count = torch.full((NL,), -1, dtype=torch.int32, device="cuda")
     d_offset = torch.full((NL + 1,), -1, dtype=torch.int32, device="cuda")
     d_perm = torch.full((T,), -1, dtype=torch.int32, device="cuda")
-    for _ in range(2):      # twice: the workspace must come back clean
-        F.fff_bucket(d_li, depth, d_count, d_offset, d_perm)
-        torch.cuda.synchronize()
-        assert np.array_equal(d_count.cpu().numpy(), count)
-        assert np.array_equal(d_offset.cpu().numpy(), offset)
-        assert np.array_equal(d_perm.cpu().numpy(), perm)
+    try:
+        for _ in range(2):      # twice: the workspace must come back clean
+            F.fff_bucket(d_li, depth, d_count, d_offset, d_perm)
+            torch.cuda.synchronize()
+            assert np.array_equal(d_count.cpu().numpy(), count)
+            assert np.array_equal(d_offset.cpu().numpy(), offset)
+            assert np.array_equal(d_perm.cpu().numpy(), perm)
+    finally:
+        F.fff_set_option("bucket_kernel", 0)
 
 
 def test_descend_and_leaf_stages():
@@ -182,7 +203,7 @@ def test_descend_and_leaf_stages():
     assert err.max() <= 2e-2
 
 
-@pytest.mark.parametrize("opt", [("bucketing", 0), ("path", 1), ("path", 2), ("path", 3)])
+@pytest.mark.parametrize("opt", [("bucketing", 0), ("path", 1), ("path", 2), ("path", 3), ("leaf_path", 1)])
 def test_alternative_paths_agree_with_the_oracle(opt):
     import paper_2308_14711_amd as F
     w = W.make_layer("paths", 2000, 256, 128, 6, 4, W.ACT_GELU, W.DTYPE_BF16, seed=9)
