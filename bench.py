@@ -132,6 +132,7 @@ def main():
             cpu_passes += 1
         cpu_s = time.perf_counter() - t2
     alg = algorithmic_bytes(w, ref_idx)
+    path_names = {1: "fused", 2: "staged", 3: "generic"}
 
     # per-stage durations: HIP events recorded by the library on the call's stream
     stages = {}
@@ -142,7 +143,10 @@ def main():
         torch.cuda.synchronize()
         d_ms, b_ms, l_ms, calls = F.fff_stage_times()
         F.fff_set_option("stage_timing", 0)
-        for name, ms in (("descent", d_ms), ("bucketing", b_ms), ("leaf", l_ms)):
+        fused = F.fff_get_option("last_path") != 2
+        if fused:      # one launch did the whole path: it carries the whole path's bytes
+            alg = dict(alg, walk_fused=alg["path"])
+        for name, ms in ((("walk_fused", d_ms),) if fused else (("descent", d_ms), ("bucketing", b_ms), ("leaf", l_ms))):
             avg = ms / max(calls, 1)
             gbs = alg[name] / (avg * 1e-3) / 1e9 if avg > 0 else 0.0
             stages[name] = {"avg_ms": round(avg, 5), "alg_bytes": alg[name], "GBps": round(gbs, 1),
@@ -205,7 +209,8 @@ def main():
         "dtype": "bf16" if w.dtype == W.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (w.name, w.note), "T": w.T, "D": w.D, "O": w.O, "depth": w.depth,
                    "leaf_width": w.leaf_width, "act": "gelu" if w.act else "relu", "buffer_sets": nsets,
-                   "seed": 0, "options": args.opt},
+                   "seed": 0, "options": args.opt,
+                   "launch_path": path_names.get(F.fff_get_option("last_path"), "?")},
         "roofline": roofline,
         "path": {"alg_bytes": alg["path"], "GBps": round(path_gbs, 1), "frac": round(path_gbs / HBM_PEAK_GBS, 4),
                  "u_node": alg["u_node"], "u_leaf": alg["u_leaf"]},

@@ -141,12 +141,14 @@ int fff_release_workspace(void);
  *   "leaf_path"      staged path only: 0 = MFMA tile kernel when the shape allows it
  *                    (bf16, leaf_width <= 16, D % 8 == 0, O % 4 == 0), else the gather
  *                    kernel (default); 1 = always the gather kernel
- *   "path"           0 = choose by shape (default), 1 = one fused launch (walk, leaf
- *                    network and output row per token; leaf_width <= 8), 2 = staged
+ *   "path"           0 = choose by shape (default: staged when leaf_width >= 4 and a leaf
+ *                    sees >= 32 tokens on average, else fused), 1 = one fused launch (walk,
+ *                    leaf network and output row per token; leaf_width <= 8), 2 = staged
  *                    (descent, bucketing, leaf kernel), 3 = the element-wise fallback
  *                    kernel; a path the shape does not allow falls back to one it does
  *   "bucketing"      1 (default) = the leaf kernel visits tokens grouped by leaf,
  *                    0 = in token order (no bucketing stage)
+ *   "last_path"      read it after a call: the path (1, 2 or 3) fff_forward_hard took
  *   "bucket_kernel"  0 = choose by size (default), 1 = the one-launch bucketing kernel when
  *                    the sizes allow it, 2 = always the chunk-matrix kernels
  *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages

@@ -30,6 +30,7 @@ struct Options {
     int64_t bucketing = 1;       // 0: leaf kernel visits tokens in token order
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
     int64_t bucket_kernel = 0;   // 0 auto, 1 one-launch kernel, 2 chunk-matrix kernels
+    int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
 } g_opt;
 
 // Events recorded around the stages of fff_forward_hard while "stage_timing" is on:
@@ -184,7 +185,9 @@ int choose_path(const Problem& p) {
     if (g_opt.path == kPathGeneric || (!fused_ok && !staged_ok)) return kPathGeneric;
     if (!staged_ok) return kPathFused;
     if (!fused_ok) return kPathStaged;
-    return (p.L <= 2 || p.T <= 8192) ? kPathFused : kPathStaged;
+    // grouping pays once a leaf is wide enough and visited by enough tokens to share its rows
+    const int64_t tokens_per_leaf = p.T >> p.depth;
+    return (p.L >= 4 && tokens_per_leaf >= 32 && p.T > 8192) ? kPathStaged : kPathFused;
 }
 
 // K2 with whichever kernel set takes the sizes; outputs may be null (then workspace arrays are used).
@@ -250,6 +253,7 @@ int fff_forward_hard(const void* x, const void* node_w, const void* node_b, cons
     g_last_error.clear();
 
     const int path = choose_path(p);
+    g_opt.last_path = path;
     if (path == kPathGeneric) {
         hipError_t e = launch_fused_generic(p, leaf_idx, s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "generic kernel launch");
@@ -357,6 +361,7 @@ static int64_t* option_slot(const char* name) {
     if (!std::strcmp(name, "bucketing")) return &g_opt.bucketing;
     if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
+    if (!std::strcmp(name, "last_path")) return &g_opt.last_path;
     return nullptr;
 }
 

@@ -189,12 +189,89 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
 
 constexpr int kOnepassWaves = 16;
 constexpr int kOnepassMaxLeavesPerBlock = 512;
-constexpr int kAhead = 16;
+constexpr int kAhead = 16;         // 16-byte loads in flight per lane (4096 tokens per wave)
+constexpr int kBatch = 4 * kWave;  // tokens per wave step: lane l holds tokens 4 l .. 4 l + 3
 
 __device__ __forceinline__ uint64_t lanes_below(int lane) { return lane == 0 ? 0ull : (~0ull >> (64 - lane)); }
 
+// leaf ids of tokens t0 .. t0 + 3 (sentinel past the end); the fast form needs 16-byte alignment
+__device__ __forceinline__ int4 load_leaf4(const int32_t* __restrict__ leaf_idx, int64_t t0, int64_t T, bool vec) {
+    const int32_t none = 0x7fffffff;
+    if (vec && t0 + 3 < T) return *(const int4*)(leaf_idx + t0);
+    int4 v;
+    v.x = t0 + 0 < T ? leaf_idx[t0 + 0] : none;
+    v.y = t0 + 1 < T ? leaf_idx[t0 + 1] : none;
+    v.z = t0 + 2 < T ? leaf_idx[t0 + 2] : none;
+    v.w = t0 + 3 < T ? leaf_idx[t0 + 3] : none;
+    return v;
+}
+
+// Pass 1 on one batch: tokens of lower leaves go to n_below, tokens of owned leaves to my_cnt.
+__device__ __forceinline__ void onepass_count(const int4 v, int32_t lo, uint32_t n_own, int32_t& n_below,
+                                              int32_t* my_cnt) {
+    const int32_t e[4] = {v.x, v.y, v.z, v.w};
+    bool own[4];
+    bool any = false;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        n_below += e[k] < lo ? 1 : 0;
+        own[k] = (uint32_t)(e[k] - lo) < n_own;
+        any = any || own[k];
+    }
+    if (__ballot(any)) {             // rare: most batches hold no token of this block's leaves
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (own[k]) atomicAdd(&my_cnt[e[k] - lo], 1);
+    }
+}
+
+// Pass 2 on one batch whose first token is t0 (lane l holds tokens t0 + 4 l .. + 3):
+// position = start of the leaf + tokens of earlier waves + tokens this wave has already placed
+// + rank inside the batch (lane-major, then element).
+__device__ __forceinline__ void onepass_place(const int4 v, int64_t t0, int lane, int32_t lo, uint32_t n_own,
+                                              const int32_t* lbase, int32_t* my_cnt,
+                                              int32_t* __restrict__ perm) {
+    const int32_t e[4] = {v.x, v.y, v.z, v.w};
+    bool own[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) own[k] = (uint32_t)(e[k] - lo) < n_own;
+    uint64_t pending = __ballot(own[0] || own[1] || own[2] || own[3]);
+    while (pending) {
+        // the smallest pending (lane, element) decides which leaf is placed next
+        const int first = __ffsll((unsigned long long)pending) - 1;
+        int32_t mine = 0x7fffffff;
+#pragma unroll
+        for (int k = 3; k >= 0; --k)
+            if (own[k]) mine = e[k];
+        const int32_t leaf = __shfl(mine, first, kWave);
+        int c = 0, pre[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            pre[k] = c;
+            c += (own[k] && e[k] == leaf) ? 1 : 0;
+        }
+        const uint64_t m0 = __ballot(c & 1), m1 = __ballot(c & 2), m2 = __ballot(c & 4);
+        const uint64_t lt = lanes_below(lane);
+        const int lanes_before = __popcll(m0 & lt) + 2 * __popcll(m1 & lt) + 4 * __popcll(m2 & lt);
+        const int n_grp = __popcll(m0) + 2 * __popcll(m1) + 4 * __popcll(m2);
+        const int local = leaf - lo;
+        int32_t seen = 0;
+        if (lane == first) seen = atomicAdd(&my_cnt[local], n_grp);
+        seen = __shfl(seen, first, kWave);
+        const int32_t at = lbase[local] + seen + lanes_before;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (own[k] && e[k] == leaf) {
+                perm[at + pre[k]] = (int32_t)(t0 + 4 * lane + k);
+                own[k] = false;
+            }
+        }
+        pending = __ballot(own[0] || own[1] || own[2] || own[3]);
+    }
+}
+
 __global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __restrict__ leaf_idx, int64_t T,
-                                                              int64_t n_leaves, int per_block,
+                                                              int64_t n_leaves, int per_block, int vec,
                                                               int32_t* __restrict__ count,
                                                               int32_t* __restrict__ offset,
                                                               int32_t* __restrict__ perm) {
@@ -204,33 +281,36 @@ __global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __r
     int32_t* below = lbase + per_block;                      // [16] tokens of lower leaves, per wave
     int32_t* wsum = below + kOnepassWaves;                   // [16] scratch of the block scan
     const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
-    const int64_t lo = (int64_t)blockIdx.x * per_block;
-    const int64_t hi = lo + per_block < n_leaves ? lo + per_block : n_leaves;
-    const int n_own = (int)(hi - lo);
+    const int32_t lo = (int32_t)((int64_t)blockIdx.x * per_block);
+    const int32_t hi = lo + per_block < n_leaves ? lo + per_block : (int32_t)n_leaves;
+    const uint32_t n_own = (uint32_t)(hi - lo);
 
     for (int i = tid; i < kOnepassWaves * per_block; i += 1024) cnt[i] = 0;
     __syncthreads();
 
-    // token range of this wave: whole 64-token batches
-    const int64_t batches = (T + kWave - 1) / kWave;
+    // token range of this wave: whole batches of 256 tokens, in token order over the waves
+    const int64_t batches = (T + kBatch - 1) / kBatch;
     const int64_t per_wave = (batches + kOnepassWaves - 1) / kOnepassWaves;
-    const int64_t b_beg = per_wave * w, b_end = b_beg + per_wave < batches ? b_beg + per_wave : batches;
+    const int64_t b_beg = per_wave * w < batches ? per_wave * w : batches;
+    const int64_t b_end = b_beg + per_wave < batches ? b_beg + per_wave : batches;
+    const int64_t full = vec ? T / kBatch : 0;      // batches read with one unguarded 16-byte load
     int32_t* my_cnt = cnt + w * per_block;
+    const int4* src = (const int4*)leaf_idx + lane;
+    const int4 none4 = make_int4(0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff);
+    auto load_batch = [&](int64_t b) {
+        return b < b_end ? (b < full ? src[b * kWave] : load_leaf4(leaf_idx, b * kBatch + 4 * lane, T, vec)) : none4;
+    };
+    // kAhead batches are fetched before any is examined.  When the wave's whole range is one
+    // such group (T <= 65536) it stays in registers for both passes.
+    const bool single = per_wave <= kAhead;
+    int4 keep[kAhead];
 
-    // kAhead independent loads per lane are in flight before any is used
     int32_t n_below = 0;
     for (int64_t b = b_beg; b < b_end; b += kAhead) {
-        int32_t lf[kAhead];
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            const int64_t t = (b + u) * kWave + lane;
-            lf[u] = (b + u < b_end && t < T) ? leaf_idx[t] : 0x7fffffff;
-        }
+        for (int u = 0; u < kAhead; ++u) keep[u] = load_batch(b + u);
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            n_below += lf[u] < lo ? 1 : 0;
-            if (lf[u] >= lo && lf[u] < hi) atomicAdd(&my_cnt[lf[u] - lo], 1);
-        }
+        for (int u = 0; u < kAhead; ++u) onepass_count(keep[u], lo, n_own, n_below, my_cnt);
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) n_below += __shfl_xor(n_below, d, kWave);
@@ -239,7 +319,7 @@ __global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __r
 
     // per owned leaf: exclusive prefix over the waves (token order), and the leaf's total
     int32_t total = 0;
-    if (tid < n_own) {
+    if ((uint32_t)tid < n_own) {
         for (int ww = 0; ww < kOnepassWaves; ++ww) {
             const int32_t v = cnt[ww * per_block + tid];
             cnt[ww * per_block + tid] = total;
@@ -260,7 +340,7 @@ __global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __r
         if (ww < w) before += wsum[ww];
         n_below_all += below[ww];
     }
-    if (tid < n_own) {
+    if ((uint32_t)tid < n_own) {
         const int32_t start = n_below_all + before + inc - total;
         lbase[tid] = start;
         if (offset) offset[lo + tid] = start;
@@ -270,32 +350,15 @@ __global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __r
     __syncthreads();
     if (!perm) return;
 
-    // pass 2: same tokens, same order; positions are start of leaf + tokens of earlier
-    // waves + tokens seen so far by this wave + rank inside the batch
+    // pass 2: same tokens, same order
     for (int64_t b = b_beg; b < b_end; b += kAhead) {
-        int32_t lf[kAhead];
+        if (!single) {
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            const int64_t t = (b + u) * kWave + lane;
-            lf[u] = (b + u < b_end && t < T) ? leaf_idx[t] : 0x7fffffff;
+            for (int u = 0; u < kAhead; ++u) keep[u] = load_batch(b + u);
         }
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            const bool own = lf[u] >= lo && lf[u] < hi;
-            uint64_t pending = __ballot(own);
-            while (pending) {
-                const int first = __ffsll((unsigned long long)pending) - 1;
-                const int32_t leaf = __shfl(lf[u], first, kWave);
-                const uint64_t grp = __ballot(own && lf[u] == leaf);
-                const int local = leaf - (int32_t)lo;
-                int32_t seen = 0;
-                if (lane == first) seen = atomicAdd(&my_cnt[local], __popcll(grp));
-                seen = __shfl(seen, first, kWave);
-                if ((grp >> lane) & 1ull)
-                    perm[lbase[local] + seen + __popcll(grp & lanes_below(lane))] = (int32_t)((b + u) * kWave + lane);
-                pending &= ~grp;
-            }
-        }
+        for (int u = 0; u < kAhead; ++u)
+            onepass_place(keep[u], (b + u) * kBatch, lane, lo, n_own, lbase, my_cnt, perm);
     }
 }
 
@@ -309,8 +372,9 @@ hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, 
     if (per_block > kOnepassMaxLeavesPerBlock) per_block = kOnepassMaxLeavesPerBlock;
     const int64_t blocks = (NL + per_block - 1) / per_block;
     const size_t lds = sizeof(int32_t) * (size_t)(kOnepassWaves * per_block + per_block + 2 * kOnepassWaves);
-    bucket_onepass_kernel<<<dim3((unsigned)blocks), dim3(1024), lds, s>>>(leaf_idx, T, NL, (int)per_block, count,
-                                                                          offset, perm);
+    const int vec = (reinterpret_cast<uintptr_t>(leaf_idx) & 15u) == 0;
+    bucket_onepass_kernel<<<dim3((unsigned)blocks), dim3(1024), lds, s>>>(leaf_idx, T, NL, (int)per_block, vec,
+                                                                          count, offset, perm);
     return hipGetLastError();
 }
 

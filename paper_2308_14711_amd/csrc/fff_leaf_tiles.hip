@@ -45,6 +45,9 @@ struct TilesArgs {
     int D, O, L, act;
 };
 
+constexpr int kChunk = 12;   // K steps of the first contraction in flight per lane
+constexpr int kRanges = 4;   // 64-wide output ranges of the second contraction in flight per lane
+
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
@@ -83,7 +86,7 @@ __global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
         n_q[q] = (4 * kg + q) % L;
     }
     const uint16_t* xrow = a.x + (int64_t)tok * D;
-    const int nk = (D + 31) / 32;
+    const int nk = 2 * ((D + 63) / 64);
 
     for (int pass = 0; pass < n_runs; pass += P) {
         // leaf of every run of this pass, handed to the lanes that need it
@@ -99,18 +102,28 @@ __global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
             }
         }
 
-        // first contraction over D
+        // first contraction over D.  The K index is only a summation order, so step s gives
+        // lane group kg the 8 elements at 64 (s / 2) + 16 kg + 8 (s % 2): two consecutive steps
+        // read 32 contiguous bytes per lane and the four lane groups cover a whole 128-byte line.
+        // kChunk steps are fetched before any is consumed so that the loads overlap.
         const uint16_t* arow = a.w1 + ((int64_t)(row_leaf >= 0 ? row_leaf : 0) * L + n_i) * D;
         const bool a_ok = row_leaf >= 0;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-        for (int s = 0; s < nk; ++s) {
-            const int k0 = 32 * s + 8 * kg;
-            uint4 av = make_uint4(0, 0, 0, 0), bv = make_uint4(0, 0, 0, 0);
-            if (a_ok && k0 < D) av = *(const uint4*)(arow + k0);
-            if (vj && k0 < D) bv = *(const uint4*)(xrow + k0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
-                                                          __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
+        for (int s0 = 0; s0 < nk; s0 += kChunk) {
+            uint4 av[kChunk], bv[kChunk];
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u) {
+                const int s = s0 + u;
+                const int k0 = 64 * (s >> 1) + 16 * kg + 8 * (s & 1);
+                av[u] = make_uint4(0, 0, 0, 0);
+                bv[u] = make_uint4(0, 0, 0, 0);
+                if (a_ok && k0 < D) av[u] = *(const uint4*)(arow + k0);
+                if (vj && k0 < D) bv[u] = *(const uint4*)(xrow + k0);
+            }
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
+                                                              __builtin_bit_cast(bf16x8_t, bv[u]), acc, 0, 0, 0);
         }
 
         // activation, mask to the token's own run, append the run indicators
@@ -137,34 +150,45 @@ __global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
             st_ok[q] = v_row[q] && run_row[q] >= pass && run_row[q] < pass + P;
         }
 
-        // second contraction, 64 outputs at a time
-        for (int o0 = 4 * j; o0 < O + 4 * j; o0 += 64) {
-            const bool o_ok = o0 < O;
-            uint2 wv[4], bv[4];
+        // second contraction, 64 outputs per step; the rows of kRanges steps are fetched before
+        // the first of them is multiplied, so their latencies overlap
+        for (int og = 4 * j; og < O + 4 * j; og += 64 * kRanges) {
+            uint2 wv[kRanges][4], bv2[kRanges][4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                wv[q] = (wptr[q] && o_ok) ? *(const uint2*)(wptr[q] + o0) : make_uint2(0, 0);
-                bv[q] = (bptr[q] && o_ok) ? *(const uint2*)(bptr[q] + o0) : make_uint2(0, 0);
-            }
-            const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
-            const uint4 f0 = make_uint4(pack_lo(wv[0].x, wv[1].x), pack_lo(wv[2].x, wv[3].x),
-                                        pack_lo(bv[0].x, bv[1].x), pack_lo(bv[2].x, bv[3].x));
-            const uint4 f1 = make_uint4(pack_hi(wv[0].x, wv[1].x), pack_hi(wv[2].x, wv[3].x),
-                                        pack_hi(bv[0].x, bv[1].x), pack_hi(bv[2].x, bv[3].x));
-            const uint4 f2 = make_uint4(pack_lo(wv[0].y, wv[1].y), pack_lo(wv[2].y, wv[3].y),
-                                        pack_lo(bv[0].y, bv[1].y), pack_lo(bv[2].y, bv[3].y));
-            const uint4 f3 = make_uint4(pack_hi(wv[0].y, wv[1].y), pack_hi(wv[2].y, wv[3].y),
-                                        pack_hi(bv[0].y, bv[1].y), pack_hi(bv[2].y, bv[3].y));
-            const f32x4_t d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f0), zero, 0, 0, 0);
-            const f32x4_t d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f1), zero, 0, 0, 0);
-            const f32x4_t d2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f2), zero, 0, 0, 0);
-            const f32x4_t d3 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f3), zero, 0, 0, 0);
-            if (o_ok) {
+            for (int g = 0; g < kRanges; ++g) {
+                const int o0 = og + 64 * g;
+                const bool ok = o0 < O;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if (st_ok[q]) {
-                        const uint2 o2 = make_uint2(pack_bf16x2(d0[q], d1[q]), pack_bf16x2(d2[q], d3[q]));
-                        *(uint2*)(a.out + (int64_t)tok_row[q] * O + o0) = o2;
+                    wv[g][q] = (wptr[q] && ok) ? *(const uint2*)(wptr[q] + o0) : make_uint2(0, 0);
+                    bv2[g][q] = (bptr[q] && ok) ? *(const uint2*)(bptr[q] + o0) : make_uint2(0, 0);
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < kRanges; ++g) {
+                const int o0 = og + 64 * g;
+                const uint2* w = wv[g];
+                const uint2* b = bv2[g];
+                const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+                const uint4 f0 = make_uint4(pack_lo(w[0].x, w[1].x), pack_lo(w[2].x, w[3].x),
+                                            pack_lo(b[0].x, b[1].x), pack_lo(b[2].x, b[3].x));
+                const uint4 f1 = make_uint4(pack_hi(w[0].x, w[1].x), pack_hi(w[2].x, w[3].x),
+                                            pack_hi(b[0].x, b[1].x), pack_hi(b[2].x, b[3].x));
+                const uint4 f2 = make_uint4(pack_lo(w[0].y, w[1].y), pack_lo(w[2].y, w[3].y),
+                                            pack_lo(b[0].y, b[1].y), pack_lo(b[2].y, b[3].y));
+                const uint4 f3 = make_uint4(pack_hi(w[0].y, w[1].y), pack_hi(w[2].y, w[3].y),
+                                            pack_hi(b[0].y, b[1].y), pack_hi(b[2].y, b[3].y));
+                const f32x4_t d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f0), zero, 0, 0, 0);
+                const f32x4_t d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f1), zero, 0, 0, 0);
+                const f32x4_t d2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f2), zero, 0, 0, 0);
+                const f32x4_t d3 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f3), zero, 0, 0, 0);
+                if (o0 < O) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (st_ok[q]) {
+                            const uint2 o2 = make_uint2(pack_bf16x2(d0[q], d1[q]), pack_bf16x2(d2[q], d3[q]));
+                            *(uint2*)(a.out + (int64_t)tok_row[q] * O + o0) = o2;
+                        }
                     }
                 }
             }

@@ -24,13 +24,14 @@ namespace fff {
 constexpr int kFusedMaxLeafWidth = 8;
 
 // xv . row, where row[v] is fetched by LOAD(v)
-template <bool BF16, int LPT, int NV, typename LoadRow>
+// TIGHT: the row is exactly LPT * NV vectors long, so no lane needs a bounds check.
+template <bool BF16, int LPT, int NV, bool TIGHT, typename LoadRow>
 __device__ __forceinline__ float row_dot(const uint4 (&xv)[NV], int sub, int nvec, LoadRow load) {
     uint4 wv[NV];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int v = sub + i * LPT;
-        wv[i] = v < nvec ? load(v) : make_uint4(0, 0, 0, 0);
+        wv[i] = (TIGHT || v < nvec) ? load(v) : make_uint4(0, 0, 0, 0);
     }
     float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
@@ -74,7 +75,8 @@ struct WalkArgs {
 };
 
 // FUSED = false: writes leaf_idx only.  FUSED = true: also the leaf network (L <= 8).
-template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED>
+// TIGHT: D (and, when FUSED with vector output, O) is exactly LPT * NV vectors.
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT>
 __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
     extern __shared__ uint4 lds[];                 // [(2^top - 1) * nvec] rows, then (2^top - 1) biases
     constexpr int kGroups = kWalkBlock / LPT;
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 const int v = sub + i * LPT;
-                xv[k][i] = v < nvec ? load_stream(xrow + v) : make_uint4(0, 0, 0, 0);
+                xv[k][i] = (TIGHT || v < nvec) ? load_stream(xrow + v) : make_uint4(0, 0, 0, 0);
             }
         }
         int node[TPG];
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
 #pragma unroll
             for (int k = 0; k < TPG; ++k) {
                 const uint4* row = lds + (int64_t)node[k] * nvec;
-                s[k] = row_dot<BF16, LPT, NV>(xv[k], sub, nvec, [&](int v) { return row[v]; });
+                s[k] = row_dot<BF16, LPT, NV, TIGHT>(xv[k], sub, nvec, [&](int v) { return row[v]; });
             }
 #pragma unroll
             for (int k = 0; k < TPG; ++k) {
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
             for (int k = 0; k < TPG; ++k) {
                 const uint4* row = a.node_w + (int64_t)node[k] * nvec;
                 bias[k] = Elem<BF16>::load(a.node_b, node[k]);
-                s[k] = row_dot<BF16, LPT, NV>(xv[k], sub, nvec, [&](int v) { return row[v]; });
+                s[k] = row_dot<BF16, LPT, NV, TIGHT>(xv[k], sub, nvec, [&](int v) { return row[v]; });
             }
 #pragma unroll
             for (int k = 0; k < TPG; ++k) {
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
                 for (int k = 0; k < TPG; ++k) {
                     const uint4* row = a.w1 + (leaf[k] * a.L + r) * nvec;
                     bias[k] = Elem<BF16>::load(a.b1, leaf[k] * a.L + r);
-                    s[k] = row_dot<BF16, LPT, NV>(xv[k], sub, nvec, [&](int v) { return row[v]; });
+                    s[k] = row_dot<BF16, LPT, NV, TIGHT>(xv[k], sub, nvec, [&](int v) { return row[v]; });
                 }
 #pragma unroll
                 for (int k = 0; k < TPG; ++k) h[k][r] = activate(group_sum<LPT>(s[k]) + bias[k], a.act);
@@ -173,22 +175,51 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
         for (int k = 0; k < TPG; ++k) {
             if (!live[k]) continue;
             if (a.out_vec) {
+                // NV vectors per lane at a time, all of a row's fetches issued before they are used
                 const int ovec = (int)(a.O / VE);
                 const uint4* w2v = (const uint4*)a.w2 + leaf[k] * a.L * ovec;
                 const uint4* b2v = (const uint4*)a.b2 + leaf[k] * ovec;
                 uint4* orow = (uint4*)a.out + t[k] * ovec;
-                for (int ov = sub; ov < ovec; ov += LPT) {
-                    float acc[VE], wf[VE];
-                    unpack_vec<BF16>(b2v[ov], acc);
+                for (int ov0 = sub; ov0 < ovec + sub; ov0 += LPT * NV) {
+                    uint4 bv[NV], wv[NV];
 #pragma unroll
-                    for (int r = 0; r < kFusedMaxLeafWidth; ++r) {
-                        if (r < a.L) {
-                            unpack_vec<BF16>(w2v[(int64_t)r * ovec + ov], wf);
+                    for (int i = 0; i < NV; ++i) {
+                        const int ov = ov0 + i * LPT;
+                        const bool ok = TIGHT || ov < ovec;
+                        bv[i] = ok ? b2v[ov] : make_uint4(0, 0, 0, 0);
+                        wv[i] = ok ? w2v[ov] : make_uint4(0, 0, 0, 0);
+                    }
+                    float acc[NV][VE];
 #pragma unroll
-                            for (int e = 0; e < VE; ++e) acc[e] = fmaf(h[k][r], wf[e], acc[e]);
+                    for (int i = 0; i < NV; ++i) {
+                        float wf[VE];
+                        unpack_vec<BF16>(bv[i], acc[i]);
+                        unpack_vec<BF16>(wv[i], wf);
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) acc[i][e] = fmaf(h[k][0], wf[e], acc[i][e]);
+                    }
+                    for (int r = 1; r < a.L; ++r) {
+#pragma unroll
+                        for (int i = 0; i < NV; ++i) {
+                            const int ov = ov0 + i * LPT;
+                            wv[i] = (TIGHT || ov < ovec) ? w2v[(int64_t)r * ovec + ov] : make_uint4(0, 0, 0, 0);
+                        }
+                        float hr = h[k][0];
+#pragma unroll
+                        for (int q = 1; q < kFusedMaxLeafWidth; ++q) hr = q == r ? h[k][q] : hr;
+#pragma unroll
+                        for (int i = 0; i < NV; ++i) {
+                            float wf[VE];
+                            unpack_vec<BF16>(wv[i], wf);
+#pragma unroll
+                            for (int e = 0; e < VE; ++e) acc[i][e] = fmaf(hr, wf[e], acc[i][e]);
                         }
                     }
-                    store_stream(orow + ov, pack_vec<BF16>(acc));
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) {
+                        const int ov = ov0 + i * LPT;
+                        if (TIGHT || ov < ovec) store_stream(orow + ov, pack_vec<BF16>(acc[i]));
+                    }
                 }
             } else {
                 for (int64_t o = sub; o < a.O; o += LPT) {
@@ -258,8 +289,8 @@ DeviceInfo device_info() {
 WalkTuning g_walk_tuning;
 namespace {
 
-template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED>
-hipError_t run_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT>
+hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     constexpr int kGroups = kWalkBlock / LPT;
     const DeviceInfo di = device_info();
     const int64_t tile = (int64_t)kGroups * TPG;
@@ -279,7 +310,7 @@ hipError_t run_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     }
     if (g_walk_tuning.top > 0 && g_walk_tuning.top - 1 < top) top = (int)g_walk_tuning.top - 1;
     const size_t lds_bytes = (size_t)(((int64_t)1 << top) - 1) * (row_bytes + 4);
-    auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED>;
+    auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED, TIGHT>;
     if (lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
@@ -305,6 +336,15 @@ hipError_t run_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     a.out_vec = FUSED && vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
     kern<<<dim3((unsigned)blocks), dim3(kWalkBlock), lds_bytes, s>>>(a);
     return hipGetLastError();
+}
+
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED>
+hipError_t run_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+    const int64_t per = Elem<BF16>::kPerVec;
+    const bool out_vec = FUSED && vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
+    const bool tight = p.D == per * LPT * NV && (!FUSED || !out_vec || p.O == per * LPT * NV);
+    return tight ? run_walk_t<BF16, LPT, NV, TPG, kWalkBlock, FUSED, true>(p, leaf_idx, s)
+                 : run_walk_t<BF16, LPT, NV, TPG, kWalkBlock, FUSED, false>(p, leaf_idx, s);
 }
 
 template <bool BF16, bool FUSED>

@@ -10,6 +10,22 @@ from fff_testlib import check_against_oracle, oracle_inputs, out_to_f64, run_for
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(scope="module")
+def c5_workload():
+    """Built once: drawing 1.3e9 weights takes a while."""
+    import torch
+    w = W.config("C5", keep_f32=False)
+    dev = to_device(w)
+    ref = oracle.forward_hard(*oracle_inputs(w), w.depth, w.leaf_width, w.act)
+    # margin tokens are validated against the fp32 view of the node tensors only
+    w.f32["x"] = W.bf16_widen(w.bits["x"])
+    w.f32["node_w"] = W.bf16_widen(w.bits["node_w"])
+    w.f32["node_b"] = W.bf16_widen(w.bits["node_b"])
+    yield w, dev, ref
+    del dev
+    torch.cuda.empty_cache()
+
+
 def _log(name, stats):
     print("\n[parity] %s: %s" % (name, stats), flush=True)
 
@@ -20,6 +36,20 @@ def test_named_workloads(name):
     w = W.config(name)
     out, idx = run_forward(w)
     _log(name, check_against_oracle(w, out, idx))
+
+
+@pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
+def test_large_skewed_workload(path, c5_workload):
+    """C5 at full size (2.4 GB of leaf weights, Zipf leaf occupancy), both launch configurations."""
+    import paper_2308_14711_amd as F
+    print("\n[case] workload C5 seed 0 path=%d" % path, flush=True)
+    w, dev, ref = c5_workload
+    F.fff_set_option("path", path)
+    try:
+        out, idx = run_forward(w, dev)
+    finally:
+        F.fff_set_option("path", 0)
+    _log("C5 path=%d" % path, check_against_oracle(w, out, idx, ref=ref))
 
 
 SMALL = [
@@ -165,6 +195,9 @@ def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
         li = np.full(T, NL - 1, np.int32)
     count, offset, perm = oracle.bucket(li, depth)
     d_li = torch.from_numpy(li).cuda()
+    if T % 2 == 1:           # odd sizes also come in through a pointer that is only 4-byte aligned
+        d_li = torch.cat([torch.zeros(1, dtype=torch.int32, device="cuda"), d_li])[1:]
+        assert d_li.data_ptr() % 16 != 0
     d_count = torch.full((NL,), -1, dtype=torch.int32, device="cuda")
     d_offset = torch.full((NL + 1,), -1, dtype=torch.int32, device="cuda")
     d_perm = torch.full((T,), -1, dtype=torch.int32, device="cuda")
