@@ -3,7 +3,7 @@
 // feedforward block; Algorithm 1 returns its output), with every output row
 // written straight to its token's position.
 //
-// Tokens arrive grouped by leaf (perm from the bucketing stage).  A wave owns a
+// Tokens arrive grouped by leaf (perm from the bucketing stage).  A block owns a
 // tile of 16 consecutive slots of perm.  Inside a tile the slots form runs of
 // equal leaf; because a leaf has few neurons, several runs share one MFMA:
 //
@@ -12,6 +12,8 @@
 //       cols  = the 16 tokens                              -> x[token][:]
 //       C[(r, n)][token] is a hidden pre-activation wherever the token belongs
 //       to run r; the other entries are discarded (set to zero).
+//       The W waves of the block each take every W-th pair of K steps; the
+//       partial C tiles are summed through LDS.
 //   second contraction (v_mfma_f32_16x16x32_bf16, K = 32 slots)
 //       A     = the activated, masked C of the first contraction -- it is
 //               already in the lanes and registers the instruction wants --
@@ -19,6 +21,7 @@
 //       B     = W2[leaf_r][n][o] for the first 16 slots, b2[leaf_r][o] for the
 //               spare ones, so the bias rides in the same instruction
 //       D[token][o] = sum_n h[token][n] W2[leaf(token)][n][o] + b2[leaf(token)][o]
+//       The waves each take every W-th 64-wide range of o.
 //
 // A tile with more than 16 / l runs takes several passes.  W2 is stored with o
 // contiguous (per neuron, its O output weights), while the instruction wants K
@@ -45,16 +48,16 @@ struct TilesArgs {
     int D, O, L, act;
 };
 
-constexpr int kChunk = 12;   // K steps of the first contraction in flight per lane
-constexpr int kRanges = 4;   // 64-wide output ranges of the second contraction in flight per lane
+constexpr int kChunk = 8;    // K steps of the first contraction in flight per lane
+constexpr int kRanges = 2;   // 64-wide output ranges of the second contraction in flight per lane
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
-__global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= a.n_tiles) return;          // whole waves leave; nothing below synchronises the block
+__global__ __launch_bounds__(512) void leaf_tiles_kernel(const TilesArgs a) {
+    extern __shared__ f32x4_t part[];        // [2][W][64] partial tiles of the first contraction
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
+    const int64_t tile = blockIdx.x;
     const int j = lane & 15, kg = lane >> 4;
     const int D = a.D, O = a.O, L = a.L;
     const int P = 16 / L;                    // runs per pass
@@ -86,9 +89,10 @@ __global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
         n_q[q] = (4 * kg + q) % L;
     }
     const uint16_t* xrow = a.x + (int64_t)tok * D;
-    const int nk = 2 * ((D + 63) / 64);
+    const int n_pairs = (D + 63) / 64;       // pairs of K steps (64 elements of a row each)
 
-    for (int pass = 0; pass < n_runs; pass += P) {
+    int buf = 0;
+    for (int pass = 0; pass < n_runs; pass += P, buf ^= 1) {
         // leaf of every run of this pass, handed to the lanes that need it
         int32_t row_leaf = -1, w2_leaf[4] = {-1, -1, -1, -1}, b2_leaf[4] = {-1, -1, -1, -1};
         for (int rr = 0; rr < P && pass + rr < n_runs; ++rr) {
@@ -103,18 +107,17 @@ __global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
         }
 
         // first contraction over D.  The K index is only a summation order, so step s gives
-        // lane group kg the 8 elements at 64 (s / 2) + 16 kg + 8 (s % 2): two consecutive steps
+        // lane group kg the 8 elements at 64 (s / 2) + 16 kg + 8 (s % 2): the two steps of a pair
         // read 32 contiguous bytes per lane and the four lane groups cover a whole 128-byte line.
-        // kChunk steps are fetched before any is consumed so that the loads overlap.
+        // This wave takes pairs wave, wave + W, ...; kChunk steps are fetched before any is used.
         const uint16_t* arow = a.w1 + ((int64_t)(row_leaf >= 0 ? row_leaf : 0) * L + n_i) * D;
         const bool a_ok = row_leaf >= 0;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        for (int s0 = 0; s0 < nk; s0 += kChunk) {
+        for (int p0 = wave; p0 < n_pairs; p0 += W * (kChunk / 2)) {
             uint4 av[kChunk], bv[kChunk];
 #pragma unroll
             for (int u = 0; u < kChunk; ++u) {
-                const int s = s0 + u;
-                const int k0 = 64 * (s >> 1) + 16 * kg + 8 * (s & 1);
+                const int k0 = 64 * (p0 + W * (u >> 1)) + 16 * kg + 8 * (u & 1);
                 av[u] = make_uint4(0, 0, 0, 0);
                 bv[u] = make_uint4(0, 0, 0, 0);
                 if (a_ok && k0 < D) av[u] = *(const uint4*)(arow + k0);
@@ -125,6 +128,12 @@ __global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
                                                               __builtin_bit_cast(bf16x8_t, bv[u]), acc, 0, 0, 0);
         }
+        // sum the partial tiles of the W waves (two buffers, so one barrier per pass is enough)
+        f32x4_t* mine_part = part + (buf * W) * 64;
+        mine_part[wave * 64 + lane] = acc;
+        __syncthreads();
+        acc = mine_part[lane];
+        for (int w = 1; w < W; ++w) acc += mine_part[w * 64 + lane];
 
         // activation, mask to the token's own run, append the run indicators
         float hq[4], iq[4];
@@ -152,11 +161,11 @@ __global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
 
         // second contraction, 64 outputs per step; the rows of kRanges steps are fetched before
         // the first of them is multiplied, so their latencies overlap
-        for (int og = 4 * j; og < O + 4 * j; og += 64 * kRanges) {
+        for (int og = 4 * j + 64 * wave; og < O + 4 * j; og += 64 * kRanges * W) {
             uint2 wv[kRanges][4], bv2[kRanges][4];
 #pragma unroll
             for (int g = 0; g < kRanges; ++g) {
-                const int o0 = og + 64 * g;
+                const int o0 = og + 64 * W * g;
                 const bool ok = o0 < O;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -166,7 +175,7 @@ __global__ __launch_bounds__(256) void leaf_tiles_kernel(const TilesArgs a) {
             }
 #pragma unroll
             for (int g = 0; g < kRanges; ++g) {
-                const int o0 = og + 64 * g;
+                const int o0 = og + 64 * W * g;
                 const uint2* w = wv[g];
                 const uint2* b = bv2[g];
                 const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
@@ -220,8 +229,13 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* leaf_idx, const in
     a.O = (int)p.O;
     a.L = p.L;
     a.act = p.act;
-    const int64_t blocks = (a.n_tiles + 3) / 4;
-    leaf_tiles_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
+    // waves per tile: enough that a wave's share is a few K-step pairs and output ranges
+    const int64_t n_pairs = (p.D + 63) / 64, n_ranges = (p.O + 63) / 64;
+    const int64_t big = n_pairs > n_ranges ? n_pairs : n_ranges;
+    int W = 4;
+    while (W < 8 && big > 4 * W) W *= 2;
+    const size_t lds = sizeof(float) * 4 * 64 * 2 * (size_t)W;
+    leaf_tiles_kernel<<<dim3((unsigned)a.n_tiles), dim3(64 * W), lds, s>>>(a);
     return hipGetLastError();
 }
 

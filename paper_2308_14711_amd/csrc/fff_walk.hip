@@ -367,7 +367,14 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     }
     if (nvec <= 128) return run_walk<BF16, 16, 8, 2, 512, FUSED>(p, leaf_idx, s);
     if (nvec <= 256) return run_walk<BF16, 64, 4, 2, 1024, FUSED>(p, leaf_idx, s);
-    if (nvec <= 512) return run_walk<BF16, 64, 8, 2, 512, FUSED>(p, leaf_idx, s);
+    if (nvec <= 512) {
+        const int64_t tpg = g_walk_tuning.tpg, blk = g_walk_tuning.block;
+        if (tpg == 1 && blk == 1024) return run_walk<BF16, 64, 8, 1, 1024, FUSED>(p, leaf_idx, s);
+        if (tpg == 3 && blk == 512) return run_walk<BF16, 64, 8, 3, 512, FUSED>(p, leaf_idx, s);
+        if (tpg == 4 && blk == 256) return run_walk<BF16, 64, 8, 4, 256, FUSED>(p, leaf_idx, s);
+        if (tpg == 6 && blk == 256) return run_walk<BF16, 64, 8, 6, 256, FUSED>(p, leaf_idx, s);
+        return run_walk<BF16, 64, 8, 2, 512, FUSED>(p, leaf_idx, s);
+    }
     return run_walk<BF16, 64, 16, 1, 512, FUSED>(p, leaf_idx, s);
 }
 
