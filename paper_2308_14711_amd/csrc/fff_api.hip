@@ -218,7 +218,8 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
     const int rc = run_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, s);
     if (rc != FFF_OK) return rc;
     if (timed) stage_mark(s);
-    if (g_opt.leaf_path != 1 && tiles_shape_ok(p))
+    // the MFMA tile path pays once a leaf has a few neurons; for 1-2 the VALU gather kernel is leaner
+    if (g_opt.leaf_path != 1 && tiles_shape_ok(p) && (p.L >= 3 || g_opt.leaf_path == 2))
         e = launch_leaf_tiles(p, leaf_idx, ws.perm, s);
     else
         e = launch_leaf_gather(p, leaf_idx, ws.perm, s);

@@ -48,39 +48,34 @@ struct TilesArgs {
     int D, O, L, act;
 };
 
-constexpr int kChunk = 8;    // K steps of the first contraction in flight per lane
-constexpr int kRanges = 2;   // 64-wide output ranges of the second contraction in flight per lane
+constexpr int kChunk = 6;    // K steps of the first contraction fetched per lane per group (3 pairs)
+constexpr int kPre = 1;      // 128-wide output ranges of the second contraction fetched ahead of the first
 
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+// the c-th bf16 of the 8 held by a 16-byte vector, for the 4x4 (here 4x8) register transposes
+__device__ __forceinline__ uint32_t dword_of(const uint4& v, int c) {
+    return (c >> 1) == 0 ? v.x : (c >> 1) == 1 ? v.y : (c >> 1) == 2 ? v.z : v.w;
+}
+__device__ __forceinline__ uint32_t pack_half(uint32_t a, uint32_t b, int hi) {
+    return hi ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+}
 
-__global__ __launch_bounds__(512) void leaf_tiles_kernel(const TilesArgs a) {
-    extern __shared__ f32x4_t part[];        // [2][W][64] partial tiles of the first contraction
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
-    const int64_t tile = blockIdx.x;
+// Blocks are persistent and software-pipelined over work items (tile, pass): while the item at
+// hand is reduced, activated, multiplied by W2 and stored, the token rows and W1 rows of the next
+// item are already in flight, and so are the slot -> token -> leaf lookups of the tiles after it.
+// Loads return in issue order, so within an item the W2 / b2 rows are requested first, then the
+// next item's rows: waiting for the former never waits for the latter.
+// W = waves per block (compile time, so that the strides between a wave's K pairs and output
+// ranges are immediates).  DTAIL = D is not a multiple of 64 (lanes then check their K offset).
+template <int W, bool DTAIL>
+__global__ __launch_bounds__(64 * W) void leaf_tiles_kernel(const TilesArgs a) {
+    __shared__ f32x4_t part[2 * W * 64];     // [2][W][64] partial tiles of the first contraction
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 15, kg = lane >> 4;
     const int D = a.D, O = a.O, L = a.L;
     const int P = 16 / L;                    // runs per pass
+    const int n_pairs = (D + 63) / 64;       // pairs of K steps (64 elements of a row each)
+    const int64_t G = gridDim.x;
 
-    // this lane's column: slot, token, leaf (all four 16-lane rows hold the same 16 columns)
-    const int64_t slot = tile * 16 + j;
-    const bool vj = slot < a.T;
-    const int32_t tok = vj ? a.perm[slot] : 0;
-    const int32_t leaf = vj ? a.leaf_idx[tok] : -1;
-    const int32_t prev = __shfl_up(leaf, 1, 16);
-    const uint32_t ch16 = (uint32_t)__ballot(vj && j > 0 && leaf != prev) & 0xffffu;
-    const int run_j = __popc(ch16 & ((2u << j) - 1u));
-    const int n_runs = __popc(ch16) + 1;
-
-    // token rows this lane stores at the end: rows 4 kg + q
-    int32_t tok_row[4], run_row[4];
-    bool v_row[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        tok_row[q] = __shfl(tok, 4 * kg + q, 64);
-        run_row[q] = __shfl(run_j, 4 * kg + q, 64);
-        v_row[q] = tile * 16 + 4 * kg + q < a.T;
-    }
     const int rr_i = j / L, n_i = j % L;     // A row j of the first contraction = (run rr_i of the pass, neuron n_i)
     int rr_q[4], n_q[4];                      // K slots 4 kg + q of the second contraction, same pairing
 #pragma unroll
@@ -88,15 +83,30 @@ __global__ __launch_bounds__(512) void leaf_tiles_kernel(const TilesArgs a) {
         rr_q[q] = (4 * kg + q) / L;
         n_q[q] = (4 * kg + q) % L;
     }
-    const uint16_t* xrow = a.x + (int64_t)tok * D;
-    const int n_pairs = (D + 63) / 64;       // pairs of K steps (64 elements of a row each)
 
-    int buf = 0;
-    for (int pass = 0; pass < n_runs; pass += P, buf ^= 1) {
-        // leaf of every run of this pass, handed to the lanes that need it
-        int32_t row_leaf = -1, w2_leaf[4] = {-1, -1, -1, -1}, b2_leaf[4] = {-1, -1, -1, -1};
+    // slot -> token and token -> leaf of this lane's column (all four 16-lane rows hold the same
+    // 16 columns); -1 marks a slot past the end
+    auto load_tok = [&](int64_t tile) -> int32_t {
+        const int64_t slot = tile * 16 + j;
+        return (tile < a.n_tiles && slot < a.T) ? a.perm[slot] : -1;
+    };
+    auto load_leaf = [&](int32_t tok) -> int32_t { return tok >= 0 ? a.leaf_idx[tok] : -1; };
+    // runs of equal leaf inside a tile: run index of this lane's column, and the number of runs
+    auto derive = [&](int32_t leaf, int& run_j, int& n_runs) {
+        const int32_t prev = __shfl_up(leaf, 1, 16);
+        const uint32_t ch16 = (uint32_t)__ballot(leaf >= 0 && j > 0 && leaf != prev) & 0xffffu;
+        run_j = __popc(ch16 & ((2u << j) - 1u));
+        n_runs = __popc(ch16) + 1;
+    };
+    // leaf of every run of a pass, handed to the lanes that need it
+    auto pass_leaves = [&](int32_t leaf, int run_j, int n_runs, int pass, int32_t& row_leaf,
+                           int32_t (&w2_leaf)[4], int32_t (&b2_leaf)[4]) {
+        row_leaf = -1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w2_leaf[q] = b2_leaf[q] = -1;
         for (int rr = 0; rr < P && pass + rr < n_runs; ++rr) {
-            const uint32_t m = (uint32_t)__ballot(vj && run_j == pass + rr) & 0xffffu;
+            const uint32_t m = (uint32_t)__ballot(leaf >= 0 && run_j == pass + rr) & 0xffffu;
+            if (m == 0) break;                     // a tile past the end has no runs
             const int32_t lf = __shfl(leaf, __ffs(m) - 1, 64);
             if (rr_i == rr) row_leaf = lf;
 #pragma unroll
@@ -105,111 +115,217 @@ __global__ __launch_bounds__(512) void leaf_tiles_kernel(const TilesArgs a) {
                 if (4 * kg + q == rr) b2_leaf[q] = lf;
             }
         }
-
-        // first contraction over D.  The K index is only a summation order, so step s gives
-        // lane group kg the 8 elements at 64 (s / 2) + 16 kg + 8 (s % 2): the two steps of a pair
-        // read 32 contiguous bytes per lane and the four lane groups cover a whole 128-byte line.
-        // This wave takes pairs wave, wave + W, ...; kChunk steps are fetched before any is used.
-        const uint16_t* arow = a.w1 + ((int64_t)(row_leaf >= 0 ? row_leaf : 0) * L + n_i) * D;
-        const bool a_ok = row_leaf >= 0;
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        for (int p0 = wave; p0 < n_pairs; p0 += W * (kChunk / 2)) {
-            uint4 av[kChunk], bv[kChunk];
+    };
+    // First contraction.  The K index is only a summation order, so step u of pair pp gives lane
+    // group kg the 8 elements at 64 pp + 16 kg + 8 u: the two steps of a pair read 32 contiguous
+    // bytes per lane and the four lane groups cover a whole 128-byte line.  This wave takes pairs
+    // wave, wave + W, ...; group g of them is pairs wave + W (3 g + {0, 1, 2}).
+    auto fetch_chunk = [&](int32_t tok, int32_t row_leaf, int g, uint4* av, uint4* bv) {
+        const uint16_t* xrow = a.x + (int64_t)(tok >= 0 ? tok : 0) * D + 16 * kg;
+        const uint16_t* arow = a.w1 + ((int64_t)(row_leaf >= 0 ? row_leaf : 0) * L + n_i) * D + 16 * kg;
+        const int pp0 = wave + W * (kChunk / 2) * g;
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
-                const int k0 = 64 * (p0 + W * (u >> 1)) + 16 * kg + 8 * (u & 1);
-                av[u] = make_uint4(0, 0, 0, 0);
-                bv[u] = make_uint4(0, 0, 0, 0);
-                if (a_ok && k0 < D) av[u] = *(const uint4*)(arow + k0);
-                if (vj && k0 < D) bv[u] = *(const uint4*)(xrow + k0);
+        for (int u = 0; u < kChunk; ++u) {
+            av[u] = make_uint4(0, 0, 0, 0);
+            bv[u] = make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            const int pp = pp0 + W * (u >> 1);                // wave-uniform
+            const int k0 = 64 * pp + 8 * (u & 1);             // + 16 kg is in the row pointers
+            const bool in = pp < n_pairs && (!DTAIL || k0 + 16 * kg < D);
+            if (in && row_leaf >= 0) av[u] = *(const uint4*)(arow + k0);
+            if (in && tok >= 0) bv[u] = *(const uint4*)(xrow + k0);
+        }
+    };
+    const int n_groups = (n_pairs - wave + W * (kChunk / 2) - 1) / (W * (kChunk / 2));   // <= 0: nothing for this wave
+
+    // metadata of the tile at hand (A), the next (B), and the token of the one after (C)
+    int64_t tile = blockIdx.x;
+    int32_t tokA = load_tok(tile), tokB = load_tok(tile + G), tokC = load_tok(tile + 2 * G);
+    int32_t leafA = load_leaf(tokA), leafB = load_leaf(tokB);
+    int run_j, n_runs, pass = 0;
+    derive(leafA, run_j, n_runs);
+    int32_t row_leaf, w2_leaf[4], b2_leaf[4];
+    pass_leaves(leafA, run_j, n_runs, 0, row_leaf, w2_leaf, b2_leaf);
+    uint4 av[kChunk], bv[kChunk];
+    fetch_chunk(tokA, row_leaf, 0, av, bv);
+
+    int buf = 0;
+    while (tile < a.n_tiles) {
+        // ---- rows of the second contraction for this item (requested before anything else).
+        // A lane holds K rows 4 kg + q (W2 rows of (run, neuron) pairs, then b2 rows of runs) and
+        // 8 consecutive outputs o0 .. o0 + 7 of a 128-wide range; rows that stand for nothing
+        // are read from row 0 (always there) and zeroed.
+        const uint16_t* wptr[4];
+        const uint16_t* bptr[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            wptr[q] = a.w2 + ((int64_t)(w2_leaf[q] >= 0 ? w2_leaf[q] : 0) * L + n_q[q]) * O + 8 * j;
+            bptr[q] = a.b2 + (int64_t)(b2_leaf[q] >= 0 ? b2_leaf[q] : 0) * O + 8 * j;
+        }
+        auto fetch_range = [&](int r, uint4* w, uint4* b) {      // r: index of a 128-wide range
+            const int o0 = 128 * r;
+            const bool ok = o0 + 8 * j < O;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                w[q] = make_uint4(0, 0, 0, 0);
+                b[q] = make_uint4(0, 0, 0, 0);
+                if (ok && w2_leaf[q] >= 0) w[q] = *(const uint4*)(wptr[q] + o0);
+                if (ok && b2_leaf[q] >= 0) b[q] = *(const uint4*)(bptr[q] + o0);
             }
+        };
+        uint4 wpre[kPre][4], bpre[kPre][4];
+#pragma unroll
+        for (int g = 0; g < kPre; ++g) fetch_range(wave + W * g, wpre[g], bpre[g]);
+
+        // ---- first contraction: the group in registers, then any further groups
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
+                                                          __builtin_bit_cast(bf16x8_t, bv[u]), acc, 0, 0, 0);
+        for (int g = 1; g < n_groups; ++g) {
+            fetch_chunk(tokA, row_leaf, g, av, bv);
 #pragma unroll
             for (int u = 0; u < kChunk; ++u)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
                                                               __builtin_bit_cast(bf16x8_t, bv[u]), acc, 0, 0, 0);
         }
-        // sum the partial tiles of the W waves (two buffers, so one barrier per pass is enough)
+
+        // ---- the next item: another pass over this tile, or the first pass of the next tile
+        const bool same_tile = pass + P < n_runs;
+        int32_t n_row_leaf, n_w2_leaf[4], n_b2_leaf[4];
+        int n_run_j = run_j, n_n_runs = n_runs;
+        if (same_tile) {
+            pass_leaves(leafA, run_j, n_runs, pass + P, n_row_leaf, n_w2_leaf, n_b2_leaf);
+            fetch_chunk(tokA, n_row_leaf, 0, av, bv);
+        } else {
+            derive(leafB, n_run_j, n_n_runs);
+            pass_leaves(leafB, n_run_j, n_n_runs, 0, n_row_leaf, n_w2_leaf, n_b2_leaf);
+            fetch_chunk(tokB, n_row_leaf, 0, av, bv);       // all-invalid past the last tile: no loads
+        }
+        int32_t leafC = -1, tokD = -1;
+        if (!same_tile) {
+            leafC = load_leaf(tokC);
+            tokD = load_tok(tile + 3 * G);
+        }
+
+        // ---- sum the partial tiles of the W waves (two buffers, so one barrier per item is enough)
         f32x4_t* mine_part = part + (buf * W) * 64;
         mine_part[wave * 64 + lane] = acc;
         __syncthreads();
         acc = mine_part[lane];
+#pragma unroll
         for (int w = 1; w < W; ++w) acc += mine_part[w * 64 + lane];
 
-        // activation, mask to the token's own run, append the run indicators
+        // ---- activation, mask to the token's own run, append the run indicators
         float hq[4], iq[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const bool mine = vj && rr_q[q] < P && run_j == pass + rr_q[q];
+            const bool mine = leafA >= 0 && rr_q[q] < P && run_j == pass + rr_q[q];
             float v = 0.f;
-            if (mine) v = activate(acc[q] + bf16_to_f32(a.b1[(int64_t)leaf * L + n_q[q]]), a.act);
+            if (mine) v = activate(acc[q] + bf16_to_f32(a.b1[(int64_t)leafA * L + n_q[q]]), a.act);
             hq[q] = v;
-            iq[q] = (vj && 4 * kg + q < P && run_j == pass + 4 * kg + q) ? 1.0f : 0.0f;
+            iq[q] = (leafA >= 0 && 4 * kg + q < P && run_j == pass + 4 * kg + q) ? 1.0f : 0.0f;
         }
         const uint4 a2u = make_uint4(pack_bf16x2(hq[0], hq[1]), pack_bf16x2(hq[2], hq[3]),
                                      pack_bf16x2(iq[0], iq[1]), pack_bf16x2(iq[2], iq[3]));
         const bf16x8_t a2 = __builtin_bit_cast(bf16x8_t, a2u);
 
-        const uint16_t* wptr[4];
-        const uint16_t* bptr[4];
+        // ---- second contraction and the output rows of the tokens of this pass.  Column j of the
+        // c-th MFMA of a range stands for output o0 + 8 j + c, so a lane ends with 8 consecutive
+        // outputs of each of its 4 token rows: one 16-byte store per row.
+        uint16_t* orow[4];
         bool st_ok[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            wptr[q] = w2_leaf[q] >= 0 ? a.w2 + ((int64_t)w2_leaf[q] * L + n_q[q]) * O : nullptr;
-            bptr[q] = b2_leaf[q] >= 0 ? a.b2 + (int64_t)b2_leaf[q] * O : nullptr;
-            st_ok[q] = v_row[q] && run_row[q] >= pass && run_row[q] < pass + P;
+            const int32_t tq = __shfl(tokA, 4 * kg + q, 64);
+            const int rrow = __shfl(run_j, 4 * kg + q, 64);
+            st_ok[q] = tq >= 0 && rrow >= pass && rrow < pass + P;
+            orow[q] = a.out + (int64_t)(tq >= 0 ? tq : 0) * O + 8 * j;
         }
-
-        // second contraction, 64 outputs per step; the rows of kRanges steps are fetched before
-        // the first of them is multiplied, so their latencies overlap
-        for (int og = 4 * j + 64 * wave; og < O + 4 * j; og += 64 * kRanges * W) {
-            uint2 wv[kRanges][4], bv2[kRanges][4];
+        auto mul_store = [&](const uint4* w, const uint4* b, int r) {
+            const int o0 = 128 * r;
+            const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+            f32x4_t d[8];
 #pragma unroll
-            for (int g = 0; g < kRanges; ++g) {
-                const int o0 = og + 64 * W * g;
-                const bool ok = o0 < O;
+            for (int c = 0; c < 8; ++c) {
+                const uint4 f = make_uint4(pack_half(dword_of(w[0], c), dword_of(w[1], c), c & 1),
+                                           pack_half(dword_of(w[2], c), dword_of(w[3], c), c & 1),
+                                           pack_half(dword_of(b[0], c), dword_of(b[1], c), c & 1),
+                                           pack_half(dword_of(b[2], c), dword_of(b[3], c), c & 1));
+                d[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f), zero, 0, 0, 0);
+            }
+            if (o0 + 8 * j < O) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    wv[g][q] = (wptr[q] && ok) ? *(const uint2*)(wptr[q] + o0) : make_uint2(0, 0);
-                    bv2[g][q] = (bptr[q] && ok) ? *(const uint2*)(bptr[q] + o0) : make_uint2(0, 0);
-                }
-            }
-#pragma unroll
-            for (int g = 0; g < kRanges; ++g) {
-                const int o0 = og + 64 * W * g;
-                const uint2* w = wv[g];
-                const uint2* b = bv2[g];
-                const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
-                const uint4 f0 = make_uint4(pack_lo(w[0].x, w[1].x), pack_lo(w[2].x, w[3].x),
-                                            pack_lo(b[0].x, b[1].x), pack_lo(b[2].x, b[3].x));
-                const uint4 f1 = make_uint4(pack_hi(w[0].x, w[1].x), pack_hi(w[2].x, w[3].x),
-                                            pack_hi(b[0].x, b[1].x), pack_hi(b[2].x, b[3].x));
-                const uint4 f2 = make_uint4(pack_lo(w[0].y, w[1].y), pack_lo(w[2].y, w[3].y),
-                                            pack_lo(b[0].y, b[1].y), pack_lo(b[2].y, b[3].y));
-                const uint4 f3 = make_uint4(pack_hi(w[0].y, w[1].y), pack_hi(w[2].y, w[3].y),
-                                            pack_hi(b[0].y, b[1].y), pack_hi(b[2].y, b[3].y));
-                const f32x4_t d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f0), zero, 0, 0, 0);
-                const f32x4_t d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f1), zero, 0, 0, 0);
-                const f32x4_t d2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f2), zero, 0, 0, 0);
-                const f32x4_t d3 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f3), zero, 0, 0, 0);
-                if (o0 < O) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        if (st_ok[q]) {
-                            const uint2 o2 = make_uint2(pack_bf16x2(d0[q], d1[q]), pack_bf16x2(d2[q], d3[q]));
-                            *(uint2*)(a.out + (int64_t)tok_row[q] * O + o0) = o2;
-                        }
+                    if (st_ok[q]) {
+                        const uint4 o4 = make_uint4(pack_bf16x2(d[0][q], d[1][q]), pack_bf16x2(d[2][q], d[3][q]),
+                                                    pack_bf16x2(d[4][q], d[5][q]), pack_bf16x2(d[6][q], d[7][q]));
+                        store_stream((uint4*)(orow[q] + o0), o4);
                     }
                 }
             }
+        };
+#pragma unroll
+        for (int g = 0; g < kPre; ++g) mul_store(wpre[g], bpre[g], wave + W * g);
+        for (int r = wave + W * kPre; 128 * r < O; r += W) {
+            uint4 wv[4], bv2[4];
+            fetch_range(r, wv, bv2);
+            mul_store(wv, bv2, r);
         }
+
+        // ---- move on
+        row_leaf = n_row_leaf;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            w2_leaf[q] = n_w2_leaf[q];
+            b2_leaf[q] = n_b2_leaf[q];
+        }
+        if (same_tile) {
+            pass += P;
+        } else {
+            pass = 0;
+            run_j = n_run_j;
+            n_runs = n_n_runs;
+            tile += G;
+            tokA = tokB; leafA = leafB;
+            tokB = tokC; leafB = leafC;
+            tokC = tokD;
+        }
+        buf ^= 1;
     }
 }
 
-// bf16, leaf width <= 16, rows of x / W1 16-byte aligned, rows of W2 / b2 / out 8-byte aligned
+// bf16, leaf width <= 16, 16-byte aligned rows of x, W1, W2, b2 and out
 bool tiles_shape_ok(const Problem& p) {
     auto al = [](const void* q, uintptr_t m) { return (reinterpret_cast<uintptr_t>(q) & (m - 1)) == 0; };
-    return p.bf16 && p.L <= 16 && p.D % 8 == 0 && p.O % 4 == 0 && p.D < (1 << 30) && p.O < (1 << 30) &&
-           al(p.x, 16) && al(p.leaf_w1, 16) && al(p.leaf_w2, 8) && al(p.leaf_b2, 8) && al(p.out, 8);
+    return p.bf16 && p.L <= 16 && p.D % 8 == 0 && p.O % 8 == 0 && p.D < (1 << 30) && p.O < (1 << 30) &&
+           al(p.x, 16) && al(p.leaf_w1, 16) && al(p.leaf_w2, 16) && al(p.leaf_b2, 16) && al(p.out, 16);
+}
+
+template <int W, bool DTAIL>
+static hipError_t run_tiles(const TilesArgs& a, hipStream_t s) {
+    // persistent blocks: as many as fit on the chip at once
+    static int per_cu = 0, cus = 0;
+    if (per_cu == 0) {
+        int dev = 0, n = 0;
+        hipDeviceProp_t prop;
+        cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            prop.multiProcessorCount > 0)
+            cus = prop.multiProcessorCount;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, leaf_tiles_kernel<W, DTAIL>, 64 * W, 0) != hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            n = 1;
+        }
+        per_cu = n;
+    }
+    int64_t blocks = (int64_t)cus * per_cu;
+    if (blocks > a.n_tiles) blocks = a.n_tiles;
+    leaf_tiles_kernel<W, DTAIL><<<dim3((unsigned)blocks), dim3(64 * W), 0, s>>>(a);
+    return hipGetLastError();
 }
 
 hipError_t launch_leaf_tiles(const Problem& p, const int32_t* leaf_idx, const int32_t* perm, hipStream_t s) {
@@ -230,13 +346,11 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* leaf_idx, const in
     a.L = p.L;
     a.act = p.act;
     // waves per tile: enough that a wave's share is a few K-step pairs and output ranges
-    const int64_t n_pairs = (p.D + 63) / 64, n_ranges = (p.O + 63) / 64;
-    const int64_t big = n_pairs > n_ranges ? n_pairs : n_ranges;
-    int W = 4;
-    while (W < 8 && big > 4 * W) W *= 2;
-    const size_t lds = sizeof(float) * 4 * 64 * 2 * (size_t)W;
-    leaf_tiles_kernel<<<dim3((unsigned)a.n_tiles), dim3(64 * W), lds, s>>>(a);
-    return hipGetLastError();
+    const int64_t n_pairs = (p.D + 63) / 64, n_ranges = (p.O + 127) / 128;
+    const bool wide = n_pairs > 24 || n_ranges > 16;
+    const bool dtail = p.D % 64 != 0;
+    if (wide) return dtail ? run_tiles<8, true>(a, s) : run_tiles<8, false>(a, s);
+    return dtail ? run_tiles<4, true>(a, s) : run_tiles<4, false>(a, s);
 }
 
 }  // namespace fff
