@@ -24,6 +24,16 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 
+# HBM-side bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/ (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0, the factors a plain device
+# copy of known size reads there).  Keyed by (workload, launch path, kernel); None where not measured.
+MEASURED_TRAFFIC = {
+    ("C4", "fused", "walk_fused"): 533.2e6,    # profiles/bert_base_fff_fused_C4.md
+    ("C3", "staged", "leaf"): 211.9e6,         # profiles/vit_block_fff_staged_C3.md
+    ("C3", "staged", "descent"): 80.9e6,
+    ("C5", "fused", "walk_fused"): 1646.5e6,   # profiles/large_skewed_fff_fused_C5.md
+}
+
 
 def algorithmic_bytes(w, ref_idx):
     """Bytes the method itself must move: x once, out once, leaf_idx, and every
@@ -154,8 +164,10 @@ def main():
     dom = max(stages, key=lambda k: stages[k]["avg_ms"]) if stages else None
     roofline = None
     if dom:
+        launch = path_names.get(F.fff_get_option("last_path"), "?")
+        traffic = None if args.opt else MEASURED_TRAFFIC.get((w.name, launch, dom))
         roofline = {"bound": "hbm", "kernel": dom, "achieved": stages[dom]["GBps"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": stages[dom]["frac"], "traffic": None}
+                    "unit": "GB/s", "frac": stages[dom]["frac"], "traffic": traffic}
     path_gbs = alg["path"] / (ms_per_step * 1e-3) / 1e9
 
     # parity spot check of the timed configuration against the oracle

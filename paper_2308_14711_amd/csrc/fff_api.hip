@@ -359,6 +359,7 @@ static int64_t* option_slot(const char* name) {
     if (!std::strcmp(name, "walk_block")) return &g_walk_tuning.block;
     if (!std::strcmp(name, "walk_top")) return &g_walk_tuning.top;
     if (!std::strcmp(name, "walk_bpc")) return &g_walk_tuning.bpc;
+    if (!std::strcmp(name, "walk_prefetch")) return &g_walk_tuning.prefetch;
     if (!std::strcmp(name, "bucketing")) return &g_opt.bucketing;
     if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;

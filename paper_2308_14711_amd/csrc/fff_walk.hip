@@ -76,7 +76,7 @@ struct WalkArgs {
 
 // FUSED = false: writes leaf_idx only.  FUSED = true: also the leaf network (L <= 8).
 // TIGHT: D (and, when FUSED with vector output, O) is exactly LPT * NV vectors.
-template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT>
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT, bool PREFETCH>
 __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
     extern __shared__ uint4 lds[];                 // [(2^top - 1) * nvec] rows, then (2^top - 1) biases
     constexpr int kGroups = kWalkBlock / LPT;
@@ -94,21 +94,39 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
     const int64_t tile = (int64_t)kGroups * TPG;
     const int n_nodes = (1 << a.depth) - 1;
 
-    for (int64_t base = (int64_t)blockIdx.x * tile; base < a.T; base += (int64_t)gridDim.x * tile) {
+    // token rows of a tile: row of token base + g TPG + k goes to xr[k] (clamped past the end)
+    auto fetch_rows = [&](int64_t base, uint4 (&xr)[TPG][NV]) {
+#pragma unroll
+        for (int k = 0; k < TPG; ++k) {
+            const int64_t tt = base + (int64_t)g * TPG + k;
+            const uint4* xrow = a.x + (tt < a.T ? tt : a.T - 1) * nvec;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int v = sub + i * LPT;
+                xr[k][i] = (TIGHT || v < nvec) ? load_stream(xrow + v) : make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    const int64_t stride = (int64_t)gridDim.x * tile;
+    uint4 xv[TPG][NV];
+    if (PREFETCH) fetch_rows((int64_t)blockIdx.x * tile, xv);
+
+    for (int64_t base = (int64_t)blockIdx.x * tile; base < a.T; base += stride) {
         int64_t t[TPG];
         bool live[TPG];
-        uint4 xv[TPG][NV];
 #pragma unroll
         for (int k = 0; k < TPG; ++k) {
             const int64_t tt = base + (int64_t)g * TPG + k;
             live[k] = tt < a.T;
             t[k] = live[k] ? tt : a.T - 1;
-            const uint4* xrow = a.x + t[k] * nvec;
-#pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                const int v = sub + i * LPT;
-                xv[k][i] = (TIGHT || v < nvec) ? load_stream(xrow + v) : make_uint4(0, 0, 0, 0);
-            }
+        }
+        // PREFETCH: the rows of this tile were requested one iteration ago; request the next
+        // tile's now, so that they travel while this tile walks the tree
+        uint4 xn[TPG][NV];
+        if (PREFETCH) {
+            if (base + stride < a.T) fetch_rows(base + stride, xn);
+        } else {
+            fetch_rows(base, xv);
         }
         int node[TPG];
 #pragma unroll
@@ -149,7 +167,15 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
             leaf[k] = node[k] - n_nodes;
             if (a.leaf_idx && live[k] && sub == 0) a.leaf_idx[t[k]] = (int32_t)leaf[k];
         }
-        if (!FUSED) continue;
+        if (!FUSED) {
+            if (PREFETCH) {
+#pragma unroll
+                for (int k = 0; k < TPG; ++k)
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) xv[k][i] = xn[k][i];
+            }
+            continue;
+        }
 
         // hidden neurons of the leaf reached: h[r] = act(W1[leaf][r] . x + b1[leaf][r])
         float h[TPG][kFusedMaxLeafWidth];
@@ -231,6 +257,12 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
                 }
             }
         }
+        if (PREFETCH) {
+#pragma unroll
+            for (int k = 0; k < TPG; ++k)
+#pragma unroll
+                for (int i = 0; i < NV; ++i) xv[k][i] = xn[k][i];
+        }
     }
 }
 
@@ -289,7 +321,7 @@ DeviceInfo device_info() {
 WalkTuning g_walk_tuning;
 namespace {
 
-template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT>
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT, bool PREFETCH = false>
 hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     constexpr int kGroups = kWalkBlock / LPT;
     const DeviceInfo di = device_info();
@@ -310,7 +342,7 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     }
     if (g_walk_tuning.top > 0 && g_walk_tuning.top - 1 < top) top = (int)g_walk_tuning.top - 1;
     const size_t lds_bytes = (size_t)(((int64_t)1 << top) - 1) * (row_bytes + 4);
-    auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED, TIGHT>;
+    auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED, TIGHT, PREFETCH>;
     if (lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
@@ -358,6 +390,13 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     if (nvec <= 96) {
         const int64_t tpg = g_walk_tuning.tpg, blk = g_walk_tuning.block;
         if (tpg == 1 && blk == 512) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
+        // measured best for the fused launch on 768-wide rows: blocks of 512 (256 VGPRs per lane),
+        // two tokens per group, next tile's rows requested one iteration ahead (85 vs 88 us on the
+        // BERT-base-sized workload); the descent-only launch gains nothing from it
+        const bool exact = nvec == 96 && FUSED && p.O == p.D && vec_ok(p.out, p.O, BF16) &&
+                           vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
+        if (exact && ((tpg == 0 && blk == 0) || g_walk_tuning.prefetch))
+            return run_walk_t<BF16, 16, 6, 2, 512, FUSED, true, true>(p, leaf_idx, s);
         if (tpg == 1) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
         if (tpg == 2 && blk == 512) return run_walk<BF16, 16, 6, 2, 512, FUSED>(p, leaf_idx, s);
         if (tpg == 4 && blk == 512) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
