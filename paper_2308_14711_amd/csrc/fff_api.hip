@@ -56,8 +56,8 @@ constexpr int64_t kCtrlWords = 64;
 int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    int64_t n_chunks, max_tiles;
-    int64_t o_ctrl, o_leaf, o_rank, o_perm, o_count, o_offset, o_tileoff, o_matrix, o_tiles, total;
+    int64_t n_chunks;
+    int64_t o_ctrl, o_leaf, o_rank, o_sleaf, o_perm, o_count, o_offset, o_tileoff, o_matrix, o_hidden, total;
 };
 
 Layout layout_for(int64_t T, int depth) {
@@ -69,18 +69,18 @@ Layout layout_for(int64_t T, int depth) {
     if (c > per_round) c = per_round;
     if (c < 1) c = 1;
     l.n_chunks = c;
-    l.max_tiles = (T + kTileRows - 1) / kTileRows + (NL < T ? NL : T);
     int64_t o = 0;
     auto take = [&](int64_t words) { int64_t at = o; o += round_up(words, kAlignWords); return at; };
     l.o_ctrl = take(kCtrlWords);
     l.o_leaf = take(T);
     l.o_rank = take(T);
+    l.o_sleaf = take(T);
     l.o_perm = take(T);
     l.o_count = take(NL);
     l.o_offset = take(NL + 1);
     l.o_tileoff = take(NL + 1);
     l.o_matrix = take(c * NL);
-    l.o_tiles = take(2 * l.max_tiles);
+    l.o_hidden = take(8 * T);
     l.total = o;
     return l;
 }
@@ -129,14 +129,14 @@ int get_workspace(int64_t T, int depth, Workspace* ws, Layout* lay) {
     ws->ctrl = b + lay->o_ctrl;
     ws->leaf_idx = b + lay->o_leaf;
     ws->rank = b + lay->o_rank;
+    ws->slot_leaf = b + lay->o_sleaf;
     ws->perm = b + lay->o_perm;
     ws->count = b + lay->o_count;
     ws->offset = b + lay->o_offset;
     ws->tile_off = b + lay->o_tileoff;
     ws->chunk_cnt = b + lay->o_matrix;
-    ws->tiles = b + lay->o_tiles;
+    ws->hidden = b + lay->o_hidden;
     ws->n_chunks = lay->n_chunks;
-    ws->max_tiles = lay->max_tiles;
     return FFF_OK;
 }
 
@@ -192,16 +192,16 @@ int choose_path(const Problem& p) {
 
 // K2 with whichever kernel set takes the sizes; outputs may be null (then workspace arrays are used).
 int run_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws, int32_t* count,
-               int32_t* offset, int32_t* perm, hipStream_t s) {
+               int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s) {
     hipError_t e;
     if (g_opt.bucket_kernel != 2 && bucket_onepass_ok(T, depth)) {
-        e = launch_bucket_onepass(leaf_idx, T, depth, count, offset, perm, s);
+        e = launch_bucket_onepass(leaf_idx, T, depth, count, offset, perm, slot_leaf, s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
     }
     const int64_t NL = (int64_t)1 << depth;
     if ((e = launch_zero(ws.chunk_cnt, round_up(ws.n_chunks * NL, 4), s)) != hipSuccess)
         return set_device_error(e, "zero kernel launch");
-    if ((e = launch_bucket(leaf_idx, T, depth, ws, count, offset, perm, s)) != hipSuccess)
+    if ((e = launch_bucket(leaf_idx, T, depth, ws, count, offset, perm, slot_leaf, s)) != hipSuccess)
         return set_device_error(e, "bucket kernel launch");
     return FFF_OK;
 }
@@ -215,12 +215,12 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
         if (timed) stage_mark(s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "leaf kernel launch");
     }
-    const int rc = run_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, s);
+    const int rc = run_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, ws.slot_leaf, s);
     if (rc != FFF_OK) return rc;
     if (timed) stage_mark(s);
     // the MFMA tile path pays once a leaf has a few neurons; for 1-2 the VALU gather kernel is leaner
     if (g_opt.leaf_path != 1 && tiles_shape_ok(p) && (p.L >= 3 || g_opt.leaf_path == 2))
-        e = launch_leaf_tiles(p, leaf_idx, ws.perm, s);
+        e = launch_leaf_tiles(p, ws.slot_leaf, ws.perm, ws.hidden, s);
     else
         e = launch_leaf_gather(p, leaf_idx, ws.perm, s);
     if (e != hipSuccess) return set_device_error(e, "leaf kernel launch");
@@ -301,7 +301,7 @@ int fff_bucket(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, in
     Layout lay;
     int rc = get_workspace(T, depth, &ws, &lay);
     if (rc != FFF_OK) return rc;
-    return run_bucket(leaf_idx, T, depth, ws, count, offset, perm, (hipStream_t)stream);
+    return run_bucket(leaf_idx, T, depth, ws, count, offset, perm, nullptr, (hipStream_t)stream);
 }
 
 int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1, const void* leaf_w2,

@@ -177,13 +177,15 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
                                                              int rounds, int64_t n_chunks,
                                                              const int32_t* __restrict__ M,
                                                              const int32_t* __restrict__ offset,
-                                                             int32_t* __restrict__ perm) {
+                                                             int32_t* __restrict__ perm,
+                                                             int32_t* __restrict__ slot_leaf) {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= T) return;
     const int64_t leaf = leaf_idx[t];
     const int64_t chunk = t / ((int64_t)kChunkTokens * rounds);
     const int32_t pos = offset[leaf] + M[leaf * n_chunks + chunk] + rank[t];
     perm[pos] = (int32_t)t;
+    if (slot_leaf) slot_leaf[pos] = (int32_t)leaf;
 }
 
 
@@ -230,7 +232,7 @@ __device__ __forceinline__ void onepass_count(const int4 v, int32_t lo, uint32_t
 // + rank inside the batch (lane-major, then element).
 __device__ __forceinline__ void onepass_place(const int4 v, int64_t t0, int lane, int32_t lo, uint32_t n_own,
                                               const int32_t* lbase, int32_t* my_cnt,
-                                              int32_t* __restrict__ perm) {
+                                              int32_t* __restrict__ perm, int32_t* __restrict__ slot_leaf) {
     const int32_t e[4] = {v.x, v.y, v.z, v.w};
     bool own[4];
 #pragma unroll
@@ -263,6 +265,7 @@ __device__ __forceinline__ void onepass_place(const int4 v, int64_t t0, int lane
         for (int k = 0; k < 4; ++k) {
             if (own[k] && e[k] == leaf) {
                 perm[at + pre[k]] = (int32_t)(t0 + 4 * lane + k);
+                if (slot_leaf) slot_leaf[at + pre[k]] = leaf;
                 own[k] = false;
             }
         }
@@ -274,7 +277,8 @@ __global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __r
                                                               int64_t n_leaves, int per_block, int vec,
                                                               int32_t* __restrict__ count,
                                                               int32_t* __restrict__ offset,
-                                                              int32_t* __restrict__ perm) {
+                                                              int32_t* __restrict__ perm,
+                                                              int32_t* __restrict__ slot_leaf) {
     extern __shared__ int32_t sm[];
     int32_t* cnt = sm;                                       // [16][per_block] per-wave counts, then bases
     int32_t* lbase = sm + kOnepassWaves * per_block;         // [per_block] start of each owned leaf
@@ -358,7 +362,7 @@ __global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __r
         }
 #pragma unroll
         for (int u = 0; u < kAhead; ++u)
-            onepass_place(keep[u], (b + u) * kBatch, lane, lo, n_own, lbase, my_cnt, perm);
+            onepass_place(keep[u], (b + u) * kBatch, lane, lo, n_own, lbase, my_cnt, perm, slot_leaf);
     }
 }
 
@@ -366,7 +370,7 @@ __global__ __launch_bounds__(1024) void bucket_onepass_kernel(const int32_t* __r
 bool bucket_onepass_ok(int64_t T, int depth) { return depth <= 19 && T <= ((int64_t)1 << 21); }
 
 hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count,
-                                 int32_t* offset, int32_t* perm, hipStream_t s) {
+                                 int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s) {
     const int64_t NL = (int64_t)1 << depth;
     int64_t per_block = (NL + 255) / 256;
     if (per_block > kOnepassMaxLeavesPerBlock) per_block = kOnepassMaxLeavesPerBlock;
@@ -374,12 +378,12 @@ hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, 
     const size_t lds = sizeof(int32_t) * (size_t)(kOnepassWaves * per_block + per_block + 2 * kOnepassWaves);
     const int vec = (reinterpret_cast<uintptr_t>(leaf_idx) & 15u) == 0;
     bucket_onepass_kernel<<<dim3((unsigned)blocks), dim3(1024), lds, s>>>(leaf_idx, T, NL, (int)per_block, vec,
-                                                                          count, offset, perm);
+                                                                          count, offset, perm, slot_leaf);
     return hipGetLastError();
 }
 
 hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,
-                         int32_t* count, int32_t* offset, int32_t* perm, hipStream_t s) {
+                         int32_t* count, int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s) {
     const int64_t NL = (int64_t)1 << depth;
     const int64_t per_round = (T + kChunkTokens - 1) / kChunkTokens;
     const int rounds = (int)((per_round + ws.n_chunks - 1) / ws.n_chunks);
@@ -396,7 +400,7 @@ hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Wo
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (T > 0 && perm) {
         bucket_scatter_kernel<<<dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s>>>(
-            leaf_idx, ws.rank, T, rounds, ws.n_chunks, ws.chunk_cnt, offset ? offset : ws.offset, perm);
+            leaf_idx, ws.rank, T, rounds, ws.n_chunks, ws.chunk_cnt, offset ? offset : ws.offset, perm, slot_leaf);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;

@@ -25,15 +25,15 @@ struct Problem {
 struct Workspace {
     int32_t* leaf_idx;   // [T]      when the caller passes none
     int32_t* rank;       // [T]      rank of a token among same-leaf tokens of its chunk
+    int32_t* slot_leaf;  // [T]      leaf of every slot of perm
     int32_t* perm;       // [T]      token ids grouped by leaf
     int32_t* count;      // [NL]
     int32_t* offset;     // [NL + 1]
     int32_t* tile_off;   // [NL + 1] exclusive prefix of per-leaf tile counts
     int32_t* chunk_cnt;  // [C, NL]  per-chunk histograms, then per-chunk bases
-    int32_t* tiles;      // [max_tiles, 2] (leaf, first slot) per tile
+    int32_t* hidden;     // [8 T]    hidden activations of the tile path, T * L bf16 (L <= 16)
     int32_t* ctrl;       // [16]     ticket counters and totals
     int64_t n_chunks;
-    int64_t max_tiles;
 };
 
 constexpr int kChunkTokens = 256;   // tokens per bucketing chunk
@@ -58,21 +58,23 @@ bool walk_shape_ok(const Problem& p);
 bool fused_shape_ok(const Problem& p);
 
 // K2: bucketing.  Needs ws.chunk_cnt zeroed on entry; leaves it dirty.
+//   slot_leaf (optional): the leaf of every slot of perm
 hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,
-                         int32_t* count, int32_t* offset, int32_t* perm, hipStream_t s);
+                         int32_t* count, int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s);
 hipError_t launch_zero(int32_t* p, int64_t n, hipStream_t s);
 // K2 in one launch (no workspace besides the outputs); any output may be null.
 bool bucket_onepass_ok(int64_t T, int depth);
 hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count,
-                                 int32_t* offset, int32_t* perm, hipStream_t s);
+                                 int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s);
 
 // K3 + K4: leaf networks and output rows.
 //   order == nullptr: slot i is token i.  Otherwise slot i is token order[i].
 hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order,
                               hipStream_t s);
-// MFMA tile path over tokens grouped by leaf (perm); needs tiles_shape_ok(p).
+// MFMA tile path over tokens grouped by leaf (perm, and the leaf of every slot); needs tiles_shape_ok(p).
 bool tiles_shape_ok(const Problem& p);
-hipError_t launch_leaf_tiles(const Problem& p, const int32_t* leaf_idx, const int32_t* perm, hipStream_t s);
+hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const int32_t* perm, void* hidden,
+                             hipStream_t s);
 
 // Whole forward pass in one launch, one token per lane group (any shape).
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);
