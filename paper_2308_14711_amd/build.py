@@ -14,7 +14,8 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["fff_api.hip", "fff_walk.hip", "fff_bucket.hip", "fff_leaf.hip", "fff_leaf_tiles.hip"]
 HEADERS = ["fff_device.h", "fff_internal.h", os.path.join("..", "..", "include", "fff.h")]
 
-# packed fp32 VALU forms are switched off on purpose ("Build flags")
+# packed fp32 VALU forms are switched off on purpose: some of them have given wrong results on
+# the target machines; ordinary float code is compiled without them
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wall", "-Wno-unused-function"]

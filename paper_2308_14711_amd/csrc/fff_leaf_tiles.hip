@@ -155,12 +155,23 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
         }
         // lane (j, kg) holds rows 4 kg + q of column j: the entries of the token's own run are its
         // hidden pre-activations
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int rho = 4 * kg + q, rr = rho / L, n = rho % L;
+        if (L % 4 == 0) {
+            const int rr = (4 * kg) / L, n0 = (4 * kg) % L;
             if (c.tok >= 0 && rr < P && c.run == pass + rr) {
-                const float v = activate(acc[q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n]), a.act);
-                a.hidden[(int64_t)c.tok * L + n] = f32_to_bf16(v);
+                float v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    v[q] = activate(acc[q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n0 + q]), a.act);
+                *(uint2*)(a.hidden + (int64_t)c.tok * L + n0) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int rho = 4 * kg + q, rr = rho / L, n = rho % L;
+                if (c.tok >= 0 && rr < P && c.run == pass + rr) {
+                    const float v = activate(acc[q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n]), a.act);
+                    a.hidden[(int64_t)c.tok * L + n] = f32_to_bf16(v);
+                }
             }
         }
     }
@@ -204,18 +215,31 @@ __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
                 if (4 * kg + q == rr) { b_leaf[q] = lf; b_ok[q] = true; }
             }
         }
-        float hq[4], iq[4];
+        uint32_t h01 = 0, h23 = 0;               // this lane's four K slots of h, as two bf16 pairs
+        float iq[4];
+        if (L % 4 == 0) {
+            // the four slots are four consecutive neurons of one run: one 8-byte load
+            const int rr = (4 * kg) / L, n0 = (4 * kg) % L;
+            if (c.tok >= 0 && rr < P && c.run == pass + rr) {
+                const uint2 hv = *(const uint2*)(a.hidden + (int64_t)c.tok * L + n0);
+                h01 = hv.x;
+                h23 = hv.y;
+            }
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int rho = 4 * kg + q, rr = rho / L, n = rho % L;
             wptr[q] = a.w2 + ((int64_t)w_leaf[q] * L + n) * O + 8 * j;
             bptr[q] = a.b2 + (int64_t)b_leaf[q] * O + 8 * j;
-            const bool mine = c.tok >= 0 && rr < P && c.run == pass + rr;
-            hq[q] = mine ? bf16_to_f32(a.hidden[(int64_t)c.tok * L + n]) : 0.f;
+            if (L % 4 != 0) {
+                const bool mine = c.tok >= 0 && rr < P && c.run == pass + rr;
+                const uint32_t hb = mine ? a.hidden[(int64_t)c.tok * L + n] : 0u;
+                if (q < 2) h01 |= hb << (16 * q);
+                else h23 |= hb << (16 * (q - 2));
+            }
             iq[q] = (c.tok >= 0 && rho < P && c.run == pass + rho) ? 1.0f : 0.0f;
         }
-        const uint4 a2u = make_uint4(pack_bf16x2(hq[0], hq[1]), pack_bf16x2(hq[2], hq[3]),
-                                     pack_bf16x2(iq[0], iq[1]), pack_bf16x2(iq[2], iq[3]));
+        const uint4 a2u = make_uint4(h01, h23, pack_bf16x2(iq[0], iq[1]), pack_bf16x2(iq[2], iq[3]));
         const bf16x8_t a2 = __builtin_bit_cast(bf16x8_t, a2u);
         bool st_ok[4];
 #pragma unroll
