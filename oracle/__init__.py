@@ -32,12 +32,21 @@ def build(force: bool = False) -> str:
 
 
 _lib = None
+_lib_path = None
+
+
+def use_library(path: Optional[str]) -> None:
+    """Point the wrapper at another build of the oracle (tests that plant mistakes in a copy of
+    the C source use this); None goes back to the regular build."""
+    global _lib, _lib_path
+    _lib = None
+    _lib_path = path
 
 
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        _lib = ctypes.CDLL(_lib_path or build())
         vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_double
         _lib.fff_oracle_forward_hard.argtypes = [vp] * 7 + [i32, i32, i32, i64, i64, i64, i32, vp, vp, vp]
         _lib.fff_oracle_leaf_forward.argtypes = [vp] * 6 + [i32, i32, i32, i64, i64, i64, i32, vp]

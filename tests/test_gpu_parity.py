@@ -247,3 +247,37 @@ def test_alternative_paths_agree_with_the_oracle(opt):
     finally:
         F.fff_set_option(opt[0], old)
     _log("paths %s" % (opt,), check_against_oracle(w, out, idx))
+
+
+@pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
+def test_capture_in_a_hip_graph_and_replay(path):
+    """The call only enqueues kernels on the given stream (no allocation once the workspace is
+    reserved, no memset nodes): it can be captured, and every replay, with eager work and
+    synchronisations in between, must reproduce the eager result bit for bit."""
+    import torch
+    import paper_2308_14711_amd as F
+    w = W.make_layer("graph", 3000, 256, 128, 6, 4, W.ACT_GELU, W.DTYPE_BF16, seed=11)
+    dev = to_device(w)
+    F.fff_set_option("path", path)
+    try:
+        eager_out, eager_idx = run_forward(w, dev)
+        _log("graph eager path=%d" % path, check_against_oracle(w, eager_out, eager_idx))
+        F.fff_reserve_workspace(w.T, w.depth)
+        out = torch.zeros_like(eager_out)
+        idx = torch.zeros_like(eager_idx)
+        g = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            F.fff_forward_hard(dev["x"], dev["node_w"], dev["node_b"], dev["leaf_w1"], dev["leaf_b1"],
+                               dev["leaf_w2"], dev["leaf_b2"], w.depth, w.leaf_width, w.act, out, idx)
+        for rep in range(4):
+            out.fill_(float("nan"))
+            idx.fill_(-1)
+            scratch = torch.randn(1 << 16, device="cuda").sum().item()      # eager work between replays
+            assert scratch == scratch
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), eager_out.view(torch.int16)), "replay %d differs" % rep
+            assert torch.equal(idx, eager_idx)
+    finally:
+        F.fff_set_option("path", 0)

@@ -1,0 +1,90 @@
+"""The pins must have teeth: a copy of the oracle's C source with one planted mistake is
+compiled (CPU only) and at least one pin has to fail for it.  Nothing here touches the GPU."""
+import os
+import subprocess
+import tempfile
+
+import pytest
+
+import oracle
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "fff_oracle.c")
+
+# (name, text to replace, replacement): each is a plausible slip in one place
+MUTATIONS = [
+    ("strict_tie", "if (logit >= 0.0) n = 2 * n + 1;", "if (logit > 0.0) n = 2 * n + 1;"),
+    ("children_swapped", "if (logit >= 0.0) n = 2 * n + 1;   /* c >= 1/2 */\n            else n = 2 * n;",
+     "if (logit >= 0.0) n = 2 * n;\n            else n = 2 * n + 1;"),
+    ("heap_row_off_by_one", "int64_t row = (((int64_t)1 << m) - 1) + n;", "int64_t row = ((int64_t)1 << m) + n;"),
+    ("node_bias_dropped", "return s + b;", "return s;"),
+    ("w2_transposed", "s += h[r] * ld(w2, (k * L + r) * O + o, dtype);", "s += h[r] * ld(w2, (k * O + o) * L + r, dtype);"),
+    ("w1_wrong_leaf_stride", "ld(w1, (k * L + r) * D + j, dtype)", "ld(w1, (k + r) * D + j, dtype)"),
+    ("b1_dropped", "h[r] = activation(s + ld(b1, k * L + r, dtype), act);", "h[r] = activation(s, act);"),
+    ("b2_dropped", "y[o] = s + ld(b2, k * O + o, dtype);", "y[o] = s;"),
+    ("gelu_tanh", "return 0.5 * v * (1.0 + erf(v / sqrt(2.0)));",
+     "return 0.5 * v * (1.0 + tanh(0.7978845608028654 * (v + 0.044715 * v * v * v)));"),
+    ("relu_leaky", "return v > 0.0 ? v : 0.0;", "return v > 0.0 ? v : 0.01 * v;"),
+    ("soft_children_swapped", "forward_t(c, m + 1, 2 * n + 1, weight * cmn, yr);\n    forward_t(c, m + 1, 2 * n, weight * (1.0 - cmn), yl);",
+     "forward_t(c, m + 1, 2 * n, weight * cmn, yr);\n    forward_t(c, m + 1, 2 * n + 1, weight * (1.0 - cmn), yl);"),
+    ("soft_no_complement", "y[o] = cmn * yr[o] + (1.0 - cmn) * yl[o];", "y[o] = cmn * yr[o] + cmn * yl[o];"),
+    ("bucket_unstable", "for (int64_t t = 0; t < T; ++t) perm[cur[leaf_idx[t]]++] = (int32_t)t;",
+     "for (int64_t t = T - 1; t >= 0; --t) perm[cur[leaf_idx[t]]++] = (int32_t)t;"),
+    ("bucket_offset_inclusive", "offset[j + 1] = offset[j] + count[j];", "offset[j + 1] = offset[j] + count[j] + (j == 0);"),
+    ("training_size_nodes", "return (((int64_t)1 << depth) - 1) * node_size + ((int64_t)1 << depth) * leaf_size;",
+     "return ((int64_t)1 << depth) * node_size + ((int64_t)1 << depth) * leaf_size;"),
+    ("inference_size", "return (int64_t)depth * node_size + leaf_size;", "return (int64_t)(depth + 1) * node_size + leaf_size;"),
+    ("bf16_widen_shift", "uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 16;", "uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 15;"),
+]
+
+PINS = [
+    pins.test_sizes_match_the_papers_table,
+    pins.test_hand_worked_depth2_example,
+    pins.test_gelu_closed_form_points,
+    lambda: pins.test_saturated_soft_equals_hard(3, 5, 3, 2, oracle.ACT_RELU),
+    pins.test_mixture_is_a_stochastic_vector,
+    pins.test_zero_node_weights_give_the_dense_ff,
+    lambda: pins.test_depth_zero_is_a_plain_ff(oracle.ACT_GELU),
+    lambda: pins.test_depth_zero_is_a_plain_ff(oracle.ACT_RELU),
+    lambda: pins.test_bit_path_agrees_with_node_signs(3),
+    pins.test_axis_aligned_nodes_route_like_a_kd_tree,
+    pins.test_identical_leaves_make_routing_irrelevant,
+    pins.test_leaf_forward_matches_forward_hard_and_library,
+    pins.test_bf16_and_f32_inputs_are_widened_exactly,
+    lambda: pins.test_bucket_against_library_sort(8, 5000),
+]
+
+
+@pytest.fixture(scope="module")
+def workdir():
+    with tempfile.TemporaryDirectory() as d:
+        yield d
+    oracle.use_library(None)
+
+
+@pytest.mark.parametrize("mutation", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_a_planted_mistake_is_caught(mutation, workdir):
+    name, old, new = mutation
+    src = open(SRC).read()
+    assert src.count(old) >= 1, "mutation %s no longer matches the oracle source" % name
+    mutated = os.path.join(workdir, name + ".c")
+    lib = os.path.join(workdir, name + ".so")
+    open(mutated, "w").write(src.replace(old, new))
+    subprocess.check_call(["gcc", "-O1", "-std=c99", "-fPIC", "-shared", "-w", "-o", lib, mutated, "-lm"])
+    oracle.use_library(lib)
+    caught = []
+    try:
+        for pin in PINS:
+            try:
+                pin()
+            except (AssertionError, ValueError):
+                caught.append(pin)
+    finally:
+        oracle.use_library(None)
+    assert caught, "no pin noticed the planted mistake '%s'" % name
+
+
+def test_the_real_oracle_passes_the_same_pins():
+    oracle.use_library(None)
+    for pin in PINS:
+        pin()
