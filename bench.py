@@ -59,6 +59,80 @@ def algorithmic_bytes(w, ref_idx):
     }
 
 
+def depth_sweep(args, np, torch, W, F):
+    """Time per call against tree depth for a small batch: inputs and outputs 768 wide, leaves of
+    `--sweep-leaf-width` neurons, depth `--sweep-min-depth`..`--sweep-max-depth`, `--sweep-batch` tokens (the shape
+    of the paper's inference-speed experiment, with synthetic inputs).  Three clocks per depth:
+    calls issued back to back from Python (launch cost of the host loop included), the same calls
+    replayed from a HIP graph holding 20 of them (per-call device time with launches amortised),
+    and the CPU oracle.  The routing of every depth is checked against the oracle."""
+    import oracle
+    T, L, D, O = args.sweep_batch, args.sweep_leaf_width, 768, 768
+    rows = []
+    for d in range(args.sweep_min_depth, args.sweep_max_depth + 1):
+        w = W.make_layer("depth_sweep", T, D, O, d, L, W.ACT_GELU, W.DTYPE_BF16, seed=d, keep_f32=False)
+        dev = {}
+        for k in W.TENSORS:
+            a = np.ascontiguousarray(w.device_array(k))
+            dev[k] = torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        out = torch.empty((T, O), dtype=torch.bfloat16, device="cuda")
+        idx = torch.empty((T,), dtype=torch.int32, device="cuda")
+        F.fff_reserve_workspace(T, d)
+
+        def call(stream=None):
+            F.fff_forward_hard(dev["x"], dev["node_w"], dev["node_b"], dev["leaf_w1"], dev["leaf_b1"],
+                               dev["leaf_w2"], dev["leaf_b2"], d, L, w.act, out, idx, stream)
+
+        for _ in range(args.warmup):
+            call()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            call()
+        torch.cuda.synchronize()
+        eager_us = (time.perf_counter() - t0) * 1e6 / args.steps
+        per_graph = 20
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(per_graph):
+                call()
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // per_graph)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) * 1e6 / (reps * per_graph)
+        ins = [np.ascontiguousarray(w.device_array(k)) for k in W.TENSORS]
+        t0 = time.perf_counter()
+        ref_out, ref_idx, margin = oracle.forward_hard(*ins, d, L, w.act)
+        cpu_us = (time.perf_counter() - t0) * 1e6
+        got_idx = idx.cpu().numpy()
+        mism = np.nonzero(got_idx != ref_idx)[0]
+        keep = got_idx == ref_idx
+        got = out.float().cpu().numpy().astype(np.float64)
+        scale = np.maximum(np.abs(ref_out[keep]).max(axis=1), 1e-30)
+        rows.append({"depth": d, "us_per_call_python_loop": round(eager_us, 2), "us_per_call_graph": round(graph_us, 2),
+                     "us_cpu_oracle": round(cpu_us, 1), "launch_path": int(F.fff_get_option("last_path")),
+                     "idx_mismatch_outside_margin": int((margin[mism] >= 1e-4).sum()),
+                     "max_rel_row_err": float((np.abs(got[keep] - ref_out[keep]).max(axis=1) / scale).max())})
+        del dev, w, ins
+    ds = np.array([r["depth"] for r in rows], dtype=np.float64)
+    ys = np.array([r["us_per_call_graph"] for r in rows])
+    slope, icpt = (np.polyfit(ds, ys, 1) if len(rows) > 1 else (0.0, ys[0]))
+    resid = ys - (slope * ds + icpt)
+    print(json.dumps({
+        "metric": "fff_hard_inference_latency_vs_depth", "unit": "us per call", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "depth sweep: batch %d, D = O = 768, leaf width %d, GELU" % (T, L),
+                   "options": args.opt, "cpu_oracle_cores": oracle.num_threads()},
+        "linear_fit_graph": {"us_per_level": round(float(slope), 3), "us_at_depth_0": round(float(icpt), 2),
+                             "max_abs_residual_us": round(float(np.abs(resid).max()), 2)},
+        "sweep": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +144,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
+    ap.add_argument("--sweep", choices=["depth"], default=None,
+                    help="depth: the small-batch latency sweep (time per call against tree depth) instead of a workload")
+    ap.add_argument("--sweep-batch", type=int, default=256)
+    ap.add_argument("--sweep-leaf-width", type=int, default=32)
+    ap.add_argument("--sweep-min-depth", type=int, default=1)
+    ap.add_argument("--sweep-max-depth", type=int, default=15)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -89,6 +169,10 @@ def main():
     for kv in args.opt:
         k, v = kv.split("=")
         F.fff_set_option(k, int(v))
+
+    if args.sweep == "depth":
+        depth_sweep(args, np, torch, W, F)
+        return
 
     w = W.config(args.config, keep_f32=False)
     tdt = torch.bfloat16 if w.dtype == W.DTYPE_BF16 else torch.float32
@@ -142,7 +226,7 @@ def main():
             cpu_passes += 1
         cpu_s = time.perf_counter() - t2
     alg = algorithmic_bytes(w, ref_idx)
-    path_names = {1: "fused", 2: "staged", 3: "generic"}
+    path_names = {1: "fused", 2: "staged", 3: "generic", 4: "token_block"}
 
     # per-stage durations: HIP events recorded by the library on the call's stream
     stages = {}

@@ -138,17 +138,30 @@ int fff_release_workspace(void);
 
 /*
  * Tuning and test switches (process-wide; not thread-safe against running calls).
- *   "leaf_path"      staged path only: 0 = MFMA tile kernel when the shape allows it
- *                    (bf16, leaf_width <= 16, D % 8 == 0, O % 4 == 0), else the gather
- *                    kernel (default); 1 = always the gather kernel
- *   "path"           0 = choose by shape (default: staged when leaf_width >= 4 and a leaf
- *                    sees >= 32 tokens on average, else fused), 1 = one fused launch (walk,
- *                    leaf network and output row per token; leaf_width <= 8), 2 = staged
- *                    (descent, bucketing, leaf kernel), 3 = the element-wise fallback
- *                    kernel; a path the shape does not allow falls back to one it does
+ *   "leaf_path"      staged path only: 0 = the MFMA tile kernels when the shape allows them
+ *                    (bf16, 3 <= leaf_width <= 16, D % 8 == 0, O % 8 == 0, 16-byte aligned
+ *                    rows), else the gather kernel (default); 1 = always the gather kernel;
+ *                    2 = the tile kernels also for leaf_width 1 and 2
+ *   "path"           0 = choose by shape and batch size (default), 1 = one fused launch
+ *                    (walk, leaf network and output row per token, tokens streamed through
+ *                    persistent blocks; leaf_width <= 8), 2 = staged (descent, bucketing,
+ *                    leaf kernels), 3 = the element-wise fallback kernel, 4 = one block per
+ *                    token (small batches: several tree levels per memory round trip, the
+ *                    leaf's neurons split over the block's waves; rows of at most 512
+ *                    16-byte vectors); a path the shape does not allow falls back to one it
+ *                    does.  The default takes 4 for batches of up to "token_max_T" tokens
+ *                    (8 times that where leaf_width > 8 rules out the fused launch), then
+ *                    staged when leaf_width >= 4, a leaf sees >= 32 tokens on average and
+ *                    T > 8192, else fused
+ *   "token_max_T"    see "path" (default 512)
+ *   "walk_tpg", "walk_block", "walk_top", "walk_bpc", "walk_prefetch"
+ *                    experiment switches of the fused/descent kernel (tokens per lane
+ *                    group, threads per block, k + 1 = at most k LDS-staged levels,
+ *                    persistent blocks per compute unit, next-tile prefetch); 0 = built-in
+ *                    choice, combinations the kernel is not built for are ignored
  *   "bucketing"      1 (default) = the leaf kernel visits tokens grouped by leaf,
  *                    0 = in token order (no bucketing stage)
- *   "last_path"      read it after a call: the path (1, 2 or 3) fff_forward_hard took
+ *   "last_path"      read it after a call: the path (1, 2, 3 or 4) fff_forward_hard took
  *   "bucket_kernel"  0 = choose by size (default), 1 = the one-launch bucketing kernel when
  *                    the sizes allow it, 2 = always the chunk-matrix kernels
  *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages

@@ -31,6 +31,7 @@ struct Options {
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
     int64_t bucket_kernel = 0;   // 0 auto, 1 one-launch kernel, 2 chunk-matrix kernels
     int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
+    int64_t token_max_T = 512;   // batches up to this many tokens (8x where no fused launch fits) go one block per token
 } g_opt;
 
 // Events recorded around the stages of fff_forward_hard while "stage_timing" is on:
@@ -172,17 +173,25 @@ bool staged_shape_ok(const Problem& p) {
     return walk_shape_ok(p) && vec_ok(p.leaf_w1, p.D, p.bf16) && p.L <= 64;
 }
 
-enum { kPathAuto = 0, kPathFused = 1, kPathStaged = 2, kPathGeneric = 3 };
+enum { kPathAuto = 0, kPathFused = 1, kPathStaged = 2, kPathGeneric = 3, kPathToken = 4 };
 
 // One launch that keeps the token row in registers from the root to the output
 // row wins while a leaf is narrow (its weights are a few rows per token, like a
 // few more tree levels); wider leaves want tokens grouped so that a leaf's
 // weights are read once per group.
 int choose_path(const Problem& p) {
-    const bool fused_ok = fused_shape_ok(p), staged_ok = staged_shape_ok(p);
+    const bool fused_ok = fused_shape_ok(p), staged_ok = staged_shape_ok(p), token_ok = token_shape_ok(p);
+    if (g_opt.path == kPathToken && token_ok) return kPathToken;
     if (g_opt.path == kPathFused && fused_ok) return kPathFused;
     if (g_opt.path == kPathStaged && staged_ok) return kPathStaged;
-    if (g_opt.path == kPathGeneric || (!fused_ok && !staged_ok)) return kPathGeneric;
+    if (g_opt.path == kPathGeneric) return kPathGeneric;
+    // a small batch cannot fill the chip with streaming work: one block per token, built for latency
+    // (measured crossovers on 768-wide rows: the fused launch catches up near 1024 tokens; leaves too
+    // wide for it leave only the staged path, which needs several thousand tokens to pay off)
+    if (g_opt.path == kPathAuto && token_ok &&
+        p.T <= (fused_ok ? g_opt.token_max_T : 8 * g_opt.token_max_T))
+        return kPathToken;
+    if (!fused_ok && !staged_ok) return token_ok ? kPathToken : kPathGeneric;
     if (!staged_ok) return kPathFused;
     if (!fused_ok) return kPathStaged;
     // grouping pays once a leaf is wide enough and visited by enough tokens to share its rows
@@ -258,6 +267,14 @@ int fff_forward_hard(const void* x, const void* node_w, const void* node_b, cons
     if (path == kPathGeneric) {
         hipError_t e = launch_fused_generic(p, leaf_idx, s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "generic kernel launch");
+    }
+    if (path == kPathToken) {
+        stage_mark(s);
+        hipError_t e = launch_token_block(p, leaf_idx, s);
+        stage_mark(s);
+        stage_mark(s);
+        stage_mark(s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "token-block kernel launch");
     }
     if (path == kPathFused) {
         stage_mark(s);
@@ -355,6 +372,7 @@ static int64_t* option_slot(const char* name) {
     if (!name) return nullptr;
     if (!std::strcmp(name, "leaf_path")) return &g_opt.leaf_path;
     if (!std::strcmp(name, "path")) return &g_opt.path;
+    if (!std::strcmp(name, "token_max_T")) return &g_opt.token_max_T;
     if (!std::strcmp(name, "walk_tpg")) return &g_walk_tuning.tpg;
     if (!std::strcmp(name, "walk_block")) return &g_walk_tuning.block;
     if (!std::strcmp(name, "walk_top")) return &g_walk_tuning.top;

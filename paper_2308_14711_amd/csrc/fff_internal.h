@@ -76,6 +76,13 @@ bool tiles_shape_ok(const Problem& p);
 hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const int32_t* perm, void* hidden,
                              hipStream_t s);
 
+// Whole forward pass in one launch, one block per token: the small-batch path, built for the
+// latency of the dependent loads rather than for throughput; needs token_shape_ok(p).
+constexpr size_t kTokenMaxLds = 144 * 1024;
+constexpr int64_t kTokenMaxBlocks = 8192;
+bool token_shape_ok(const Problem& p);
+hipError_t launch_token_block(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+
 // Whole forward pass in one launch, one token per lane group (any shape).
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 

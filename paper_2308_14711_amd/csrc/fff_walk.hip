@@ -298,6 +298,7 @@ namespace {
 struct DeviceInfo {
     int cus = 0;
     size_t lds_per_block = 0;
+    int dev = 0;
 };
 
 DeviceInfo device_info() {
@@ -313,6 +314,7 @@ DeviceInfo device_info() {
             (void)hipGetLastError();
             info[dev] = DeviceInfo{256, 64 * 1024};
         }
+        info[dev].dev = dev;
     }
     return info[dev];
 }
@@ -343,10 +345,14 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     if (g_walk_tuning.top > 0 && g_walk_tuning.top - 1 < top) top = (int)g_walk_tuning.top - 1;
     const size_t lds_bytes = (size_t)(((int64_t)1 << top) - 1) * (row_bytes + 4);
     auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED, TIGHT, PREFETCH>;
-    if (lds_bytes > 48 * 1024) {
+    // raise this instantiation's dynamic LDS limit once per device (the limit only ever grows)
+    static size_t lds_allowed_on[64];
+    size_t& lds_allowed = lds_allowed_on[di.dev];
+    if (lds_bytes > 48 * 1024 && lds_bytes > lds_allowed) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds_bytes);
+                                           (int)lds_cap);
         if (e != hipSuccess) return e;
+        lds_allowed = lds_cap;
     }
     WalkArgs a;
     a.x = (const uint4*)p.x;

@@ -79,10 +79,19 @@ SMALL = [
     ("tiles_L16",         300, 128, 200, 2, 16, W.ACT_RELU, W.DTYPE_BF16),
     ("tiles_sparse",      200, 64,  64,  10, 4, W.ACT_GELU, W.DTYPE_BF16),
     ("gather_L17",        150, 64,  64,  3, 17, W.ACT_GELU, W.DTYPE_BF16),
+    # small batches: the one-block-per-token launch (depths around multiples of its 3-level rounds,
+    # rows of 1, 2, 4 and 8 vectors per lane, outputs wider than inputs, a batch above its grid cap)
+    ("latency_L32_d7",    256, 768, 768, 7, 32, W.ACT_GELU, W.DTYPE_BF16),
+    ("latency_L32_d9",    256, 768, 768, 9, 32, W.ACT_GELU, W.DTYPE_BF16),
+    ("latency_f32_d5",    100, 768, 256, 5, 6,  W.ACT_RELU, W.DTYPE_F32),
+    ("latency_wide_out",  64,  64,  1024, 4, 9, W.ACT_GELU, W.DTYPE_BF16),
+    ("latency_4096_d5",   33,  4096, 512, 5, 3, W.ACT_GELU, W.DTYPE_BF16),
+    ("latency_L70",       20,  128, 10, 2, 70, W.ACT_GELU, W.DTYPE_F32),
+    ("latency_many",      9001, 32, 16, 8, 2, W.ACT_RELU, W.DTYPE_BF16),
 ]
 
 
-@pytest.mark.parametrize("path", [0, 2], ids=["auto", "staged"])
+@pytest.mark.parametrize("path", [0, 1, 2, 4], ids=["auto", "fused", "staged", "token"])
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
 def test_small_and_edge_shapes(case, path):
     import paper_2308_14711_amd as F
@@ -94,9 +103,13 @@ def test_small_and_edge_shapes(case, path):
     F.fff_set_option("path", path)
     try:
         out, idx = run_forward(w)
+        took = F.fff_get_option("last_path")
     finally:
         F.fff_set_option("path", 0)
-    _log(name, check_against_oracle(w, out, idx))
+    per = 8 if dtype == W.DTYPE_BF16 else 4
+    if D % per == 0 and D // per <= 512 and (path == 4 or (path == 0 and T <= 512)):
+        assert took == 4, "the one-block-per-token launch takes this shape, but path %d ran" % took
+    _log("%s path=%d took=%d" % (name, path, took), check_against_oracle(w, out, idx))
 
 
 def test_empty_batch_is_a_noop():
@@ -236,7 +249,8 @@ def test_descend_and_leaf_stages():
     assert err.max() <= 2e-2
 
 
-@pytest.mark.parametrize("opt", [("bucketing", 0), ("path", 1), ("path", 2), ("path", 3), ("leaf_path", 1)])
+@pytest.mark.parametrize("opt", [("bucketing", 0), ("path", 1), ("path", 2), ("path", 3), ("path", 4),
+                                 ("leaf_path", 1)])
 def test_alternative_paths_agree_with_the_oracle(opt):
     import paper_2308_14711_amd as F
     w = W.make_layer("paths", 2000, 256, 128, 6, 4, W.ACT_GELU, W.DTYPE_BF16, seed=9)
@@ -249,7 +263,7 @@ def test_alternative_paths_agree_with_the_oracle(opt):
     _log("paths %s" % (opt,), check_against_oracle(w, out, idx))
 
 
-@pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
+@pytest.mark.parametrize("path", [1, 2, 4], ids=["fused", "staged", "token"])
 def test_capture_in_a_hip_graph_and_replay(path):
     """The call only enqueues kernels on the given stream (no allocation once the workspace is
     reserved, no memset nodes): it can be captured, and every replay, with eager work and
