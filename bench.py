@@ -56,6 +56,10 @@ def algorithmic_bytes(w, ref_idx):
         "descent": T * D * s + 4 * T + node_bytes,
         "bucketing": 4 * T + 4 * T,                     # leaf_idx in, perm out
         "leaf": T * D * s + T * O * s + 8 * T + leaf_bytes,
+        # the tile path's two launches: token rows in, hidden activations out (bf16); those back in
+        # with the output weights, output rows out; both read the grouped order and the slots' leaves
+        "leaf_hidden": T * D * s + 8 * T + u_leaf * (L * D * s + L * s) + T * L * 2,
+        "leaf_output": T * L * 2 + 8 * T + u_leaf * (L * O * s + O * s) + T * O * s,
     }
 
 
@@ -235,12 +239,17 @@ def main():
         for i in range(args.steps):
             step(i)
         torch.cuda.synchronize()
-        d_ms, b_ms, l_ms, calls = F.fff_stage_times()
+        d_ms, b_ms, l_ms, l2_ms, calls = F.fff_stage_times()
         F.fff_set_option("stage_timing", 0)
-        fused = F.fff_get_option("last_path") != 2
-        if fused:      # one launch did the whole path: it carries the whole path's bytes
-            alg = dict(alg, walk_fused=alg["path"])
-        for name, ms in ((("walk_fused", d_ms),) if fused else (("descent", d_ms), ("bucketing", b_ms), ("leaf", l_ms))):
+        single = F.fff_get_option("last_path") != 2
+        if single:     # one launch did the whole path: it carries the whole path's bytes
+            alg = dict(alg, walk_fused=alg["path"], token_block=alg["path"])
+            names = ((("token_block" if F.fff_get_option("last_path") == 4 else "walk_fused"), d_ms),)
+        elif l2_ms > 0.1 * l_ms:   # the leaf stage ran as two kernels
+            names = (("descent", d_ms), ("bucketing", b_ms), ("leaf_hidden", l_ms), ("leaf_output", l2_ms))
+        else:
+            names = (("descent", d_ms), ("bucketing", b_ms), ("leaf", l_ms))
+        for name, ms in names:
             avg = ms / max(calls, 1)
             gbs = alg[name] / (avg * 1e-3) / 1e9 if avg > 0 else 0.0
             stages[name] = {"avg_ms": round(avg, 5), "alg_bytes": alg[name], "GBps": round(gbs, 1),

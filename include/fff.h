@@ -173,9 +173,12 @@ int fff_get_option(const char* name, int64_t* value);
 
 /*
  * Waits for, sums and clears the stage events recorded since the last call:
- * ms[0..2] = total milliseconds of descent, bucketing and leaf kernel (with
- * output rows), *calls = number of fff_forward_hard calls summed.  Blocks
- * until those calls have finished.
+ * ms[0..3] = total milliseconds of descent, bucketing, the leaf stage's first
+ * kernel and its second (the MFMA tile path computes hidden activations, then
+ * output rows; the gather kernel does both in one launch and ms[3] is then the
+ * gap between two marks; a single-launch path reports its kernel in ms[0]),
+ * *calls = number of fff_forward_hard calls summed.  Blocks until those calls
+ * have finished.
  */
 int fff_stage_times(double* ms, int64_t* calls);
 

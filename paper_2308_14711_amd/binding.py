@@ -151,11 +151,13 @@ def fff_get_option(name: str) -> int:
 
 
 def fff_stage_times():
-    """(ms_descent, ms_bucketing, ms_leaf, calls) summed since the last read."""
-    ms = (ctypes.c_double * 3)()
+    """(ms_descent, ms_bucketing, ms_leaf_first_kernel, ms_leaf_second_kernel, calls) summed since
+    the last read.  The leaf stage is two kernels (hidden activations, output rows) on the MFMA
+    tile path and one otherwise (then the fourth figure is the gap between two marks)."""
+    ms = (ctypes.c_double * 4)()
     calls = ctypes.c_int64(0)
     _check(lib().fff_stage_times(ms, ctypes.byref(calls)), "fff_stage_times")
-    return ms[0], ms[1], ms[2], int(calls.value)
+    return ms[0], ms[1], ms[2], ms[3], int(calls.value)
 
 
 def fff_status_string(status: int) -> str:

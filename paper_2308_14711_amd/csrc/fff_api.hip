@@ -35,7 +35,8 @@ struct Options {
 } g_opt;
 
 // Events recorded around the stages of fff_forward_hard while "stage_timing" is on:
-// four per call (start, after descent, after bucketing, after the leaf kernel).
+// five per call (start, after descent, after bucketing, after the leaf stage's first kernel, after
+// its second; a path with fewer kernels records the later marks back to back).
 std::vector<hipEvent_t> g_stage_events;
 
 void stage_mark(hipStream_t s) {
@@ -222,6 +223,7 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
         if (timed) stage_mark(s);
         e = launch_leaf_gather(p, leaf_idx, nullptr, s);
         if (timed) stage_mark(s);
+        if (timed) stage_mark(s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "leaf kernel launch");
     }
     const int rc = run_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, ws.slot_leaf, s);
@@ -229,9 +231,11 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
     if (timed) stage_mark(s);
     // the MFMA tile path pays once a leaf has a few neurons; for 1-2 the VALU gather kernel is leaner
     if (g_opt.leaf_path != 1 && tiles_shape_ok(p) && (p.L >= 3 || g_opt.leaf_path == 2))
-        e = launch_leaf_tiles(p, ws.slot_leaf, ws.perm, ws.hidden, s);
-    else
+        e = launch_leaf_tiles(p, ws.slot_leaf, ws.perm, ws.hidden, s, timed ? stage_mark : nullptr);
+    else {
         e = launch_leaf_gather(p, leaf_idx, ws.perm, s);
+        if (timed) stage_mark(s);
+    }
     if (e != hipSuccess) return set_device_error(e, "leaf kernel launch");
     if (timed) stage_mark(s);
     return FFF_OK;
@@ -271,17 +275,13 @@ int fff_forward_hard(const void* x, const void* node_w, const void* node_b, cons
     if (path == kPathToken) {
         stage_mark(s);
         hipError_t e = launch_token_block(p, leaf_idx, s);
-        stage_mark(s);
-        stage_mark(s);
-        stage_mark(s);
+        for (int k = 0; k < 4; ++k) stage_mark(s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "token-block kernel launch");
     }
     if (path == kPathFused) {
         stage_mark(s);
         hipError_t e = launch_walk_fused(p, leaf_idx, s);
-        stage_mark(s);
-        stage_mark(s);
-        stage_mark(s);
+        for (int k = 0; k < 4; ++k) stage_mark(s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "fused walk kernel launch");
     }
     Workspace ws;
@@ -407,16 +407,16 @@ int fff_stage_times(double* ms, int64_t* calls) {
         std::lock_guard<std::mutex> lock(g_mu);
         ev.swap(g_stage_events);
     }
-    ms[0] = ms[1] = ms[2] = 0.0;
+    for (int k = 0; k < 4; ++k) ms[k] = 0.0;
     *calls = 0;
     int rc = FFF_OK;
-    for (size_t i = 0; i + 3 < ev.size(); i += 4) {
-        if (hipEventSynchronize(ev[i + 3]) != hipSuccess) { rc = FFF_ERR_DEVICE; break; }
-        float d[3];
+    for (size_t i = 0; i + 4 < ev.size(); i += 5) {
+        if (hipEventSynchronize(ev[i + 4]) != hipSuccess) { rc = FFF_ERR_DEVICE; break; }
+        float d[4];
         bool ok = true;
-        for (int k = 0; k < 3; ++k) ok = ok && hipEventElapsedTime(&d[k], ev[i + k], ev[i + k + 1]) == hipSuccess;
+        for (int k = 0; k < 4; ++k) ok = ok && hipEventElapsedTime(&d[k], ev[i + k], ev[i + k + 1]) == hipSuccess;
         if (!ok) { rc = FFF_ERR_DEVICE; break; }
-        for (int k = 0; k < 3; ++k) ms[k] += d[k];
+        for (int k = 0; k < 4; ++k) ms[k] += d[k];
         *calls += 1;
     }
     for (hipEvent_t e : ev) (void)hipEventDestroy(e);

@@ -72,9 +72,10 @@ hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, 
 hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order,
                               hipStream_t s);
 // MFMA tile path over tokens grouped by leaf (perm, and the leaf of every slot); needs tiles_shape_ok(p).
+// Two launches (hidden activations, output rows); `between`, if given, is called between them.
 bool tiles_shape_ok(const Problem& p);
 hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const int32_t* perm, void* hidden,
-                             hipStream_t s);
+                             hipStream_t s, void (*between)(hipStream_t) = nullptr);
 
 // Whole forward pass in one launch, one block per token: the small-batch path, built for the
 // latency of the dependent loads rather than for throughput; needs token_shape_ok(p).

@@ -296,7 +296,7 @@ bool tiles_shape_ok(const Problem& p) {
 
 // hidden: workspace of T * L bf16 values
 hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const int32_t* perm, void* hidden,
-                             hipStream_t s) {
+                             hipStream_t s, void (*between)(hipStream_t)) {
     if (p.T == 0) return hipSuccess;
     TilesArgs a;
     a.x = (const uint16_t*)p.x;
@@ -323,6 +323,7 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const i
         leaf_hidden_kernel<false><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (between) between(s);
     const int64_t blocks_o = (a.n_tiles * a.units_per_tile + 3) / 4;
     leaf_output_kernel<<<dim3((unsigned)blocks_o), dim3(256), 0, s>>>(a);
     return hipGetLastError();
