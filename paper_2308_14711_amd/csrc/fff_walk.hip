@@ -396,13 +396,15 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     if (nvec <= 96) {
         const int64_t tpg = g_walk_tuning.tpg, blk = g_walk_tuning.block;
         if (tpg == 1 && blk == 512) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
-        // measured best for the fused launch on 768-wide rows: blocks of 512 (256 VGPRs per lane),
-        // two tokens per group, next tile's rows requested one iteration ahead (85 vs 88 us on the
-        // BERT-base-sized workload); the descent-only launch gains nothing from it
+        // measured best for the fused launch on 768-wide rows: blocks of 512 (256 VGPRs per lane) with
+        // four tokens per lane group (82 us on the BERT-base-sized workload, against 83 with two and
+        // 86 with two plus the next tile's rows requested one iteration ahead); the descent-only
+        // launch is fastest with blocks of 1024 and two tokens per group
         const bool exact = nvec == 96 && FUSED && p.O == p.D && vec_ok(p.out, p.O, BF16) &&
                            vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
-        if (exact && ((tpg == 0 && blk == 0) || g_walk_tuning.prefetch))
+        if (exact && g_walk_tuning.prefetch)
             return run_walk_t<BF16, 16, 6, 2, 512, FUSED, true, true>(p, leaf_idx, s);
+        if (FUSED && tpg == 0 && blk == 0) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
         if (tpg == 1) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
         if (tpg == 2 && blk == 512) return run_walk<BF16, 16, 6, 2, 512, FUSED>(p, leaf_idx, s);
         if (tpg == 4 && blk == 512) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
