@@ -82,7 +82,7 @@ Layout layout_for(int64_t T, int depth) {
     l.o_offset = take(NL + 1);
     l.o_tileoff = take(NL + 1);
     l.o_matrix = take(c * NL);
-    l.o_hidden = take(8 * T);
+    l.o_hidden = take((int64_t)(kTilesMaxLeafWidth / 2) * T);   // T * L bf16 values, L up to the tile path's limit
     l.total = o;
     return l;
 }

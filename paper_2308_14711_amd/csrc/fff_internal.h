@@ -31,13 +31,14 @@ struct Workspace {
     int32_t* offset;     // [NL + 1]
     int32_t* tile_off;   // [NL + 1] exclusive prefix of per-leaf tile counts
     int32_t* chunk_cnt;  // [C, NL]  per-chunk histograms, then per-chunk bases
-    int32_t* hidden;     // [8 T]    hidden activations of the tile path, T * L bf16 (L <= 16)
+    int32_t* hidden;     // [16 T]   hidden activations of the tile path, T * L bf16 (L <= 32)
     int32_t* ctrl;       // [16]     ticket counters and totals
     int64_t n_chunks;
 };
 
 constexpr int kChunkTokens = 256;   // tokens per bucketing chunk
 constexpr int kTileRows = 16;       // rows of one MFMA tile
+constexpr int kTilesMaxLeafWidth = 32;   // widest leaf the MFMA tile path takes
 
 bool vec_ok(const void* p, int64_t row_elems, bool bf16);
 

@@ -1,4 +1,4 @@
-// K3 + K4, MFMA tile path (bf16, leaf width <= 16) -- the leaf networks of the
+// K3 + K4, MFMA tile path (bf16, leaf width <= 32) -- the leaf networks of the
 // leaves the tokens arrived at (Definition: each leaf is a <D, l, O>
 // feedforward block; Algorithm 1 returns its output), with every output row
 // written straight to its token's position.
@@ -23,7 +23,9 @@
 //               spare ones, so the bias rides in the same instruction
 //       D[token][o] = sum_n h[token][n] W2[leaf(token)][n][o] + b2[leaf(token)][o]
 //
-// A tile with more than 16 / l runs takes several passes.  W2 is stored with o
+// A tile with more than 16 / l runs takes several passes.  Leaves of 17..32 neurons take one run
+// per pass, as two blocks of 16 rows in the hidden kernel (two accumulators over one token operand)
+// and as a second, accumulating instruction in the output kernel.  W2 is stored with o
 // contiguous (per neuron, its O output weights), while the instruction wants K
 // contiguous per lane: a lane loads 8 consecutive o of its 4 K rows and
 // transposes in registers; column j of the c-th MFMA of a 128-wide o range
@@ -93,7 +95,10 @@ __device__ __forceinline__ int32_t leaf_of_run(const TileColumn& c, int run) {
 // a pair) and are turned into the MFMA operand layout through a wave-private LDS buffer; piece c
 // (16 bytes) of row r sits at slot 8 r + ((c + r / 2) mod 8), which keeps both the writes and the
 // operand reads free of bank conflicts.
-template <bool DTAIL>
+//
+// NB = 1: leaf width <= 16, several runs per pass.  NB = 2: leaf width 17..32, one run per pass,
+// its neurons in two blocks of 16 rows that share the token operand (two accumulators).
+template <bool DTAIL, int NB>
 __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
     __shared__ uint4 stage[4][(kChunk / 2) * 128];   // per wave: kChunk / 2 pairs x 16 rows x 8 pieces
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -101,10 +106,11 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
     if (tile >= a.n_tiles) return;           // whole waves leave; nothing below synchronises the block
     const int j = lane & 15, kg = lane >> 4;
     const int D = a.D, L = a.L;
-    const int P = 16 / L;                    // runs per pass
+    const int P = NB == 1 ? 16 / L : 1;      // runs per pass
     const int n_pairs = (D + 63) / 64;       // pairs of K steps (64 elements of a row each)
     const TileColumn c = tile_column(a, tile, j);
-    const int rr_i = j / L, n_i = j % L;     // A row j = (run rr_i of the pass, neuron n_i)
+    // A row j of block b = (run rr_i of the pass, neuron n_i + 16 b)
+    const int rr_i = NB == 1 ? j / L : 0, n_i = NB == 1 ? j % L : j;
     uint4* my_stage = stage[wave];
 
     // loader role of this lane: piece lane % 8 of rows lane / 8 and lane / 8 + 8
@@ -123,20 +129,30 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
             const int32_t lf = leaf_of_run(c, pass + rr);
             if (rr_i == rr) row_leaf = lf;
         }
-        const uint16_t* arow = a.w1 + ((int64_t)(row_leaf >= 0 ? row_leaf : 0) * L + n_i) * D + 16 * kg;
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        const uint16_t* arow[NB];
+        bool a_ok[NB];
+        f32x4_t acc[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            a_ok[b] = row_leaf >= 0 && n_i + 16 * b < L;
+            arow[b] = a.w1 + ((int64_t)(a_ok[b] ? row_leaf : 0) * L + (a_ok[b] ? n_i + 16 * b : 0)) * D + 16 * kg;
+            acc[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
         for (int pp0 = 0; pp0 < n_pairs; pp0 += kChunk / 2) {
-            uint4 av[kChunk], xv[kChunk];
+            uint4 av[NB][kChunk], xv[kChunk];
 #pragma unroll
             for (int u = 0; u < kChunk; ++u) {
-                av[u] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < NB; ++b) av[b][u] = make_uint4(0, 0, 0, 0);
                 xv[u] = make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int u = 0; u < kChunk; ++u) {
                 const int pp = pp0 + (u >> 1);                  // wave-uniform
                 const int k0 = 64 * pp + 8 * (u & 1);           // + 16 kg is in arow
-                if (pp < n_pairs && row_leaf >= 0 && (!DTAIL || k0 + 16 * kg < D)) av[u] = *(const uint4*)(arow + k0);
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    if (pp < n_pairs && a_ok[b] && (!DTAIL || k0 + 16 * kg < D)) av[b][u] = *(const uint4*)(arow[b] + k0);
                 // u even: rows 0..7 of pair pp, u odd: rows 8..15
                 const int32_t tk = (u & 1) ? tok_hi : tok_lo;
                 if (pp < n_pairs && tk >= 0 && (!DTAIL || 64 * pp + 8 * lc < D))
@@ -149,19 +165,47 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
 #pragma unroll
             for (int u = 0; u < kChunk; ++u) {
                 const uint4 bv = my_stage[128 * (u >> 1) + ((u & 1) ? rd1 : rd0)];
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[u]),
-                                                              __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[b][u]),
+                                                                     __builtin_bit_cast(bf16x8_t, bv), acc[b], 0, 0, 0);
             }
         }
         // lane (j, kg) holds rows 4 kg + q of column j: the entries of the token's own run are its
         // hidden pre-activations
-        if (L % 4 == 0) {
+        if (NB > 1) {
+            // one run per pass; rows 4 kg + q of block b are neurons 16 b + 4 kg + q
+            if (c.tok >= 0 && c.run == pass) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const int n0 = 16 * b + 4 * kg;
+                    if (L % 4 == 0) {
+                        if (n0 < L) {
+                            float v[4];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                v[q] = activate(acc[b][q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n0 + q]), a.act);
+                            *(uint2*)(a.hidden + (int64_t)c.tok * L + n0) =
+                                make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+                        }
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            if (n0 + q < L) {
+                                const float v = activate(acc[b][q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n0 + q]), a.act);
+                                a.hidden[(int64_t)c.tok * L + n0 + q] = f32_to_bf16(v);
+                            }
+                        }
+                    }
+                }
+            }
+        } else if (L % 4 == 0) {
             const int rr = (4 * kg) / L, n0 = (4 * kg) % L;
             if (c.tok >= 0 && rr < P && c.run == pass + rr) {
                 float v[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    v[q] = activate(acc[q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n0 + q]), a.act);
+                    v[q] = activate(acc[0][q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n0 + q]), a.act);
                 *(uint2*)(a.hidden + (int64_t)c.tok * L + n0) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
             }
         } else {
@@ -169,7 +213,7 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
             for (int q = 0; q < 4; ++q) {
                 const int rho = 4 * kg + q, rr = rho / L, n = rho % L;
                 if (c.tok >= 0 && rr < P && c.run == pass + rr) {
-                    const float v = activate(acc[q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n]), a.act);
+                    const float v = activate(acc[0][q] + bf16_to_f32(a.b1[(int64_t)c.leaf * L + n]), a.act);
                     a.hidden[(int64_t)c.tok * L + n] = f32_to_bf16(v);
                 }
             }
@@ -178,6 +222,10 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
 }
 
 // ---- output kernel: out[token] = W2[leaf]^T h[token] + b2[leaf] ----
+//
+// WIDE (leaf width 17..32): one run per pass; the first instruction carries neurons 0..15 and the
+// bias, a second one accumulates neurons 16..31 on top.
+template <bool WIDE>
 __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
     const int lane = threadIdx.x & 63;
     const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -186,7 +234,7 @@ __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
     const int r_first = (int)(unit % a.units_per_tile) * kRangesPerWave;   // first 128-wide range of this wave
     const int j = lane & 15, kg = lane >> 4;
     const int O = a.O, L = a.L;
-    const int P = 16 / L;
+    const int P = WIDE ? 1 : 16 / L;
     const TileColumn c = tile_column(a, tile, j);
 
     // token rows this lane stores: rows 4 kg + q of the tile
@@ -211,41 +259,57 @@ __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
             const int32_t lf = leaf_of_run(c, pass + rr);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                if ((4 * kg + q) / L == rr) { w_leaf[q] = lf; w_ok[q] = true; }
+                if (WIDE ? rr == 0 : (4 * kg + q) / L == rr) { w_leaf[q] = lf; w_ok[q] = true; }
                 if (4 * kg + q == rr) { b_leaf[q] = lf; b_ok[q] = true; }
             }
         }
         uint32_t h01 = 0, h23 = 0;               // this lane's four K slots of h, as two bf16 pairs
+        uint32_t g01 = 0, g23 = 0;               // WIDE: the same for neurons 16 + 4 kg + q
         float iq[4];
         if (L % 4 == 0) {
             // the four slots are four consecutive neurons of one run: one 8-byte load
-            const int rr = (4 * kg) / L, n0 = (4 * kg) % L;
+            const int rr = WIDE ? 0 : (4 * kg) / L, n0 = WIDE ? 4 * kg : (4 * kg) % L;
             if (c.tok >= 0 && rr < P && c.run == pass + rr) {
                 const uint2 hv = *(const uint2*)(a.hidden + (int64_t)c.tok * L + n0);
                 h01 = hv.x;
                 h23 = hv.y;
+                if (WIDE && 16 + n0 < L) {
+                    const uint2 gv = *(const uint2*)(a.hidden + (int64_t)c.tok * L + 16 + n0);
+                    g01 = gv.x;
+                    g23 = gv.y;
+                }
             }
         }
+        const uint16_t* wptr2[4];
+        bool w2_ok[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int rho = 4 * kg + q, rr = rho / L, n = rho % L;
+            const int rho = 4 * kg + q, rr = WIDE ? 0 : rho / L, n = WIDE ? rho : rho % L;
             wptr[q] = a.w2 + ((int64_t)w_leaf[q] * L + n) * O + 8 * j;
             bptr[q] = a.b2 + (int64_t)b_leaf[q] * O + 8 * j;
+            w2_ok[q] = WIDE && w_ok[q] && 16 + rho < L;
+            wptr2[q] = a.w2 + ((int64_t)w_leaf[q] * L + (w2_ok[q] ? 16 + rho : 0)) * O + 8 * j;
             if (L % 4 != 0) {
                 const bool mine = c.tok >= 0 && rr < P && c.run == pass + rr;
                 const uint32_t hb = mine ? a.hidden[(int64_t)c.tok * L + n] : 0u;
                 if (q < 2) h01 |= hb << (16 * q);
                 else h23 |= hb << (16 * (q - 2));
+                if (WIDE) {
+                    const uint32_t gb = (mine && 16 + rho < L) ? a.hidden[(int64_t)c.tok * L + 16 + rho] : 0u;
+                    if (q < 2) g01 |= gb << (16 * q);
+                    else g23 |= gb << (16 * (q - 2));
+                }
             }
             iq[q] = (c.tok >= 0 && rho < P && c.run == pass + rho) ? 1.0f : 0.0f;
         }
         const uint4 a2u = make_uint4(h01, h23, pack_bf16x2(iq[0], iq[1]), pack_bf16x2(iq[2], iq[3]));
         const bf16x8_t a2 = __builtin_bit_cast(bf16x8_t, a2u);
+        const bf16x8_t a2w = __builtin_bit_cast(bf16x8_t, make_uint4(g01, g23, 0u, 0u));
         bool st_ok[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) st_ok[q] = run_row[q] >= pass && run_row[q] < pass + P;
 
-        uint4 wv[kRangesPerWave][4], bv[kRangesPerWave][4];
+        uint4 wv[kRangesPerWave][4], bv[kRangesPerWave][4], wv2[WIDE ? kRangesPerWave : 1][4];
 #pragma unroll
         for (int g = 0; g < kRangesPerWave; ++g) {
             const int o0 = 128 * (r_first + g);
@@ -256,6 +320,10 @@ __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
                 bv[g][q] = make_uint4(0, 0, 0, 0);
                 if (ok && w_ok[q]) wv[g][q] = *(const uint4*)(wptr[q] + o0);
                 if (ok && b_ok[q]) bv[g][q] = *(const uint4*)(bptr[q] + o0);
+                if (WIDE) {
+                    wv2[g][q] = make_uint4(0, 0, 0, 0);
+                    if (ok && w2_ok[q]) wv2[g][q] = *(const uint4*)(wptr2[q] + o0);
+                }
             }
         }
 #pragma unroll
@@ -272,6 +340,12 @@ __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
                                            pack_half(dword_of(b[0], cc), dword_of(b[1], cc), cc & 1),
                                            pack_half(dword_of(b[2], cc), dword_of(b[3], cc), cc & 1));
                 d[cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8_t, f), zero, 0, 0, 0);
+                if (WIDE) {
+                    const uint4* w2r = wv2[g];
+                    const uint4 f2 = make_uint4(pack_half(dword_of(w2r[0], cc), dword_of(w2r[1], cc), cc & 1),
+                                                pack_half(dword_of(w2r[2], cc), dword_of(w2r[3], cc), cc & 1), 0u, 0u);
+                    d[cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2w, __builtin_bit_cast(bf16x8_t, f2), d[cc], 0, 0, 0);
+                }
             }
             if (o0 + 8 * j < O) {
 #pragma unroll
@@ -287,10 +361,10 @@ __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
     }
 }
 
-// bf16, leaf width <= 16, 16-byte aligned rows of x, W1, W2, b2 and out
+// bf16, leaf width <= 32, 16-byte aligned rows of x, W1, W2, b2 and out
 bool tiles_shape_ok(const Problem& p) {
     auto al = [](const void* q, uintptr_t m) { return (reinterpret_cast<uintptr_t>(q) & (m - 1)) == 0; };
-    return p.bf16 && p.L <= 16 && p.D % 8 == 0 && p.O % 8 == 0 && p.D < (1 << 30) && p.O < (1 << 30) &&
+    return p.bf16 && p.L <= kTilesMaxLeafWidth && p.D % 8 == 0 && p.O % 8 == 0 && p.D < (1 << 30) && p.O < (1 << 30) &&
            al(p.x, 16) && al(p.leaf_w1, 16) && al(p.leaf_w2, 16) && al(p.leaf_b2, 16) && al(p.out, 16);
 }
 
@@ -317,15 +391,20 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const i
     const int n_ranges = (int)((p.O + 127) / 128);
     a.units_per_tile = (n_ranges + kRangesPerWave - 1) / kRangesPerWave;
     const int64_t blocks_h = (a.n_tiles + 3) / 4;
-    if (p.D % 64 != 0)
-        leaf_hidden_kernel<true><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
-    else
-        leaf_hidden_kernel<false><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
+    const bool wide = p.L > 16;
+    if (p.D % 64 != 0) {
+        if (wide) leaf_hidden_kernel<true, 2><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
+        else leaf_hidden_kernel<true, 1><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
+    } else {
+        if (wide) leaf_hidden_kernel<false, 2><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
+        else leaf_hidden_kernel<false, 1><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (between) between(s);
     const int64_t blocks_o = (a.n_tiles * a.units_per_tile + 3) / 4;
-    leaf_output_kernel<<<dim3((unsigned)blocks_o), dim3(256), 0, s>>>(a);
+    if (wide) leaf_output_kernel<true><<<dim3((unsigned)blocks_o), dim3(256), 0, s>>>(a);
+    else leaf_output_kernel<false><<<dim3((unsigned)blocks_o), dim3(256), 0, s>>>(a);
     return hipGetLastError();
 }
 

@@ -78,7 +78,11 @@ SMALL = [
     ("tiles_L5",          250, 64,  64,  3, 5, W.ACT_GELU, W.DTYPE_BF16),
     ("tiles_L16",         300, 128, 200, 2, 16, W.ACT_RELU, W.DTYPE_BF16),
     ("tiles_sparse",      200, 64,  64,  10, 4, W.ACT_GELU, W.DTYPE_BF16),
-    ("gather_L17",        150, 64,  64,  3, 17, W.ACT_GELU, W.DTYPE_BF16),
+    ("tiles_L17",         150, 64,  64,  3, 17, W.ACT_GELU, W.DTYPE_BF16),
+    ("tiles_L24",         500, 128, 264, 2, 24, W.ACT_RELU, W.DTYPE_BF16),
+    ("tiles_L30_sparse",  260, 72,  40,  6, 30, W.ACT_GELU, W.DTYPE_BF16),
+    ("tiles_L32",         900, 768, 768, 2, 32, W.ACT_GELU, W.DTYPE_BF16),
+    ("gather_L33",        150, 64,  64,  3, 33, W.ACT_GELU, W.DTYPE_BF16),
     # small batches: the one-block-per-token launch (depths around multiples of its 3-level rounds,
     # rows of 1, 2, 4 and 8 vectors per lane, outputs wider than inputs, a batch above its grid cap)
     ("latency_L32_d7",    256, 768, 768, 7, 32, W.ACT_GELU, W.DTYPE_BF16),
