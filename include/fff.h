@@ -139,7 +139,7 @@ int fff_release_workspace(void);
 /*
  * Tuning and test switches (process-wide; not thread-safe against running calls).
  *   "leaf_path"      staged path only: 0 = the MFMA tile kernels when the shape allows them
- *                    (bf16, 3 <= leaf_width <= 16, D % 8 == 0, O % 8 == 0, 16-byte aligned
+ *                    (bf16, 3 <= leaf_width <= 32, D % 8 == 0, O % 8 == 0, 16-byte aligned
  *                    rows), else the gather kernel (default); 1 = always the gather kernel;
  *                    2 = the tile kernels also for leaf_width 1 and 2
  *   "path"           0 = choose by shape and batch size (default), 1 = one fused launch
@@ -150,9 +150,10 @@ int fff_release_workspace(void);
  *                    leaf's neurons split over the block's waves; rows of at most 512
  *                    16-byte vectors); a path the shape does not allow falls back to one it
  *                    does.  The default takes 4 for batches of up to "token_max_T" tokens
- *                    (8 times that where leaf_width > 8 rules out the fused launch), then
- *                    staged when leaf_width >= 4, a leaf sees >= 32 tokens on average and
- *                    T > 8192, else fused
+ *                    (6 times that where leaf_width > 8 rules out the fused launch), then
+ *                    staged when a leaf sees >= 32 tokens on average, T > 8192 and the leaves
+ *                    are wide (leaf_width >= 8, or >= 4 with more than 5 MB of leaf weights
+ *                    in total), else fused
  *   "token_max_T"    see "path" (default 512)
  *   "walk_tpg", "walk_block", "walk_top", "walk_bpc", "walk_prefetch"
  *                    experiment switches of the fused/descent kernel (tokens per lane

@@ -31,7 +31,7 @@ struct Options {
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
     int64_t bucket_kernel = 0;   // 0 auto, 1 one-launch kernel, 2 chunk-matrix kernels
     int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
-    int64_t token_max_T = 512;   // batches up to this many tokens (8x where no fused launch fits) go one block per token
+    int64_t token_max_T = 512;   // batches up to this many tokens (6x where no fused launch fits) go one block per token
 } g_opt;
 
 // Events recorded around the stages of fff_forward_hard while "stage_timing" is on:
@@ -188,16 +188,21 @@ int choose_path(const Problem& p) {
     if (g_opt.path == kPathGeneric) return kPathGeneric;
     // a small batch cannot fill the chip with streaming work: one block per token, built for latency
     // (measured crossovers on 768-wide rows: the fused launch catches up near 1024 tokens; leaves too
-    // wide for it leave only the staged path, which needs several thousand tokens to pay off)
+    // wide for it leave only the staged path, which overtakes between 2048 and 4096 tokens)
     if (g_opt.path == kPathAuto && token_ok &&
-        p.T <= (fused_ok ? g_opt.token_max_T : 8 * g_opt.token_max_T))
+        p.T <= (fused_ok ? g_opt.token_max_T : 6 * g_opt.token_max_T))
         return kPathToken;
     if (!fused_ok && !staged_ok) return token_ok ? kPathToken : kPathGeneric;
     if (!staged_ok) return kPathFused;
     if (!fused_ok) return kPathStaged;
-    // grouping pays once a leaf is wide enough and visited by enough tokens to share its rows
+    // grouping pays once a leaf is visited by enough tokens to share its rows and is either wide
+    // (8 neurons) or, from 4 neurons on, the leaf weights together outgrow the 4 MB L2 of one XCD,
+    // which the fused launch relies on for its per-token row fetches (measured on 768-wide rows:
+    // depth 8 ties at 6 neurons, depth 10 at 4, depth 4 only at 8)
     const int64_t tokens_per_leaf = p.T >> p.depth;
-    return (p.L >= 4 && tokens_per_leaf >= 32 && p.T > 8192) ? kPathStaged : kPathFused;
+    const int64_t leaf_bytes = ((int64_t)1 << p.depth) * (p.L * (p.D + p.O) + p.O) * (p.bf16 ? 2 : 4);
+    const bool wide = p.L >= 8 || (p.L >= 4 && leaf_bytes >= (int64_t)5 << 20);
+    return (wide && tokens_per_leaf >= 32 && p.T > 8192) ? kPathStaged : kPathFused;
 }
 
 // K2 with whichever kernel set takes the sizes; outputs may be null (then workspace arrays are used).
