@@ -163,8 +163,11 @@ int fff_release_workspace(void);
  *   "bucketing"      1 (default) = the leaf kernel visits tokens grouped by leaf,
  *                    0 = in token order (no bucketing stage)
  *   "last_path"      read it after a call: the path (1, 2, 3 or 4) fff_forward_hard took
- *   "bucket_kernel"  0 = choose by size (default), 1 = the one-launch bucketing kernel when
- *                    the sizes allow it, 2 = always the chunk-matrix kernels
+ *   "bucket_kernel"  0 = choose by size (default: the token-chunk kernel up to 131072 tokens
+ *                    and 4096 leaves, then the leaf-range kernel up to 2^21 tokens and 2^19
+ *                    leaves, then the chunk-matrix kernels), 1 = the leaf-range kernel when the
+ *                    sizes allow it, 2 = always the chunk-matrix kernels, 3 = the token-chunk
+ *                    kernel when the sizes allow it
  *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages
  *                    (read them with fff_stage_times); 0 (default) = off
  * Unknown names or negative values return FFF_ERR_UNSUPPORTED.

@@ -29,7 +29,7 @@ struct Options {
     int64_t leaf_path = 0;       // 0 auto (MFMA tiles when the shape allows), 1 gather kernel only
     int64_t bucketing = 1;       // 0: leaf kernel visits tokens in token order
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
-    int64_t bucket_kernel = 0;   // 0 auto, 1 one-launch kernel, 2 chunk-matrix kernels
+    int64_t bucket_kernel = 0;   // 0 auto, 1 leaf-range kernel, 2 chunk-matrix kernels, 3 token-chunk kernel
     int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
     int64_t token_max_T = 512;   // batches up to this many tokens (6x where no fused launch fits) go one block per token
 } g_opt;
@@ -209,6 +209,10 @@ int choose_path(const Problem& p) {
 int run_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws, int32_t* count,
                int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s) {
     hipError_t e;
+    if ((g_opt.bucket_kernel == 0 || g_opt.bucket_kernel == 3) && bucket_hist_ok(T, depth)) {
+        e = launch_bucket_hist(leaf_idx, T, depth, count, offset, perm, slot_leaf, s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
+    }
     if (g_opt.bucket_kernel != 2 && bucket_onepass_ok(T, depth)) {
         e = launch_bucket_onepass(leaf_idx, T, depth, count, offset, perm, slot_leaf, s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");

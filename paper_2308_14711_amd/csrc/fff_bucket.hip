@@ -29,6 +29,8 @@
 #include "fff_device.h"
 #include "fff_internal.h"
 
+#include <type_traits>
+
 namespace fff {
 
 __device__ __forceinline__ int32_t load_l2(const int32_t* p) {
@@ -379,6 +381,132 @@ hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, 
     const int vec = (reinterpret_cast<uintptr_t>(leaf_idx) & 15u) == 0;
     bucket_onepass_kernel<<<dim3((unsigned)blocks), dim3(1024), lds, s>>>(leaf_idx, T, NL, (int)per_block, vec,
                                                                           count, offset, perm, slot_leaf);
+    return hipGetLastError();
+}
+
+// ---- one launch, a block per chunk of tokens (moderate T, up to 4096 leaves) ----
+//
+// Every block builds the histogram of ALL tokens in LDS by itself (one 64-bit LDS atomic per token:
+// the low word counts the leaf's tokens, the high word those that come before the block's own
+// chunk), scans it, and then places only its own chunk: position = start of the leaf + same-leaf
+// tokens of earlier chunks + rank among the same-leaf tokens of the chunk (counted by comparing
+// against the chunk's leaf ids in LDS, a broadcast read per step).  The histogram work is repeated
+// by every block but reads 4 bytes per token from L2 and runs on all CUs at once; for the sizes
+// taken here that is cheaper than two passes over the tokens with a block per leaf range.
+constexpr int kHistMaxLeaves = 4096;     // 32 KB of 64-bit counters
+constexpr int kHistMaxChunk = 512;       // tokens a block places
+constexpr int kHistBlocks = 256;
+
+// NARROW (T < 65536): both counts fit 16 bits and share one 32-bit counter, whose LDS atomics are
+// cheaper than the 64-bit ones.
+template <bool NARROW>
+__global__ __launch_bounds__(1024) void bucket_hist_kernel(const int32_t* __restrict__ leaf_idx, int64_t T,
+                                                           int n_leaves, int chunk, int vec,
+                                                           int32_t* __restrict__ count,
+                                                           int32_t* __restrict__ offset,
+                                                           int32_t* __restrict__ perm,
+                                                           int32_t* __restrict__ slot_leaf) {
+    typedef typename std::conditional<NARROW, uint32_t, unsigned long long>::type Counter;
+    constexpr int kHigh = NARROW ? 16 : 32;
+    extern __shared__ unsigned long long hist_raw[];         // [n_leaves] counters: (before << kHigh) | total
+    Counter* hist = (Counter*)hist_raw;
+    __shared__ int32_t s_leaf[kHistMaxChunk];
+    __shared__ int32_t s_wsum[kOnepassWaves];
+    const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
+    const int64_t lo = (int64_t)blockIdx.x * chunk;
+    const int64_t hi = lo + chunk < T ? lo + chunk : T;
+    const int n_own = (int)(hi - lo);
+
+    for (int i = tid; i < n_leaves; i += 1024) hist[i] = 0;
+    if (tid < n_own) s_leaf[tid] = leaf_idx[lo + tid];
+    __syncthreads();
+
+    // histogram of all tokens; a token before this block's chunk also counts in the high word
+    const int64_t n4 = (T + 3) / 4;
+    for (int64_t q0 = 0; q0 < n4; q0 += 4 * 1024) {
+        int4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t q = q0 + (int64_t)u * 1024 + tid;
+            v[u] = q < n4 ? load_leaf4(leaf_idx, 4 * q, T, vec != 0) : make_int4(-1, -1, -1, -1);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t t0 = 4 * (q0 + (int64_t)u * 1024 + tid);
+            const int32_t e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if ((uint32_t)e[k] < (uint32_t)n_leaves)
+                    atomicAdd(&hist[e[k]], (Counter)1 | (t0 + k < lo ? ((Counter)1 << kHigh) : (Counter)0));
+        }
+    }
+    __syncthreads();
+
+    // exclusive scan of the totals; afterwards hist[leaf] = (start of the leaf) + (tokens before the chunk)
+    const int per = (n_leaves + 1023) / 1024;                // leaves per thread, at most 4
+    Counter mine[kHistMaxLeaves / 1024];
+    const Counter low = ((Counter)1 << kHigh) - 1;
+    int32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kHistMaxLeaves / 1024; ++i) {
+        const int leaf = tid * per + i;
+        mine[i] = (i < per && leaf < n_leaves) ? hist[leaf] : (Counter)0;
+        sum += (int32_t)(mine[i] & low);
+    }
+    const int32_t inc = wave_incl_scan(sum, lane);
+    if (lane == kWave - 1) s_wsum[w] = inc;
+    __syncthreads();
+    int32_t start = inc - sum;
+    for (int ww = 0; ww < w; ++ww) start += s_wsum[ww];
+#pragma unroll
+    for (int i = 0; i < kHistMaxLeaves / 1024; ++i) {
+        const int leaf = tid * per + i;
+        if (i < per && leaf < n_leaves) {
+            const int32_t total = (int32_t)(mine[i] & low);
+            hist[leaf] = (Counter)(uint32_t)(start + (int32_t)(mine[i] >> kHigh));
+            if (blockIdx.x == 0) {
+                if (count) count[leaf] = total;
+                if (offset) offset[leaf] = start;
+            }
+            start += total;
+        }
+    }
+    if (blockIdx.x == 0 && offset && tid == 0) offset[n_leaves] = (int32_t)T;
+    __syncthreads();
+    if (!perm || tid >= n_own) return;
+
+    // rank of token lo + tid among the chunk's earlier tokens of the same leaf
+    const int32_t leaf = s_leaf[tid];
+    if ((uint32_t)leaf >= (uint32_t)n_leaves) return;
+    int rank = 0;
+    const int4* s4 = (const int4*)s_leaf;
+    for (int j4 = 0; 4 * j4 < tid; ++j4) {
+        const int4 v = s4[j4];
+        const int j = 4 * j4;
+        rank += (v.x == leaf) + (v.y == leaf && j + 1 < tid) + (v.z == leaf && j + 2 < tid) + (v.w == leaf && j + 3 < tid);
+    }
+    const int32_t pos = (int32_t)(uint32_t)hist[leaf] + rank;
+    perm[pos] = (int32_t)(lo + tid);
+    if (slot_leaf) slot_leaf[pos] = leaf;
+}
+
+bool bucket_hist_ok(int64_t T, int depth) {
+    return ((int64_t)1 << depth) <= kHistMaxLeaves && T <= (int64_t)kHistBlocks * kHistMaxChunk;
+}
+
+hipError_t launch_bucket_hist(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, int32_t* offset,
+                              int32_t* perm, int32_t* slot_leaf, hipStream_t s) {
+    const int NL = 1 << depth;
+    int chunk = (int)((T + kHistBlocks - 1) / kHistBlocks);
+    if (chunk < 64) chunk = 64;
+    const int64_t blocks = (T + chunk - 1) / chunk;
+    const int vec = (reinterpret_cast<uintptr_t>(leaf_idx) & 15u) == 0;
+    if (T < 65536)
+        bucket_hist_kernel<true><<<dim3((unsigned)blocks), dim3(1024), sizeof(uint32_t) * (size_t)NL, s>>>(
+            leaf_idx, T, NL, chunk, vec, count, offset, perm, slot_leaf);
+    else
+        bucket_hist_kernel<false><<<dim3((unsigned)blocks), dim3(1024), sizeof(unsigned long long) * (size_t)NL, s>>>(
+            leaf_idx, T, NL, chunk, vec, count, offset, perm, slot_leaf);
     return hipGetLastError();
 }
 

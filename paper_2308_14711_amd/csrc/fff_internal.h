@@ -68,6 +68,12 @@ bool bucket_onepass_ok(int64_t T, int depth);
 hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count,
                                  int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s);
 
+// K2 in one launch with a block per chunk of tokens (every block histograms all tokens in LDS);
+// for T up to 131072 and up to 4096 leaves; same outputs, any may be null.
+bool bucket_hist_ok(int64_t T, int depth);
+hipError_t launch_bucket_hist(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, int32_t* offset,
+                              int32_t* perm, int32_t* slot_leaf, hipStream_t s);
+
 // K3 + K4: leaf networks and output rows.
 //   order == nullptr: slot i is token i.  Otherwise slot i is token order[i].
 hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order,

@@ -195,8 +195,10 @@ def test_runs_on_a_side_stream():
 
 @pytest.mark.parametrize("depth,T,kind", [(0, 10, "u"), (3, 1, "u"), (3, 1000, "u"), (8, 5000, "zipf"),
                                           (11, 65536, "u"), (15, 16384, "zipf"), (20, 10000, "u"),
-                                          (6, 4096, "one"), (19, 70001, "zipf"), (10, 300000, "u")])
-@pytest.mark.parametrize("kernel", [1, 2])
+                                          (6, 4096, "one"), (19, 70001, "zipf"), (10, 300000, "u"),
+                                          (8, 50432, "u"), (12, 131072, "zipf"), (12, 131071, "u"), (2, 63, "u"),
+                                          (9, 16385, "zipf"), (3, 65535, "one"), (3, 65536, "one")])
+@pytest.mark.parametrize("kernel", [0, 1, 2, 3])
 def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
     import torch
     import paper_2308_14711_amd as F
