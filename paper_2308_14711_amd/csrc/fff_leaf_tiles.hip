@@ -53,6 +53,7 @@ struct TilesArgs {
 };
 
 constexpr int kChunk = 8;            // K steps of the first contraction fetched per lane per group (4 pairs)
+constexpr int kChunkPipelined = 4;   // the same where two groups are in flight (narrow leaves)
 constexpr int kRangesPerWave = 2;    // 128-wide output ranges per wave of the output kernel
 
 // the c-th bf16 of the 8 held by a 16-byte vector, for the register transposes
@@ -61,6 +62,16 @@ __device__ __forceinline__ uint32_t dword_of(const uint4& v, int c) {
 }
 __device__ __forceinline__ uint32_t pack_half(uint32_t a, uint32_t b, int hi) {
     return hi ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin (block b runs on XCD b mod 8) and every XCD has
+// its own L2.  Tiles are ordered by leaf, so consecutive tiles want the same weight rows: block b
+// takes logical index (b mod 8) * (grid / 8) + b / 8, which gives each XCD one contiguous range of
+// tiles and lets a leaf's weights be fetched into one L2 instead of all eight.  The grid is a
+// multiple of 8; logical indices past the work are idle blocks.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int64_t xcd_contiguous_block() {
+    return (int64_t)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
 }
 
 // What both kernels derive for a tile: this lane's column (slot j of the tile; all four 16-lane
@@ -102,9 +113,10 @@ template <bool DTAIL, int NB>
 __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
     __shared__ uint4 stage[4][(kChunk / 2) * 128];   // per wave: kChunk / 2 pairs x 16 rows x 8 pieces
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t tile = xcd_contiguous_block() * 4 + wave;
     if (tile >= a.n_tiles) return;           // whole waves leave; nothing below synchronises the block
     const int j = lane & 15, kg = lane >> 4;
+    constexpr int CH = NB == 1 ? kChunkPipelined : kChunk;   // K steps per group
     const int D = a.D, L = a.L;
     const int P = NB == 1 ? 16 / L : 1;      // runs per pass
     const int n_pairs = (D + 63) / 64;       // pairs of K steps (64 elements of a row each)
@@ -138,16 +150,16 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
             arow[b] = a.w1 + ((int64_t)(a_ok[b] ? row_leaf : 0) * L + (a_ok[b] ? n_i + 16 * b : 0)) * D + 16 * kg;
             acc[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
-        for (int pp0 = 0; pp0 < n_pairs; pp0 += kChunk / 2) {
-            uint4 av[NB][kChunk], xv[kChunk];
+        // one group = CH K steps: fetch (weights rows in operand layout, token rows coalesced) ...
+        auto fetch = [&](int pp0, uint4 (&av)[NB][CH], uint4 (&xv)[CH]) {
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
+            for (int u = 0; u < CH; ++u) {
 #pragma unroll
                 for (int b = 0; b < NB; ++b) av[b][u] = make_uint4(0, 0, 0, 0);
                 xv[u] = make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
+            for (int u = 0; u < CH; ++u) {
                 const int pp = pp0 + (u >> 1);                  // wave-uniform
                 const int k0 = 64 * pp + 8 * (u & 1);           // + 16 kg is in arow
 #pragma unroll
@@ -158,17 +170,41 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
                 if (pp < n_pairs && tk >= 0 && (!DTAIL || 64 * pp + 8 * lc < D))
                     xv[u] = load_stream((const uint4*)(((u & 1) ? src_hi : src_lo) + 64 * pp));
             }
+        };
+        // ... and consume: token rows through the wave's LDS buffer into operand layout, then the MFMAs
+        auto consume = [&](const uint4 (&av)[NB][CH], const uint4 (&xv)[CH]) {
             __builtin_amdgcn_wave_barrier();     // the operand reads of the previous group are done
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) my_stage[128 * (u >> 1) + ((u & 1) ? slot_hi : slot_lo)] = xv[u];
+            for (int u = 0; u < CH; ++u) my_stage[128 * (u >> 1) + ((u & 1) ? slot_hi : slot_lo)] = xv[u];
             __builtin_amdgcn_wave_barrier();     // LDS executes a wave's accesses in order
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
+            for (int u = 0; u < CH; ++u) {
                 const uint4 bv = my_stage[128 * (u >> 1) + ((u & 1) ? rd1 : rd0)];
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
                     acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[b][u]),
                                                                      __builtin_bit_cast(bf16x8_t, bv), acc[b], 0, 0, 0);
+            }
+        };
+        constexpr int kStep = CH / 2;        // pairs per group
+        if (NB == 1) {
+            // two groups in flight: the next one travels while this one is transposed and multiplied
+            uint4 av0[NB][CH], xv0[CH], av1[NB][CH], xv1[CH];
+            fetch(0, av0, xv0);
+            for (int pp0 = 0; pp0 < n_pairs; pp0 += 2 * kStep) {
+                const bool more = pp0 + kStep < n_pairs;
+                if (more) fetch(pp0 + kStep, av1, xv1);
+                consume(av0, xv0);
+                if (more) {
+                    if (pp0 + 2 * kStep < n_pairs) fetch(pp0 + 2 * kStep, av0, xv0);
+                    consume(av1, xv1);
+                }
+            }
+        } else {
+            for (int pp0 = 0; pp0 < n_pairs; pp0 += kStep) {
+                uint4 av[NB][CH], xv[CH];
+                fetch(pp0, av, xv);
+                consume(av, xv);
             }
         }
         // lane (j, kg) holds rows 4 kg + q of column j: the entries of the token's own run are its
@@ -228,7 +264,7 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
 template <bool WIDE>
 __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
     const int lane = threadIdx.x & 63;
-    const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t unit = xcd_contiguous_block() * 4 + (threadIdx.x >> 6);
     const int64_t tile = unit / a.units_per_tile;
     if (tile >= a.n_tiles) return;
     const int r_first = (int)(unit % a.units_per_tile) * kRangesPerWave;   // first 128-wide range of this wave
@@ -390,7 +426,7 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const i
     a.act = p.act;
     const int n_ranges = (int)((p.O + 127) / 128);
     a.units_per_tile = (n_ranges + kRangesPerWave - 1) / kRangesPerWave;
-    const int64_t blocks_h = (a.n_tiles + 3) / 4;
+    const int64_t blocks_h = ((a.n_tiles + 3) / 4 + kXcds - 1) / kXcds * kXcds;
     const bool wide = p.L > 16;
     if (p.D % 64 != 0) {
         if (wide) leaf_hidden_kernel<true, 2><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
@@ -402,7 +438,7 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (between) between(s);
-    const int64_t blocks_o = (a.n_tiles * a.units_per_tile + 3) / 4;
+    const int64_t blocks_o = ((a.n_tiles * a.units_per_tile + 3) / 4 + kXcds - 1) / kXcds * kXcds;
     if (wide) leaf_output_kernel<true><<<dim3((unsigned)blocks_o), dim3(256), 0, s>>>(a);
     else leaf_output_kernel<false><<<dim3((unsigned)blocks_o), dim3(256), 0, s>>>(a);
     return hipGetLastError();
