@@ -247,7 +247,7 @@ def main():
         if single:     # one launch did the whole path: it carries the whole path's bytes
             alg = dict(alg, walk_fused=alg["path"], token_block=alg["path"])
             names = ((("token_block" if F.fff_get_option("last_path") == 4 else "walk_fused"), d_ms),)
-        elif l2_ms > 0.1 * l_ms:   # the leaf stage ran as two kernels
+        elif F.fff_get_option("last_leaf_path") == 2:   # the leaf stage ran as two kernels
             names = (("descent", d_ms), ("bucketing", b_ms), ("leaf_hidden", l_ms), ("leaf_output", l2_ms))
         else:
             names = (("descent", d_ms), ("bucketing", b_ms), ("leaf", l_ms))

@@ -31,6 +31,7 @@ struct Options {
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
     int64_t bucket_kernel = 0;   // 0 auto, 1 leaf-range kernel, 2 chunk-matrix kernels, 3 token-chunk kernel
     int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
+    int64_t last_leaf_path = 0;  // read-only: leaf stage of the last staged call (1 gather kernel, 2 tile kernels)
     int64_t token_max_T = 512;   // batches up to this many tokens (6x where no fused launch fits) go one block per token
 } g_opt;
 
@@ -230,6 +231,7 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
     hipError_t e;
     if (!g_opt.bucketing) {
         if (timed) stage_mark(s);
+        g_opt.last_leaf_path = 1;
         e = launch_leaf_gather(p, leaf_idx, nullptr, s);
         if (timed) stage_mark(s);
         if (timed) stage_mark(s);
@@ -239,7 +241,9 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
     if (rc != FFF_OK) return rc;
     if (timed) stage_mark(s);
     // the MFMA tile path pays once a leaf has a few neurons; for 1-2 the VALU gather kernel is leaner
-    if (g_opt.leaf_path != 1 && tiles_shape_ok(p) && (p.L >= 3 || g_opt.leaf_path == 2))
+    const bool tiles = g_opt.leaf_path != 1 && tiles_shape_ok(p) && (p.L >= 3 || g_opt.leaf_path == 2);
+    g_opt.last_leaf_path = tiles ? 2 : 1;
+    if (tiles)
         e = launch_leaf_tiles(p, ws.slot_leaf, ws.perm, ws.hidden, s, timed ? stage_mark : nullptr);
     else {
         e = launch_leaf_gather(p, leaf_idx, ws.perm, s);
@@ -391,12 +395,14 @@ static int64_t* option_slot(const char* name) {
     if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
     if (!std::strcmp(name, "last_path")) return &g_opt.last_path;
+    if (!std::strcmp(name, "last_leaf_path")) return &g_opt.last_leaf_path;
     return nullptr;
 }
 
 int fff_set_option(const char* name, int64_t value) {
     int64_t* s = option_slot(name);
     if (!s || value < 0) return FFF_ERR_UNSUPPORTED;
+    if (s == &g_opt.last_path || s == &g_opt.last_leaf_path) return FFF_ERR_UNSUPPORTED;   // read-only
     *s = value;
     return FFF_OK;
 }

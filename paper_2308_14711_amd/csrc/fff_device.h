@@ -97,4 +97,15 @@ __device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
     __builtin_nontemporal_store(u, (u32x4_t*)p);
 }
 
+// Workgroups are dealt to the 8 XCDs round-robin (block b runs on XCD b mod 8) and every XCD
+// has its own L2.  Work that is ordered by leaf wants consecutive items on one XCD, since they
+// read the same weight rows: block b takes logical index (b mod 8) * (grid / 8) + b / 8, which
+// gives each XCD one contiguous range of the work and lets a leaf's weights be fetched into one
+// L2 instead of all eight.  The grid must be a multiple of 8; logical indices past the work are
+// idle blocks.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int64_t xcd_contiguous_block() {
+    return (int64_t)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
+}
+
 }  // namespace fff

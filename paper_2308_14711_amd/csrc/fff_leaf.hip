@@ -25,7 +25,8 @@ __global__ __launch_bounds__(256) void leaf_gather_kernel(
     __shared__ float hs[kGroups][kMaxLeafWidthGather];
     const int sub = threadIdx.x % LPT;
     const int g = threadIdx.x / LPT;
-    const int64_t slot = (int64_t)blockIdx.x * kGroups + g;
+    // in bucket order consecutive slots share a leaf: keep them on one XCD
+    const int64_t slot = (order ? xcd_contiguous_block() : (int64_t)blockIdx.x) * kGroups + g;
     const bool live = slot < T;
     const int64_t t = live ? (order ? (int64_t)order[slot] : slot) : 0;
     const int64_t leaf = leaf_idx[t];
@@ -163,7 +164,7 @@ static hipError_t run_gather(const Problem& p, const int32_t* leaf_idx, const in
     constexpr int kGroups = 256 / LPT;
     const int nvec = (int)(p.D / Elem<BF16>::kPerVec);
     const int out_vec = vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
-    const int64_t blocks = (p.T + kGroups - 1) / kGroups;
+    const int64_t blocks = ((p.T + kGroups - 1) / kGroups + kXcds - 1) / kXcds * kXcds;
     leaf_gather_kernel<BF16, LPT, NV><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(
         (const uint4*)p.x, (const uint4*)p.leaf_w1, p.leaf_b1, p.leaf_w2, p.leaf_b2, leaf_idx, order,
         p.L, p.act, p.T, nvec, p.O, out_vec, p.out);

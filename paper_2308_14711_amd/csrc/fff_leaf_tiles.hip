@@ -64,16 +64,6 @@ __device__ __forceinline__ uint32_t pack_half(uint32_t a, uint32_t b, int hi) {
     return hi ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
 }
 
-// Workgroups are dealt to the 8 XCDs round-robin (block b runs on XCD b mod 8) and every XCD has
-// its own L2.  Tiles are ordered by leaf, so consecutive tiles want the same weight rows: block b
-// takes logical index (b mod 8) * (grid / 8) + b / 8, which gives each XCD one contiguous range of
-// tiles and lets a leaf's weights be fetched into one L2 instead of all eight.  The grid is a
-// multiple of 8; logical indices past the work are idle blocks.
-constexpr int kXcds = 8;
-__device__ __forceinline__ int64_t xcd_contiguous_block() {
-    return (int64_t)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
-}
-
 // What both kernels derive for a tile: this lane's column (slot j of the tile; all four 16-lane
 // rows of the wave hold the same 16 columns), its token and leaf (-1 past the end), the index of
 // its run of equal leaves and the number of runs.
