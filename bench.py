@@ -28,12 +28,12 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # runs summarised in profiles/ (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0, the factors a plain device
 # copy of known size reads there).  Keyed by (workload, launch path, kernel); None where not measured.
 MEASURED_TRAFFIC = {
-    ("C4", "fused", "walk_fused"): 533.8e6,    # profiles/bert_base_fff_fused_C4.md
+    ("C4", "fused", "walk_fused"): 494.0e6,    # profiles/bert_base_fff_fused_C4.md
     ("C3", "staged", "descent"): 80.9e6,       # profiles/vit_block_fff_staged_C3.md
-    ("C3", "staged", "bucketing"): 2.5e6,
-    ("C3", "staged", "leaf_hidden"): 92.2e6,
-    ("C3", "staged", "leaf_output"): 111.8e6,
-    ("C5", "fused", "walk_fused"): 1645.2e6,   # profiles/large_skewed_fff_fused_C5.md
+    ("C3", "staged", "bucketing"): 3.8e6,
+    ("C3", "staged", "leaf_hidden"): 82.7e6,
+    ("C3", "staged", "leaf_output"): 85.9e6,
+    ("C5", "fused", "walk_fused"): 1645.3e6,   # profiles/large_skewed_fff_fused_C5.md
 }
 
 
