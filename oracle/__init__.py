@@ -52,6 +52,7 @@ def _load():
         _lib.fff_oracle_leaf_forward.argtypes = [vp] * 6 + [i32, i32, i32, i64, i64, i64, i32, vp]
         _lib.fff_oracle_forward_soft.argtypes = [vp] * 7 + [i32, i32, i32, i64, i64, i64, i32, f64, vp, vp]
         _lib.fff_oracle_bucket.argtypes = [vp, i64, i32, vp, vp, vp]
+        _lib.fff_oracle_moe_top1.argtypes = [vp] * 7 + [i64, i32, i32, i64, i64, i64, i32, vp, vp, vp]
         for n in ("training_size", "inference_size"):
             f = getattr(_lib, "fff_oracle_" + n)
             f.argtypes, f.restype = [i32, i32, i32], i64
@@ -144,6 +145,30 @@ def forward_soft(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, l
     if rc:
         raise ValueError("fff_oracle_forward_soft: bad arguments (%d)" % rc)
     return out, mix
+
+
+def moe_top1(x, gate_w, gate_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, leaf_width, act,
+             want_out: bool = True) -> Tuple[Optional[np.ndarray], np.ndarray, np.ndarray]:
+    """Mixture of experts, one engaged expert, noiseless gating.  gate_w [G, D], gate_b [G] or None;
+    experts stored like leaves ([G, l, D] ...).  Returns (out [T,O] fp64 or None, expert_idx [T],
+    margin [T]: relative gap between the two largest gating logits)."""
+    x, gate_w, leaf_w1, leaf_b1, leaf_w2, leaf_b2 = map(_c, (x, gate_w, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    gate_b = _c(gate_b)
+    T, D = x.shape
+    G = gate_w.shape[0]
+    assert gate_w.shape == (G, D) and leaf_w1.shape == (G, leaf_width, D) and leaf_w2.shape[:2] == (G, leaf_width)
+    O = leaf_w2.shape[2]
+    assert leaf_b1.shape == (G, leaf_width) and leaf_b2.shape == (G, O)
+    assert gate_b is None or gate_b.shape == (G,)
+    dt = _dtype_code((x, gate_w, gate_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    out = np.empty((T, O), np.float64) if want_out else None
+    idx = np.empty((T,), np.int32)
+    margin = np.empty((T,), np.float64)
+    rc = _load().fff_oracle_moe_top1(_p(x), _p(gate_w), _p(gate_b), _p(leaf_w1), _p(leaf_b1), _p(leaf_w2),
+                                     _p(leaf_b2), G, leaf_width, act, T, D, O, dt, _p(out), _p(idx), _p(margin))
+    if rc:
+        raise ValueError("fff_oracle_moe_top1: bad arguments (%d)" % rc)
+    return out, idx, margin
 
 
 def bucket(leaf_idx, depth) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:

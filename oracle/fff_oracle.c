@@ -16,6 +16,10 @@
  *                            c * F(right) + (1 - c) * F(left).
  *   fff_oracle_leaf_forward  the leaf <D, l, O> feedforward network of the
  *                            Definition, evaluated at a given leaf.
+ *   fff_oracle_moe_top1      mixture of experts with one engaged expert and
+ *                            noiseless gating (section "Inference speed
+ *                            comparison"): argmax of the gating logits, then
+ *                            that expert's feedforward output.
  *   fff_oracle_bucket        per-leaf token lists (count, exclusive offsets,
  *                            stable order).  Not in the paper; it is the plain
  *                            definition of what the bucketing stage produces.
@@ -45,8 +49,11 @@
  * vector, zero-node identity vs a library matmul, depth 0 vs a library
  * matmul, axis-aligned (k-d) routing by scalar compares, identical leaves,
  * the sizes printed in the paper's vision-transformer table, permutation
- * invariance, a hand-worked two-token example.  Numeric output values of a
- * forward pass are not printed anywhere in the paper.
+ * invariance, a hand-worked two-token example; for the mixture of experts:
+ * one-hot gating rows (argmax by scalar compares), a depth-1 FFF written as two
+ * experts, identical experts, a library argmax on tiny inputs, expert
+ * permutation, the tie and NaN rules.  Numeric output values of a forward
+ * pass are not printed anywhere in the paper.
  */
 #include <math.h>
 #include <stdint.h>
@@ -240,6 +247,59 @@ int64_t fff_oracle_training_size(int depth, int node_size, int leaf_size) {
 int64_t fff_oracle_inference_size(int depth, int node_size, int leaf_size) {
     return (int64_t)depth * node_size + leaf_size;
 }
+/*
+ * Mixture of experts with k = 1 and noiseless gating, the configuration of the
+ * paper's inference speed comparison (section "Inference speed comparison":
+ * experts of the leaf's shape, one expert engaged): gating logits g_e = G_e . x
+ * (+ bias, optional), the expert with the largest logit is evaluated (the
+ * lowest index among equal ones; a NaN logit is never larger), and with a
+ * single engaged expert its mixture weight is 1, so the output is that expert's
+ * feedforward output.  Experts are stored like leaves.
+ * expert_idx [T]; margin [T] (optional): (largest - second largest logit) over
+ * the larger of the two rows' sum of |terms| + |bias| (+inf for one expert) --
+ * a token whose margin is tiny may legitimately be gated differently by an
+ * fp32 implementation.
+ */
+int fff_oracle_moe_top1(const void *x, const void *gate_w, const void *gate_b, const void *leaf_w1,
+                        const void *leaf_b1, const void *leaf_w2, const void *leaf_b2,
+                        int64_t n_experts, int leaf_width, int act, int64_t T, int64_t D, int64_t O,
+                        int dtype, double *out, int32_t *expert_idx, double *margin) {
+    if (!args_ok(0, leaf_width, act, T, D, O, dtype) || n_experts < 1 || n_experts > ((int64_t)1 << 24)) return 1;
+    int err = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 16)
+#endif
+    for (int64_t t = 0; t < T; ++t) {
+        double *h = (double *)malloc(sizeof(double) * (size_t)leaf_width);
+        if (!h) { err = 2; continue; }
+        double best = -INFINITY, second = -INFINITY, best_scale = 0.0, second_scale = 0.0;
+        int64_t arg = 0;
+        for (int64_t e = 0; e < n_experts; ++e) {
+            double logit = gate_b ? ld(gate_b, e, dtype) : 0.0;
+            double scale = fabs(logit);
+            for (int64_t j = 0; j < D; ++j) {
+                const double term = ld(gate_w, e * D + j, dtype) * ld(x, t * D + j, dtype);
+                logit += term;
+                scale += fabs(term);
+            }
+            if (logit > best) {
+                second = best; second_scale = best_scale;
+                best = logit; best_scale = scale; arg = e;
+            } else if (logit > second) {
+                second = logit; second_scale = scale;
+            }
+        }
+        if (expert_idx) expert_idx[t] = (int32_t)arg;
+        if (margin) {
+            const double sc = best_scale > second_scale ? best_scale : second_scale;
+            margin[t] = (n_experts < 2 || !(second > -INFINITY)) ? INFINITY : (sc > 0.0 ? (best - second) / sc : 0.0);
+        }
+        if (out) leaf_eval(x, t * D, leaf_w1, leaf_b1, leaf_w2, leaf_b2, arg, leaf_width, act, D, O, dtype, h, out + t * O);
+        free(h);
+    }
+    return err;
+}
+
 int64_t fff_oracle_training_width(int depth, int leaf_size) { return ((int64_t)1 << depth) * leaf_size; }
 int64_t fff_oracle_inference_width(int depth, int leaf_size) { (void)depth; return leaf_size; }
 

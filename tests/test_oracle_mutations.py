@@ -8,6 +8,7 @@ import pytest
 
 import oracle
 import test_oracle_pins as pins
+import test_oracle_moe_pins as moe_pins
 
 SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "fff_oracle.c")
 
@@ -34,6 +35,12 @@ MUTATIONS = [
     ("training_size_nodes", "return (((int64_t)1 << depth) - 1) * node_size + ((int64_t)1 << depth) * leaf_size;",
      "return ((int64_t)1 << depth) * node_size + ((int64_t)1 << depth) * leaf_size;"),
     ("inference_size", "return (int64_t)depth * node_size + leaf_size;", "return (int64_t)(depth + 1) * node_size + leaf_size;"),
+    ("moe_tie_highest", "if (logit > best) {", "if (logit >= best) {"),
+    ("moe_bias_dropped", "double logit = gate_b ? ld(gate_b, e, dtype) : 0.0;", "double logit = 0.0;"),
+    ("moe_gate_row_stride", "ld(gate_w, e * D + j, dtype) * ld(x, t * D + j, dtype)", "ld(gate_w, e + j, dtype) * ld(x, t * D + j, dtype)"),
+    ("moe_expert_not_used", "leaf_b2, arg, leaf_width, act", "leaf_b2, 0, leaf_width, act"),
+    ("moe_margin_not_relative", "(sc > 0.0 ? (best - second) / sc : 0.0)", "(best - second)"),
+    ("moe_second_not_tracked", "} else if (logit > second) {\n                second = logit; second_scale = scale;\n            }", "}"),
     ("bf16_widen_shift", "uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 16;", "uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 15;"),
 ]
 
@@ -52,6 +59,14 @@ PINS = [
     pins.test_leaf_forward_matches_forward_hard_and_library,
     pins.test_bf16_and_f32_inputs_are_widened_exactly,
     lambda: pins.test_bucket_against_library_sort(8, 5000),
+    moe_pins.test_moe_hand_worked_example,
+    moe_pins.test_moe_one_hot_gates_pick_by_scalar_compares,
+    moe_pins.test_moe_with_two_experts_is_a_depth_one_fff,
+    moe_pins.test_moe_matches_library_argmax_and_dense_expert_on_tiny_inputs,
+    moe_pins.test_moe_identical_experts_make_gating_irrelevant,
+    moe_pins.test_moe_expert_permutation_permutes_the_indices_only,
+    moe_pins.test_moe_ties_take_the_lowest_index_and_nan_never_wins,
+    moe_pins.test_moe_bf16_bits_are_widened_exactly,
 ]
 
 
