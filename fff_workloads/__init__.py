@@ -31,7 +31,7 @@ DTYPE_BF16 = 1
 
 _TAGS = {
     "x": 1, "node_w": 2, "node_b": 3, "leaf_w1": 4, "leaf_b1": 5,
-    "leaf_w2": 6, "leaf_b2": 7, "perm": 8,
+    "leaf_w2": 6, "leaf_b2": 7, "perm": 8, "gate_w": 9, "gate_b": 10,
 }
 
 
@@ -257,6 +257,16 @@ def config(name: str, seed: int = 0, keep_f32: bool = True, T: Optional[int] = N
                           node_b="zipf", keep_f32=keep_f32,
                           note="large skewed FFF, Zipf(1.1) leaf occupancy")
     raise KeyError(name)
+
+
+def moe_gate(n_experts: int, D: int, dtype: int, seed: int = 0):
+    """Gating weights of a mixture of experts standing beside a layer of `n_experts` leaves:
+    gate_w [n_experts, D] and gate_b [n_experts], U(-1/sqrt(D), 1/sqrt(D)) like the node weights.
+    Returns the arrays whose bytes are uploaded (uint16 bf16 bits or fp32)."""
+    bD = 1.0 / np.sqrt(D)
+    bf = dtype == DTYPE_BF16
+    return (_uniform(seed, "gate_w", (n_experts, D), bD, as_bf16_bits=bf),
+            _uniform(seed, "gate_b", (n_experts,), bD, as_bf16_bits=bf))
 
 
 CONFIG_NAMES = ("C1", "C2", "C2c", "C3", "C4", "C5")

@@ -118,13 +118,37 @@ int fff_bucket(const int32_t* leaf_idx, int64_t T, int depth,
 
 /*
  * fff_leaf_forward: the leaf networks alone, token t evaluated at leaf
- * leaf_idx[t] (device array, values in [0, 2^depth)); buckets tokens
- * internally.  Writes out [T, O].
+ * leaf_idx[t] (device array, values in [0, 2^depth)); small batches run one
+ * block per token, larger ones are bucketed internally.  Writes out [T, O].
  */
 int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1,
                      const void* leaf_w2, const void* leaf_b2, const int32_t* leaf_idx,
                      int depth, int leaf_width, int act, void* out, void* stream,
                      int64_t T, int64_t D, int64_t O, int dtype);
+
+/*
+ * fff_moe_top1_forward: the mixture-of-experts counterpart the paper times the tree
+ * lookup against (section "Inference speed comparison": experts of the leaves'
+ * shape, k = 1 engaged expert, no gating noise).  Gating logits
+ * g[t][e] = gate_w[e] . x[t] (+ gate_b[e]); expert_idx[t] = the expert with the
+ * largest logit (the lowest index among equal ones; a NaN logit never wins; fp32
+ * accumulation on the matrix cores, so tokens whose two largest logits are
+ * within rounding of each other may be gated to either); out[t] = that expert's
+ * feedforward output, with mixture weight 1.  Only the lookup differs from
+ * fff_forward_hard: bucketing and the leaf kernels are the same.
+ *   gate_w [2^log2_experts, D], gate_b [2^log2_experts] or NULL, the experts in
+ *   the leaves' layout (leaf_w1 [2^log2_experts, leaf_width, D], ...);
+ *   expert_idx [T] int32 may be NULL; dtype must be FFF_BF16 with D % 8 == 0 and
+ *   16-byte aligned rows (else FFF_ERR_UNSUPPORTED); other arguments, ownership,
+ *   asynchrony and errors as for fff_forward_hard.  The gating needs
+ *   2 * T * ceil(2^log2_experts / 128) more words of workspace than
+ *   fff_workspace_bytes reports; the first call with larger sizes allocates them.
+ */
+int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b,
+                         const void* leaf_w1, const void* leaf_b1, const void* leaf_w2,
+                         const void* leaf_b2, int log2_experts, int leaf_width, int act,
+                         void* out, int32_t* expert_idx, void* stream,
+                         int64_t T, int64_t D, int64_t O, int dtype);
 
 /* Bytes of workspace a call with these sizes uses on the current device. */
 size_t fff_workspace_bytes(int64_t T, int depth);

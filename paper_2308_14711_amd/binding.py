@@ -40,6 +40,7 @@ def lib() -> ctypes.CDLL:
         L.fff_descend.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, i32]
         L.fff_bucket.argtypes = [vp, i64, i32, vp, vp, vp, vp]
         L.fff_leaf_forward.argtypes = [vp] * 6 + [i32, i32, i32, vp, vp, i64, i64, i64, i32]
+        L.fff_moe_top1_forward.argtypes = [vp] * 7 + [i32, i32, i32, vp, vp, vp, i64, i64, i64, i32]
         L.fff_workspace_bytes.argtypes = [i64, i32]
         L.fff_workspace_bytes.restype = ctypes.c_size_t
         L.fff_reserve_workspace.argtypes = [i64, i32]
@@ -126,6 +127,17 @@ def fff_leaf_forward(x, leaf_w1, leaf_b1, leaf_w2, leaf_b2, leaf_idx, depth, lea
     _check(lib().fff_leaf_forward(_ptr(x), _ptr(leaf_w1), _ptr(leaf_b1), _ptr(leaf_w2), _ptr(leaf_b2),
                                   _ptr(leaf_idx), depth, leaf_width, act, _ptr(out),
                                   _stream_handle(stream), T, D, O, _dtype_code(x)), "fff_leaf_forward")
+
+
+def fff_moe_top1_forward(x, gate_w, gate_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, log2_experts, leaf_width, act,
+                         out, expert_idx=None, stream=None) -> None:
+    _check_dense(x, gate_w, gate_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, expert_idx, out)
+    T, D = x.shape
+    O = out.shape[1]
+    _check(lib().fff_moe_top1_forward(_ptr(x), _ptr(gate_w), _ptr(gate_b), _ptr(leaf_w1), _ptr(leaf_b1),
+                                      _ptr(leaf_w2), _ptr(leaf_b2), log2_experts, leaf_width, act, _ptr(out),
+                                      _ptr(expert_idx), _stream_handle(stream), T, D, O, _dtype_code(x)),
+           "fff_moe_top1_forward")
 
 
 def fff_workspace_bytes(T: int, depth: int) -> int:

@@ -60,10 +60,11 @@ int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
     int64_t n_chunks;
-    int64_t o_ctrl, o_leaf, o_rank, o_sleaf, o_perm, o_count, o_offset, o_tileoff, o_matrix, o_hidden, total;
+    int64_t o_ctrl, o_leaf, o_rank, o_sleaf, o_perm, o_count, o_offset, o_tileoff, o_matrix, o_hidden, o_extra, total;
 };
 
-Layout layout_for(int64_t T, int depth) {
+// extra_words: room for a caller-specific scratch region (the gating candidates of the mixture of experts)
+Layout layout_for(int64_t T, int depth, int64_t extra_words = 0) {
     Layout l;
     const int64_t NL = (int64_t)1 << depth;
     const int64_t per_round = (T + kChunkTokens - 1) / kChunkTokens;
@@ -84,6 +85,7 @@ Layout layout_for(int64_t T, int depth) {
     l.o_tileoff = take(NL + 1);
     l.o_matrix = take(c * NL);
     l.o_hidden = take((int64_t)(kTilesMaxLeafWidth / 2) * T);   // T * L bf16 values, L up to the tile path's limit
+    l.o_extra = take(extra_words);
     l.total = o;
     return l;
 }
@@ -94,8 +96,8 @@ int set_device_error(hipError_t e, const char* what) {
 }
 
 // Grows the current device's workspace if needed and carves it for (T, depth).
-int get_workspace(int64_t T, int depth, Workspace* ws, Layout* lay) {
-    *lay = layout_for(T, depth);
+int get_workspace(int64_t T, int depth, Workspace* ws, Layout* lay, int64_t extra_words = 0) {
+    *lay = layout_for(T, depth, extra_words);
     const size_t need = (size_t)lay->total * sizeof(int32_t);
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -139,6 +141,7 @@ int get_workspace(int64_t T, int depth, Workspace* ws, Layout* lay) {
     ws->tile_off = b + lay->o_tileoff;
     ws->chunk_cnt = b + lay->o_matrix;
     ws->hidden = b + lay->o_hidden;
+    ws->extra = b + lay->o_extra;
     ws->n_chunks = lay->n_chunks;
     return FFF_OK;
 }
@@ -254,6 +257,19 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
     return FFF_OK;
 }
 
+// The leaf networks at given leaves: small batches go one block per token, larger ones are bucketed.
+int run_leaf_any(const Problem& p, const int32_t* leaf_idx, hipStream_t s) {
+    if (g_opt.path != kPathStaged && token_shape_ok(p) && p.T <= 6 * g_opt.token_max_T) {
+        hipError_t e = launch_token_block(p, nullptr, s, leaf_idx);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "token-block kernel launch");
+    }
+    Workspace ws;
+    Layout lay;
+    const int rc = get_workspace(p.T, p.depth, &ws, &lay);
+    if (rc != FFF_OK) return rc;
+    return run_leaf_stage(p, leaf_idx, ws, s);   // falls back per shape inside
+}
+
 }  // namespace
 }  // namespace fff
 
@@ -347,10 +363,43 @@ int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1, co
     Problem p{x, nullptr, nullptr, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, nullptr,
               T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
     g_last_error.clear();
+    return run_leaf_any(p, leaf_idx, (hipStream_t)stream);
+}
+
+int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b, const void* leaf_w1,
+                         const void* leaf_b1, const void* leaf_w2, const void* leaf_b2, int log2_experts,
+                         int leaf_width, int act, void* out, int32_t* expert_idx, void* stream, int64_t T,
+                         int64_t D, int64_t O, int dtype) {
+    int rc = check_common(log2_experts, T, D, dtype);
+    if (rc == FFF_OK) rc = check_leaf(log2_experts, leaf_width, act, T, D, O);
+    if (rc != FFF_OK) return rc;
+    if (T == 0) return FFF_OK;
+    if (!x || !gate_w || !leaf_w1 || !leaf_b1 || !leaf_w2 || !leaf_b2 || !out) return FFF_ERR_NULL;
+    const int64_t es = dtype == FFF_BF16 ? 2 : 4;
+    if (overlaps(x, T * D * es, out, T * O * es)) return FFF_ERR_ALIAS;
+    if (!moe_gate_shape_ok(x, gate_w, D, dtype == FFF_BF16)) return FFF_ERR_UNSUPPORTED;
+    const int64_t G = (int64_t)1 << log2_experts;
+    Problem p{x, nullptr, nullptr, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, nullptr,
+              T, D, O, log2_experts, leaf_width, act, dtype == FFF_BF16};
+    g_last_error.clear();
+    hipStream_t s = (hipStream_t)stream;
     Workspace ws;
     Layout lay;
-    if ((rc = get_workspace(T, depth, &ws, &lay)) != FFF_OK) return rc;
-    return run_leaf_stage(p, leaf_idx, ws, (hipStream_t)stream);   // falls back per shape inside
+    if ((rc = get_workspace(T, log2_experts, &ws, &lay, 2 * T * moe_gate_blocks(G))) != FFF_OK) return rc;
+    int32_t* ei = expert_idx ? expert_idx : ws.leaf_idx;
+    stage_mark(s);
+    hipError_t e = launch_moe_gate(x, gate_w, gate_b, T, D, G, ws.extra, ei, s);
+    if (e != hipSuccess) return set_device_error(e, "gating kernel launch");
+    stage_mark(s);
+    // the experts are leaves: small batches one block per token, larger ones bucketed
+    if (g_opt.path != kPathStaged && token_shape_ok(p) && T <= 6 * g_opt.token_max_T) {
+        g_opt.last_path = kPathToken;
+        e = launch_token_block(p, nullptr, s, ei);
+        for (int k = 0; k < 3; ++k) stage_mark(s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "token-block kernel launch");
+    }
+    g_opt.last_path = kPathStaged;
+    return run_leaf_stage(p, ei, ws, s, true);
 }
 
 size_t fff_workspace_bytes(int64_t T, int depth) {

@@ -32,6 +32,7 @@ struct Workspace {
     int32_t* tile_off;   // [NL + 1] exclusive prefix of per-leaf tile counts
     int32_t* chunk_cnt;  // [C, NL]  per-chunk histograms, then per-chunk bases
     int32_t* hidden;     // [16 T]   hidden activations of the tile path, T * L bf16 (L <= 32)
+    int32_t* extra;      // caller-specific region (gating candidates of the mixture of experts)
     int32_t* ctrl;       // [16]     ticket counters and totals
     int64_t n_chunks;
 };
@@ -88,8 +89,18 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const i
 // latency of the dependent loads rather than for throughput; needs token_shape_ok(p).
 constexpr size_t kTokenMaxLds = 144 * 1024;
 constexpr int64_t kTokenMaxBlocks = 8192;
+// given_leaf (optional): the leaf of every token; then only the leaf networks run (the node
+// weights are not read, token_shape_ok's condition on them does not apply).
 bool token_shape_ok(const Problem& p);
-hipError_t launch_token_block(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+hipError_t launch_token_block(const Problem& p, int32_t* leaf_idx, hipStream_t s,
+                              const int32_t* given_leaf = nullptr);
+
+// Gating of a mixture of experts with one engaged expert (fff_moe_gate.hip): expert_idx[t] =
+// argmax_e gate_w[e] . x[t] (+ gate_b[e]).  cand: scratch of 2 * T * moe_gate_blocks(n_experts) words.
+int64_t moe_gate_blocks(int64_t n_experts);
+bool moe_gate_shape_ok(const void* x, const void* gate_w, int64_t D, bool bf16);
+hipError_t launch_moe_gate(const void* x, const void* gate_w, const void* gate_b, int64_t T, int64_t D,
+                           int64_t n_experts, int32_t* cand, int32_t* expert_idx, hipStream_t s);
 
 // Whole forward pass in one launch, one token per lane group (any shape).
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);

@@ -31,6 +31,7 @@ struct TokenArgs {
     const void* b2;
     void* out;
     int32_t* leaf_idx;
+    const int32_t* given_leaf;   // non-null: the leaf of every token is given, nothing is descended
     int64_t T, O;
     int depth, nvec, ovec, L, act;
 };
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(kTokenBlock) void token_block_kernel(TokenArgs a) {
 
         // ---- descent by wave 0: S levels per round trip (Algorithm 1: logit >= 0 takes the right child)
         int64_t n = 0;   // position within the current level
-        for (int m = 0; wv == 0 && m < a.depth; m += S) {
+        for (int m = 0; wv == 0 && !a.given_leaf && m < a.depth; m += S) {
             const int s = a.depth - m < S ? a.depth - m : S;
             const int64_t root = (((int64_t)1 << m) - 1 + n) + 1;   // heap row of the subtree's root, plus one
             uint4 rows[kSub][NV];
@@ -141,6 +142,7 @@ __global__ __launch_bounds__(kTokenBlock) void token_block_kernel(TokenArgs a) {
             n = (n << s) + j;
         }
         if (threadIdx.x == 0) {
+            if (a.given_leaf) n = a.given_leaf[t];
             lds_leaf[0] = (int)n;
             if (a.leaf_idx) a.leaf_idx[t] = (int32_t)n;
         }
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(kTokenBlock) void token_block_kernel(TokenArgs a) {
 }
 
 template <bool BF16, int NV, int S, bool OUTVEC>
-hipError_t run_token(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+hipError_t run_token(const Problem& p, int32_t* leaf_idx, const int32_t* given_leaf, hipStream_t s) {
     constexpr int kPer = Elem<BF16>::kPerVec;
     TokenArgs a;
     a.x = (const uint4*)p.x;
@@ -255,6 +257,7 @@ hipError_t run_token(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     a.b2 = p.leaf_b2;
     a.out = p.out;
     a.leaf_idx = leaf_idx;
+    a.given_leaf = given_leaf;
     a.T = p.T;
     a.O = p.O;
     a.depth = p.depth;
@@ -281,15 +284,15 @@ hipError_t run_token(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
 }
 
 template <bool BF16, bool OUTVEC>
-hipError_t dispatch_token(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+hipError_t dispatch_token(const Problem& p, int32_t* leaf_idx, const int32_t* given_leaf, hipStream_t s) {
     constexpr int kPer = Elem<BF16>::kPerVec;
     int64_t vecs = p.D / kPer;
     if (OUTVEC && p.O / kPer > vecs) vecs = p.O / kPer;
     // (vectors per lane, levels per round trip): 2^S - 1 rows of NV vectors stay under 32 registers x 4
-    if (vecs <= 64) return run_token<BF16, 1, 3, OUTVEC>(p, leaf_idx, s);
-    if (vecs <= 128) return run_token<BF16, 2, 3, OUTVEC>(p, leaf_idx, s);
-    if (vecs <= 256) return run_token<BF16, 4, 3, OUTVEC>(p, leaf_idx, s);
-    return run_token<BF16, 8, 2, OUTVEC>(p, leaf_idx, s);
+    if (vecs <= 64) return run_token<BF16, 1, 3, OUTVEC>(p, leaf_idx, given_leaf, s);
+    if (vecs <= 128) return run_token<BF16, 2, 3, OUTVEC>(p, leaf_idx, given_leaf, s);
+    if (vecs <= 256) return run_token<BF16, 4, 3, OUTVEC>(p, leaf_idx, given_leaf, s);
+    return run_token<BF16, 8, 2, OUTVEC>(p, leaf_idx, given_leaf, s);
 }
 
 bool token_out_vec(const Problem& p) {
@@ -308,10 +311,13 @@ bool token_shape_ok(const Problem& p) {
     return token_out_vec(p) || 16 + (size_t)p.L * sizeof(float) <= kTokenMaxLds;
 }
 
-hipError_t launch_token_block(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+hipError_t launch_token_block(const Problem& p, int32_t* leaf_idx, hipStream_t s, const int32_t* given_leaf) {
     const bool ov = token_out_vec(p);
-    if (p.bf16) return ov ? dispatch_token<true, true>(p, leaf_idx, s) : dispatch_token<true, false>(p, leaf_idx, s);
-    return ov ? dispatch_token<false, true>(p, leaf_idx, s) : dispatch_token<false, false>(p, leaf_idx, s);
+    if (p.bf16)
+        return ov ? dispatch_token<true, true>(p, leaf_idx, given_leaf, s)
+                  : dispatch_token<true, false>(p, leaf_idx, given_leaf, s);
+    return ov ? dispatch_token<false, true>(p, leaf_idx, given_leaf, s)
+              : dispatch_token<false, false>(p, leaf_idx, given_leaf, s);
 }
 
 }  // namespace fff

@@ -78,6 +78,17 @@ def test_bad_arguments_are_rejected_on_the_host(L):
     assert L.fff_bucket(None, 5, 3, None, None, None, None) == NULL
     assert L.fff_bucket(None, 5, 30, None, None, None, None) == RANGE
     assert L.fff_leaf_forward(None, None, None, None, None, None, 2, 1, 0, None, None, 3, 8, 8, 1) == NULL
+    moe = lambda **kw: L.fff_moe_top1_forward(
+        kw.get("x", ctypes.c_void_p(256)), kw.get("gate_w", ctypes.c_void_p(1 << 20)), None, ctypes.c_void_p(2 << 20),
+        ctypes.c_void_p(3 << 20), ctypes.c_void_p(4 << 20), ctypes.c_void_p(5 << 20), kw.get("g", 3), 2, kw.get("act", 0),
+        ctypes.c_void_p(6 << 20), None, None, kw.get("T", 4), kw.get("D", 16), 8, kw.get("dtype", 1))
+    assert moe(T=0) == OK
+    assert moe(gate_w=None) == NULL
+    assert moe(g=25) == RANGE
+    assert moe(act=9) == UNSUP
+    assert moe(dtype=0) == UNSUP                      # the gating runs on the bf16 matrix cores only
+    assert moe(D=12) == UNSUP                         # rows must be whole 16-byte vectors
+    assert L.fff_set_option(b"last_path", 1) == UNSUP  # read-only
 
 
 def test_options(L):
