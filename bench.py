@@ -65,13 +65,17 @@ def algorithmic_bytes(w, ref_idx):
     }
 
 
-def depth_sweep(args, np, torch, W, F):
+def depth_sweep(args, np, torch, W, F, with_moe=False):
     """Time per call against tree depth for a small batch: inputs and outputs 768 wide, leaves of
     `--sweep-leaf-width` neurons, depth `--sweep-min-depth`..`--sweep-max-depth`, `--sweep-batch` tokens (the shape
     of the paper's inference-speed experiment, with synthetic inputs).  Three clocks per depth:
     calls issued back to back from Python (launch cost of the host loop included), the same calls
     replayed from a HIP graph holding 20 of them (per-call device time with launches amortised),
-    and the CPU oracle.  The routing of every depth is checked against the oracle."""
+    and the CPU oracle.  The routing of every depth is checked against the oracle.
+
+    with_moe: the paper's comparison of lookups -- a mixture of experts with one engaged expert and
+    2^depth experts (the same leaf weights, a gating matrix of 2^depth rows instead of the tree) is
+    timed and checked the same way; only the lookup differs between the two calls."""
     import oracle
     T, L, D, O = args.sweep_batch, args.sweep_leaf_width, 768, 768
     rows = []
@@ -124,13 +128,51 @@ def depth_sweep(args, np, torch, W, F):
                      "us_cpu_oracle": round(cpu_us, 1), "launch_path": int(F.fff_get_option("last_path")),
                      "idx_mismatch_outside_margin": int((margin[mism] >= 1e-4).sum()),
                      "max_rel_row_err": float((np.abs(got[keep] - ref_out[keep]).max(axis=1) / scale).max())})
+        if with_moe:
+            gw, gb = W.moe_gate(1 << d, D, W.DTYPE_BF16, seed=d)
+            d_gw = torch.from_numpy(gw.view(np.int16)).cuda().view(torch.bfloat16)
+            d_gb = torch.from_numpy(gb.view(np.int16)).cuda().view(torch.bfloat16)
+
+            def moe_call():
+                F.fff_moe_top1_forward(dev["x"], d_gw, d_gb, dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"],
+                                       dev["leaf_b2"], d, L, w.act, out, idx)
+
+            for _ in range(args.warmup):
+                moe_call()
+            torch.cuda.synchronize()
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                for _ in range(per_graph):
+                    moe_call()
+            for _ in range(3):
+                g2.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                g2.replay()
+            torch.cuda.synchronize()
+            moe_us = (time.perf_counter() - t0) * 1e6 / (reps * per_graph)
+            t0 = time.perf_counter()
+            m_out, m_idx, m_margin = oracle.moe_top1(ins[0], gw, gb, *ins[3:], L, w.act)
+            moe_cpu_us = (time.perf_counter() - t0) * 1e6
+            g_idx = idx.cpu().numpy()
+            mm = np.nonzero(g_idx != m_idx)[0]
+            kp = g_idx == m_idx
+            g_out = out.float().cpu().numpy().astype(np.float64)
+            sc = np.maximum(np.abs(m_out[kp]).max(axis=1), 1e-30)
+            rows[-1].update({"moe_us_per_call_graph": round(moe_us, 2), "moe_us_cpu_oracle": round(moe_cpu_us, 1),
+                             "moe_experts": 1 << d, "moe_idx_mismatch_outside_margin": int((m_margin[mm] >= 1e-4).sum()),
+                             "moe_max_rel_row_err": float((np.abs(g_out[kp] - m_out[kp]).max(axis=1) / sc).max()),
+                             "moe_gating_bytes": int((1 << d) * (D + 1) * 2)})
+            del d_gw, d_gb
         del dev, w, ins
     ds = np.array([r["depth"] for r in rows], dtype=np.float64)
     ys = np.array([r["us_per_call_graph"] for r in rows])
     slope, icpt = (np.polyfit(ds, ys, 1) if len(rows) > 1 else (0.0, ys[0]))
     resid = ys - (slope * ds + icpt)
     print(json.dumps({
-        "metric": "fff_hard_inference_latency_vs_depth", "unit": "us per call", "n_gpus": 1,
+        "metric": "fff_vs_moe_lookup_latency_vs_depth" if with_moe else "fff_hard_inference_latency_vs_depth",
+        "unit": "us per call", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "depth sweep: batch %d, D = O = 768, leaf width %d, GELU" % (T, L),
                    "options": args.opt, "cpu_oracle_cores": oracle.num_threads()},
@@ -150,8 +192,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
-    ap.add_argument("--sweep", choices=["depth"], default=None,
-                    help="depth: the small-batch latency sweep (time per call against tree depth) instead of a workload")
+    ap.add_argument("--sweep", choices=["depth", "experts"], default=None,
+                    help="depth: the small-batch latency sweep (time per call against tree depth) instead of a "
+                         "workload; experts: the same sweep with the mixture-of-experts lookup (one engaged "
+                         "expert) timed beside the tree lookup on the same leaves")
     ap.add_argument("--sweep-batch", type=int, default=256)
     ap.add_argument("--sweep-leaf-width", type=int, default=32)
     ap.add_argument("--sweep-min-depth", type=int, default=1)
@@ -176,8 +220,8 @@ def main():
         k, v = kv.split("=")
         F.fff_set_option(k, int(v))
 
-    if args.sweep == "depth":
-        depth_sweep(args, np, torch, W, F)
+    if args.sweep in ("depth", "experts"):
+        depth_sweep(args, np, torch, W, F, with_moe=args.sweep == "experts")
         return
 
     w = W.config(args.config, keep_f32=False)

@@ -33,6 +33,12 @@ struct GateArgs {
     int D, n_eblocks;
 };
 
+// v or zeros, component by component (a conditional on the 16-byte struct itself is lowered
+// through memory)
+__device__ __forceinline__ uint4 keep_if(bool ok, const uint4& v) {
+    return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
+}
+
 __device__ __forceinline__ int swz(int row, int piece) { return 8 * row + ((piece + (row >> 1)) & 7); }
 
 // (v, i) <- the better of (v, i) and (v2, i2): larger value, then lower index
@@ -40,6 +46,10 @@ __device__ __forceinline__ void better(float& v, int32_t& i, float v2, int32_t i
     const bool take = v2 > v || (v2 == v && i2 < i);
     v = take ? v2 : v;
     i = take ? i2 : i;
+}
+
+template <int N> __device__ __forceinline__ int32_t row_rotate_i(int32_t i) {
+    return __builtin_amdgcn_update_dpp(0, i, 0x120 + N, 0xf, 0xf, false);
 }
 
 template <int N> __device__ __forceinline__ void row_step(float& v, int32_t& i) {
@@ -60,38 +70,49 @@ __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
     const int64_t e0 = (int64_t)eb * kGateExperts;
     const int D = a.D;
     const int n_chunks = (D + kGateK - 1) / kGateK;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
 
-    // loader roles: 2 pieces of the token tile, 4 of the expert tile (8 consecutive threads = one row's 128 bytes)
-    uint4 ra[2], rb[4];
-    auto fetch = [&](int kc) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int p = tid + 256 * u, row = p >> 3, c = p & 7;
-            const int64_t t = t0 + row;
-            const int k = kc * kGateK + 8 * c;
-            ra[u] = (t < a.T && k < D) ? *(const uint4*)(a.x + t * D + k) : zero;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int p = tid + 256 * u, row = p >> 3, c = p & 7;
-            const int64_t e = e0 + row;
-            const int k = kc * kGateK + 8 * c;
-            rb[u] = (e < a.G && k < D) ? *(const uint4*)(a.gate_w + e * D + k) : zero;
-        }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int p = tid + 256 * u;
-            lds_a[buf][swz(p >> 3, p & 7)] = ra[u];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int p = tid + 256 * u;
-            lds_b[buf][swz(p >> 3, p & 7)] = rb[u];
-        }
-    };
+    // loader roles: 2 pieces of the token tile, 4 of the expert tile (8 consecutive threads = one
+    // row's 128 bytes).  kDepth chunks are kept in flight in registers: with one chunk ahead the
+    // loop is a chain of memory round trips (12 of them for D = 768), since a chunk's arithmetic
+    // is only 16 MFMAs per wave.
+    // Loads are unconditional with clamped addresses; rows past the end and K past D are zeroed
+    // when the chunk goes to LDS.  (A predicated 16-byte load compiles to guarded dword loads with
+    // a wait each, and a select right after the load makes the wave wait for it there.)
+    constexpr int kDepth = 4;
+    const int pc = tid & 7;                      // this thread's piece of every row it loads
+    const int64_t ta0 = t0 + (tid >> 3), ta1 = ta0 + 32;
+    const int64_t eb0 = e0 + (tid >> 3), eb1 = eb0 + 32, eb2 = eb0 + 64, eb3 = eb0 + 96;
+    const uint16_t* const pa0 = a.x + (ta0 < a.T ? ta0 : a.T - 1) * D + 8 * pc;
+    const uint16_t* const pa1 = a.x + (ta1 < a.T ? ta1 : a.T - 1) * D + 8 * pc;
+    const uint16_t* const pb0 = a.gate_w + (eb0 < a.G ? eb0 : a.G - 1) * D + 8 * pc;
+    const uint16_t* const pb1 = a.gate_w + (eb1 < a.G ? eb1 : a.G - 1) * D + 8 * pc;
+    const uint16_t* const pb2 = a.gate_w + (eb2 < a.G ? eb2 : a.G - 1) * D + 8 * pc;
+    const uint16_t* const pb3 = a.gate_w + (eb3 < a.G ? eb3 : a.G - 1) * D + 8 * pc;
+    const bool va0 = ta0 < a.T, va1 = ta1 < a.T;
+    const bool vb0 = eb0 < a.G, vb1 = eb1 < a.G, vb2 = eb2 < a.G, vb3 = eb3 < a.G;
+    const int sa0 = swz(tid >> 3, pc), sa1 = swz((tid >> 3) + 32, pc);
+    const int sb0 = sa0, sb1 = sa1, sb2 = swz((tid >> 3) + 64, pc), sb3 = swz((tid >> 3) + 96, pc);
+    struct Chunk { uint4 a0, a1, b0, b1, b2, b3; };   // named members: they stay in registers
+#define FFF_GATE_FETCH(KC, Q)                                                   \
+    do {                                                                        \
+        const int koff_ = (KC) * kGateK + 8 * pc < D ? (KC) * kGateK : 0;       \
+        Q.a0 = *(const uint4*)(pa0 + koff_);                                    \
+        Q.a1 = *(const uint4*)(pa1 + koff_);                                    \
+        Q.b0 = *(const uint4*)(pb0 + koff_);                                    \
+        Q.b1 = *(const uint4*)(pb1 + koff_);                                    \
+        Q.b2 = *(const uint4*)(pb2 + koff_);                                    \
+        Q.b3 = *(const uint4*)(pb3 + koff_);                                    \
+    } while (0)
+#define FFF_GATE_STASH(KC, BUF, Q)                                              \
+    do {                                                                        \
+        const bool kin_ = (KC) * kGateK + 8 * pc < D;                           \
+        lds_a[BUF][sa0] = keep_if(kin_ && va0, Q.a0);                               \
+        lds_a[BUF][sa1] = keep_if(kin_ && va1, Q.a1);                               \
+        lds_b[BUF][sb0] = keep_if(kin_ && vb0, Q.b0);                               \
+        lds_b[BUF][sb1] = keep_if(kin_ && vb1, Q.b1);                               \
+        lds_b[BUF][sb2] = keep_if(kin_ && vb2, Q.b2);                               \
+        lds_b[BUF][sb3] = keep_if(kin_ && vb3, Q.b3);                               \
+    } while (0)
 
     f32x4_t acc[4][2];
 #pragma unroll
@@ -99,34 +120,7 @@ __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int kc = 0; kc < n_chunks; ++kc) {
-        const int buf = kc & 1;
-        if (kc + 1 < n_chunks) fetch(kc + 1);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            // K is only a summation order: step u gives lane group kg the piece 2 kg + u of every row
-            bf16x8_t fa[4], fb[2];
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-                fa[mt] = __builtin_bit_cast(bf16x8_t, lds_a[buf][swz(16 * mt + j, 2 * kg + u)]);
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-                fb[nt] = __builtin_bit_cast(bf16x8_t, lds_b[buf][swz(32 * wv + 16 * nt + j, 2 * kg + u)]);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
-        }
-        if (kc + 1 < n_chunks) stash(buf ^ 1);
-        __syncthreads();
-    }
-
-    // lane (j, kg) of tile (mt, nt) holds tokens 16 mt + 4 kg + q (q = 0..3) against expert
-    // e0 + 32 wv + 16 nt + j: bias, then the best expert per token over the wave's 32
+    // the biases of this lane's two experts are requested now, long before they are needed
     const float ninf = -__builtin_inff();
     float bias[2];
     int32_t eidx[2];
@@ -137,23 +131,71 @@ __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
         eidx[nt] = ok ? (int32_t)e : 0x7fffffff;
         bias[nt] = !ok ? ninf : (a.gate_b ? bf16_to_f32(a.gate_b[e]) : 0.0f);
     }
+
+    // The loop body has no branches (the wait counters are only tracked along straight code):
+    // chunks past the end are fetched from a clamped address and stored as zeros, and the trip
+    // count is rounded up to a multiple of kDepth; the extra MFMAs add zeros.
+    Chunk c0, c1, c2, c3;
+    FFF_GATE_FETCH(0, c0);
+    FFF_GATE_FETCH(1, c1);
+    FFF_GATE_FETCH(2, c2);
+    FFF_GATE_FETCH(3, c3);
+    FFF_GATE_STASH(0, 0, c0);
+    __syncthreads();
+    // one chunk: refill the register slot the chunk came from, multiply out of LDS buffer BUF,
+    // put the next chunk into the other buffer.  Step u of a chunk gives lane group kg the piece
+    // 2 kg + u of every row (K is only a summation order).
+#define FFF_GATE_STEP(KC, BUF, CUR, NEXT)                                                                          \
+    do {                                                                                                           \
+        FFF_GATE_FETCH((KC) + kDepth, CUR);                                                                        \
+        _Pragma("unroll") for (int u = 0; u < 2; ++u) {                                                            \
+            bf16x8_t fa[4], fb[2];                                                                                 \
+            _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
+                fa[mt] = __builtin_bit_cast(bf16x8_t, lds_a[BUF][swz(16 * mt + j, 2 * kg + u)]);                   \
+            _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)                                                       \
+                fb[nt] = __builtin_bit_cast(bf16x8_t, lds_b[BUF][swz(32 * wv + 16 * nt + j, 2 * kg + u)]);         \
+            _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
+                _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)                                                   \
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);   \
+        }                                                                                                          \
+        FFF_GATE_STASH((KC) + 1, (BUF) ^ 1, NEXT);                                                                 \
+        __syncthreads();                                                                                           \
+    } while (0)
+    for (int kc0 = 0; kc0 < n_chunks; kc0 += kDepth) {
+        FFF_GATE_STEP(kc0 + 0, 0, c0, c1);
+        FFF_GATE_STEP(kc0 + 1, 1, c1, c2);
+        FFF_GATE_STEP(kc0 + 2, 0, c2, c3);
+        FFF_GATE_STEP(kc0 + 3, 1, c3, c0);
+    }
+#undef FFF_GATE_STEP
+#undef FFF_GATE_STASH
+#undef FFF_GATE_FETCH
+
+    // lane (j, kg) of tile (mt, nt) holds tokens 16 mt + 4 kg + q (q = 0..3) against expert
+    // e0 + 32 wv + 16 nt + j: bias, then the best expert per token over the wave's 32
+    // (the row maximum first, then the lowest index among the lanes that hold it: two chains of
+    // single DPP instructions per token instead of a compare-and-select exchange of pairs)
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            float v = acc[mt][0][q] + bias[0];
-            v = v != v ? ninf : v;                       // a NaN logit never wins
-            int32_t i = eidx[0];
+            float v0 = acc[mt][0][q] + bias[0];
             float v1 = acc[mt][1][q] + bias[1];
+            v0 = v0 != v0 ? ninf : v0;                     // a NaN logit never wins
             v1 = v1 != v1 ? ninf : v1;
-            better(v, i, v1, eidx[1]);
-            row_step<8>(v, i);
-            row_step<4>(v, i);
-            row_step<2>(v, i);
-            row_step<1>(v, i);
+            float m = fmaxf(v0, v1);
+            m = fmaxf(m, row_rotate<8>(m));
+            m = fmaxf(m, row_rotate<4>(m));
+            m = fmaxf(m, row_rotate<2>(m));
+            m = fmaxf(m, row_rotate<1>(m));
+            int32_t c = v0 == m ? eidx[0] : (v1 == m ? eidx[1] : 0x7fffffff);
+            c = min(c, row_rotate_i<8>(c));
+            c = min(c, row_rotate_i<4>(c));
+            c = min(c, row_rotate_i<2>(c));
+            c = min(c, row_rotate_i<1>(c));
             if (j == 0) {
-                part_v[wv][16 * mt + 4 * kg + q] = v;
-                part_i[wv][16 * mt + 4 * kg + q] = i;
+                part_v[wv][16 * mt + 4 * kg + q] = m;
+                part_i[wv][16 * mt + 4 * kg + q] = c;
             }
         }
     }
@@ -168,16 +210,23 @@ __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
     }
 }
 
-// one thread per token: the best candidate over the expert blocks
+// one wave per token: the best candidate over the expert blocks (lanes stride over the blocks)
 __global__ __launch_bounds__(256) void moe_pick_kernel(const float* __restrict__ cand_val,
                                                        const int32_t* __restrict__ cand_idx, int64_t T,
                                                        int n_eblocks, int32_t* __restrict__ expert_idx) {
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
-    float v = cand_val[t * n_eblocks];
-    int32_t i = cand_idx[t * n_eblocks];
-    for (int b = 1; b < n_eblocks; ++b) better(v, i, cand_val[t * n_eblocks + b], cand_idx[t * n_eblocks + b]);
-    expert_idx[t] = i;
+    float v = -__builtin_inff();
+    int32_t i = 0x7fffffff;
+    for (int b = lane; b < n_eblocks; b += kWave) better(v, i, cand_val[t * n_eblocks + b], cand_idx[t * n_eblocks + b]);
+    row_step<8>(v, i);
+    row_step<4>(v, i);
+    row_step<2>(v, i);
+    row_step<1>(v, i);
+#pragma unroll
+    for (int d = 16; d < kWave; d <<= 1) better(v, i, __shfl_xor(v, d, kWave), __shfl_xor(i, d, kWave));
+    if (lane == 0) expert_idx[t] = i;
 }
 
 }  // namespace
@@ -207,7 +256,7 @@ hipError_t launch_moe_gate(const void* x, const void* gate_w, const void* gate_b
     moe_gate_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    moe_pick_kernel<<<dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s>>>(a.cand_val, a.cand_idx, T, a.n_eblocks,
+    moe_pick_kernel<<<dim3((unsigned)((T + 3) / 4)), dim3(256), 0, s>>>(a.cand_val, a.cand_idx, T, a.n_eblocks,
                                                                            expert_idx);
     return hipGetLastError();
 }
