@@ -301,3 +301,46 @@ def test_capture_in_a_hip_graph_and_replay(path):
             assert torch.equal(idx, eager_idx)
     finally:
         F.fff_set_option("path", 0)
+
+
+def _random_cases(n, seed):
+    """Seeded random layer shapes: every row length class of the vector kernels (multiples of 8
+    and of 4, odd ones for the fallbacks), leaf widths across the gather / tile / wide-tile
+    limits, depths 0..9, ragged batch sizes around the tile and chunk boundaries."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        dtype = W.DTYPE_BF16 if rng.random() < 0.7 else W.DTYPE_F32
+        per = 8 if dtype == W.DTYPE_BF16 else 4
+        D = int(rng.choice([per * int(rng.integers(1, 40)), per * int(rng.integers(40, 140)), int(rng.integers(3, 300))],
+                           p=[0.5, 0.35, 0.15]))
+        O = int(rng.choice([per * int(rng.integers(1, 40)), 128 * int(rng.integers(1, 5)), int(rng.integers(1, 200))],
+                           p=[0.5, 0.3, 0.2]))
+        L = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 24, 31, 32, 33, 40]))
+        depth = int(rng.integers(0, 10))
+        T = int(rng.choice([1, 15, 16, 17, 63, 64, 65, 255, 257, 511, 513, 1000, 2049, 4097]))
+        act = W.ACT_GELU if rng.random() < 0.5 else W.ACT_RELU
+        cases.append(("rand%02d" % i, T, D, O, depth, L, act, dtype))
+    return cases
+
+
+RANDOM_CASES = _random_cases(36, seed=2024)
+
+
+@pytest.mark.parametrize("path", [0, 2], ids=["auto", "staged"])
+@pytest.mark.parametrize("case", RANDOM_CASES, ids=["%s_T%d_D%d_O%d_d%d_L%d_%s" % (c[0], c[1], c[2], c[3], c[4], c[5],
+                                                                                    "bf16" if c[7] else "f32")
+                                                    for c in RANDOM_CASES])
+def test_random_shapes(case, path):
+    import paper_2308_14711_amd as F
+    name, T, D, O, depth, L, act, dtype = case
+    print("\n[case] %s T=%d D=%d O=%d depth=%d L=%d act=%d dtype=%d seed 77 path=%d" % (name, T, D, O, depth, L, act, dtype, path),
+          flush=True)
+    w = W.make_layer(name, T, D, O, depth, L, act, dtype, seed=77)
+    F.fff_set_option("path", path)
+    try:
+        out, idx = run_forward(w)
+        took = F.fff_get_option("last_path")
+    finally:
+        F.fff_set_option("path", 0)
+    _log("%s path=%d took=%d" % (name, path, took), check_against_oracle(w, out, idx))
