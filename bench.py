@@ -275,6 +275,33 @@ def main():
             oracle.forward_hard(*ins, w.depth, w.leaf_width, w.act)
             cpu_passes += 1
         cpu_s = time.perf_counter() - t2
+    cpu_single = None
+    if not args.no_cpu_baseline:       # and on one core, on a prefix of the batch (about a second)
+        n1 = min(w.T, 8192)
+        ins1 = [np.ascontiguousarray(ins[0][:n1])] + ins[1:]
+        all_threads = oracle.num_threads()
+        oracle.set_threads(1)
+        try:
+            t3 = time.perf_counter()
+            oracle.forward_hard(*ins1, w.depth, w.leaf_width, w.act)
+            cpu_single = {"value": round(n1 / (time.perf_counter() - t3), 1), "unit": "tokens/s", "cores": 1,
+                          "sample": "first %d tokens of %s, one pass" % (n1, w.name)}
+        finally:
+            oracle.set_threads(all_threads)
+
+    # spread of the timing: ten batches of steps / 10 calls, each bracketed by a synchronisation
+    per_batch = max(1, args.steps // 10)
+    batch_ms = []
+    for b in range(10):
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        for i in range(per_batch):
+            step(b * per_batch + i)
+        torch.cuda.synchronize()
+        batch_ms.append((time.perf_counter() - tb) * 1e3 / per_batch)
+    timing_stats = {"batches": 10, "calls_per_batch": per_batch, "mean_ms": round(float(np.mean(batch_ms)), 5),
+                    "std_ms": round(float(np.std(batch_ms)), 5), "median_ms": round(float(np.median(batch_ms)), 5)}
+
     alg = algorithmic_bytes(w, ref_idx)
     path_names = {1: "fused", 2: "staged", 3: "generic", 4: "token_block"}
 
@@ -366,7 +393,9 @@ def main():
         "path": {"alg_bytes": alg["path"], "GBps": round(path_gbs, 1), "frac": round(path_gbs / HBM_PEAK_GBS, 4),
                  "u_node": alg["u_node"], "u_leaf": alg["u_leaf"]},
         "stages": stages,
+        "timing_stats": timing_stats,
         "cpu_baseline": cpu,
+        "cpu_baseline_one_core": cpu_single,
         "dense_ff": dense,
         "parity": parity,
     }

@@ -53,6 +53,8 @@ def _load():
         _lib.fff_oracle_forward_soft.argtypes = [vp] * 7 + [i32, i32, i32, i64, i64, i64, i32, f64, vp, vp]
         _lib.fff_oracle_bucket.argtypes = [vp, i64, i32, vp, vp, vp]
         _lib.fff_oracle_moe_top1.argtypes = [vp] * 7 + [i64, i32, i32, i64, i64, i64, i32, vp, vp, vp]
+        _lib.fff_oracle_set_threads.argtypes = [i32]
+        _lib.fff_oracle_set_threads.restype = None
         for n in ("training_size", "inference_size"):
             f = getattr(_lib, "fff_oracle_" + n)
             f.argtypes, f.restype = [i32, i32, i32], i64
@@ -198,6 +200,11 @@ def training_width(depth, leaf_size):
 
 def inference_width(depth, leaf_size):
     return int(_load().fff_oracle_inference_width(depth, leaf_size))
+
+
+def set_threads(n: int) -> None:
+    """Use n OpenMP threads from now on (timing the oracle on one core beside all cores)."""
+    _load().fff_oracle_set_threads(int(n))
 
 
 def num_threads() -> int:

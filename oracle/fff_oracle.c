@@ -303,6 +303,16 @@ int fff_oracle_moe_top1(const void *x, const void *gate_w, const void *gate_b, c
 int64_t fff_oracle_training_width(int depth, int leaf_size) { return ((int64_t)1 << depth) * leaf_size; }
 int64_t fff_oracle_inference_width(int depth, int leaf_size) { (void)depth; return leaf_size; }
 
+/* Number of OpenMP threads the oracle's token loops use from now on (n >= 1); no-op without OpenMP. */
+void fff_oracle_set_threads(int n) {
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int fff_oracle_num_threads(void) {
 #ifdef _OPENMP
     extern int omp_get_max_threads(void);
