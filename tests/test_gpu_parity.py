@@ -5,7 +5,7 @@ import pytest
 
 import fff_workloads as W
 import oracle
-from fff_testlib import check_against_oracle, oracle_inputs, out_to_f64, run_forward, to_device
+from fff_testlib import ROUTING_MARGIN, TOL, check_against_oracle, oracle_inputs, out_to_f64, run_forward, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -344,3 +344,32 @@ def test_random_shapes(case, path):
     finally:
         F.fff_set_option("path", 0)
     _log("%s path=%d took=%d" % (name, path, took), check_against_oracle(w, out, idx))
+
+
+@pytest.mark.parametrize("path", [1, 2, 4], ids=["fused", "staged", "token"])
+def test_nan_tokens_go_left_and_do_not_disturb_their_neighbours(path):
+    """A NaN logit compares false with 0: such a token takes the left child at every node (the
+    oracle's `logit >= 0` does the same) and its output row is NaN; every other token is unaffected."""
+    import torch
+    import paper_2308_14711_amd as F
+    w = W.make_layer("nan", 600, 128, 64, 5, 4, W.ACT_GELU, W.DTYPE_BF16, seed=13)
+    bad = [3, 17, 599]
+    for t in bad:
+        w.bits["x"][t, 5] = 0x7FC0           # a bf16 quiet NaN
+        w.f32["x"][t, 5] = np.nan
+    F.fff_set_option("path", path)
+    try:
+        out, idx = run_forward(w)
+    finally:
+        F.fff_set_option("path", 0)
+    ref_out, ref_idx, margin = oracle.forward_hard(*oracle_inputs(w), w.depth, w.leaf_width, w.act)
+    gi = idx.cpu().numpy()
+    got = out_to_f64(out)
+    assert (ref_idx[bad] == 0).all() and (gi[bad] == 0).all()
+    assert np.isnan(got[bad]).all() and np.isnan(ref_out[bad]).all()
+    ok = np.ones(w.T, bool)
+    ok[bad] = False
+    safe = ok & (margin >= ROUTING_MARGIN)
+    assert np.array_equal(gi[safe], ref_idx[safe])
+    err = np.abs(got[safe] - ref_out[safe]).max(axis=1) / np.maximum(np.abs(ref_out[safe]).max(axis=1), 1e-30)
+    assert np.isfinite(got[ok]).all() and err.max() <= TOL[W.DTYPE_BF16]
