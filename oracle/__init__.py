@@ -52,6 +52,7 @@ def _load():
         _lib.fff_oracle_leaf_forward.argtypes = [vp] * 6 + [i32, i32, i32, i64, i64, i64, i32, vp]
         _lib.fff_oracle_forward_soft.argtypes = [vp] * 7 + [i32, i32, i32, i64, i64, i64, i32, f64, vp, vp]
         _lib.fff_oracle_bucket.argtypes = [vp, i64, i32, vp, vp, vp]
+        _lib.fff_oracle_node_entropy.argtypes = [vp, vp, vp, i32, i64, i64, i32, vp]
         _lib.fff_oracle_moe_top1.argtypes = [vp] * 7 + [i64, i32, i32, i64, i64, i64, i32, vp, vp, vp]
         _lib.fff_oracle_set_threads.argtypes = [i32]
         _lib.fff_oracle_set_threads.restype = None
@@ -147,6 +148,20 @@ def forward_soft(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, l
     if rc:
         raise ValueError("fff_oracle_forward_soft: bad arguments (%d)" % rc)
     return out, mix
+
+
+def node_entropy(x, node_w, node_b, depth) -> np.ndarray:
+    """Batch mean Bernoulli entropy (nats) of every node's choice score, [2^depth - 1] fp64."""
+    x, node_w, node_b = map(_c, (x, node_w, node_b))
+    T, D = x.shape
+    NN = (1 << depth) - 1
+    assert node_w.shape == (NN, D) and node_b.shape == (NN,)
+    dt = _dtype_code((x, node_w, node_b))
+    ent = np.empty((NN,), np.float64)
+    rc = _load().fff_oracle_node_entropy(_p(x), _p(node_w), _p(node_b), depth, T, D, dt, _p(ent))
+    if rc:
+        raise ValueError("fff_oracle_node_entropy: bad arguments (%d)" % rc)
+    return ent
 
 
 def moe_top1(x, gate_w, gate_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, leaf_width, act,

@@ -16,6 +16,8 @@
  *                            c * F(right) + (1 - c) * F(left).
  *   fff_oracle_leaf_forward  the leaf <D, l, O> feedforward network of the
  *                            Definition, evaluated at a given leaf.
+ *   fff_oracle_node_entropy  batch mean entropy of the node choice scores
+ *                            (paragraph "Hardening").
  *   fff_oracle_moe_top1      mixture of experts with one engaged expert and
  *                            noiseless gating (section "Inference speed
  *                            comparison"): argmax of the gating logits, then
@@ -247,6 +249,33 @@ int64_t fff_oracle_training_size(int depth, int node_size, int leaf_size) {
 int64_t fff_oracle_inference_size(int depth, int node_size, int leaf_size) {
     return (int64_t)depth * node_size + leaf_size;
 }
+/*
+ * Batch mean of the entropy of every node's choice score, read as a Bernoulli
+ * probability (paragraph "Hardening": hardening is tracked by monitoring the
+ * batch mean of entropies of the choice scores at each node).  Natural
+ * logarithm; 0 log 0 = 0.  Every token visits every node here, as in Forward_T.
+ * entropy [2^depth - 1], heap order.
+ */
+int fff_oracle_node_entropy(const void *x, const void *node_w, const void *node_b, int depth,
+                            int64_t T, int64_t D, int dtype, double *entropy) {
+    if (!args_ok(depth, 1, ORACLE_ACT_RELU, T, D, 1, dtype)) return 1;
+    for (int m = 0; m < depth; ++m) {
+        for (int64_t n = 0; n < ((int64_t)1 << m); ++n) {
+            double sum = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                double scale;
+                const double logit = node_logit(x, t * D, node_w, node_b, m, n, D, dtype, &scale);
+                const double c = 1.0 / (1.0 + exp(-logit));
+                const double h0 = c > 0.0 ? -c * log(c) : 0.0;
+                const double h1 = c < 1.0 ? -(1.0 - c) * log(1.0 - c) : 0.0;
+                sum += h0 + h1;
+            }
+            entropy[(((int64_t)1 << m) - 1) + n] = T > 0 ? sum / (double)T : 0.0;
+        }
+    }
+    return 0;
+}
+
 /*
  * Mixture of experts with k = 1 and noiseless gating, the configuration of the
  * paper's inference speed comparison (section "Inference speed comparison":

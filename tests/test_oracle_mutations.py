@@ -41,6 +41,9 @@ MUTATIONS = [
     ("moe_expert_not_used", "leaf_b2, arg, leaf_width, act", "leaf_b2, 0, leaf_width, act"),
     ("moe_margin_not_relative", "(sc > 0.0 ? (best - second) / sc : 0.0)", "(best - second)"),
     ("moe_second_not_tracked", "} else if (logit > second) {\n                second = logit; second_scale = scale;\n            }", "}"),
+    ("entropy_one_sided", "sum += h0 + h1;\n            }\n            entropy[", "sum += h0;\n            }\n            entropy["),
+    ("entropy_not_a_mean", "entropy[(((int64_t)1 << m) - 1) + n] = T > 0 ? sum / (double)T : 0.0;", "entropy[(((int64_t)1 << m) - 1) + n] = sum;"),
+    ("entropy_level_order", "entropy[(((int64_t)1 << m) - 1) + n] =", "entropy[(((int64_t)1 << m) - 1) + (((int64_t)1 << m) - 1 - n)] ="),
     ("bf16_widen_shift", "uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 16;", "uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 15;"),
 ]
 
@@ -59,6 +62,7 @@ PINS = [
     pins.test_leaf_forward_matches_forward_hard_and_library,
     pins.test_bf16_and_f32_inputs_are_widened_exactly,
     lambda: pins.test_bucket_against_library_sort(8, 5000),
+    pins.test_node_entropy_closed_forms_and_library,
     moe_pins.test_moe_hand_worked_example,
     moe_pins.test_moe_one_hot_gates_pick_by_scalar_compares,
     moe_pins.test_moe_with_two_experts_is_a_depth_one_fff,

@@ -274,3 +274,28 @@ def test_bucket_against_library_sort(depth, T):
     for j in range(NL):
         seg = perm[offset[j]:offset[j + 1]]
         assert np.all(idx[seg] == j) and np.all(np.diff(seg) > 0)
+
+
+def test_node_entropy_closed_forms_and_library():
+    """Batch mean entropy of the node choice scores (paragraph "Hardening"): ln 2 for undecided
+    nodes, 0 for saturated ones, symmetric under a sign flip of the node, and equal to the
+    textbook binary entropy of sigmoid(logits) computed with library routines."""
+    rng = np.random.default_rng(31)
+    T, D, depth = 200, 6, 3
+    NN = (1 << depth) - 1
+    x = rng.normal(size=(T, D))
+    assert np.allclose(oracle.node_entropy(x, np.zeros((NN, D)), np.zeros(NN), depth), np.log(2.0), rtol=0, atol=1e-13)
+    w = rng.normal(size=(NN, D))
+    b = rng.normal(size=NN)
+    assert np.all(oracle.node_entropy(x, 1e4 * w, 1e4 * b, depth) < 1e-6)
+    e = oracle.node_entropy(x, w, b, depth)
+    assert np.allclose(e, oracle.node_entropy(x, -w, -b, depth), rtol=1e-12)
+    from scipy.special import expit, xlogy
+    c = expit(x @ w.T + b)                                # [T, NN], heap order = row order of w
+    ref = (-(xlogy(c, c) + xlogy(1 - c, 1 - c))).mean(axis=0)
+    assert np.allclose(e, ref, rtol=1e-12, atol=1e-15)
+    # only the node's own row matters: changing another node leaves its entropy alone
+    w2 = w.copy()
+    w2[4] *= 3.0
+    e2 = oracle.node_entropy(x, w2, b, depth)
+    assert np.array_equal(np.delete(e2, 4), np.delete(e, 4)) and e2[4] != e[4]
