@@ -150,6 +150,31 @@ int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b,
                          void* out, int32_t* expert_idx, void* stream,
                          int64_t T, int64_t D, int64_t O, int dtype);
 
+/*
+ * fff_forward_soft: Forward_T of Algorithm 1, the soft pass used in training and
+ * for the hardening diagnostics.  Every node gives a choice score
+ * c = sigmoid(w . x + b); the weight of a leaf is the product over its path of
+ * c (right turns) and 1 - c (left turns) -- a stochastic vector over the
+ * leaves -- and out[t] = sum over leaves of weight * leaf output.  Dense: all
+ * 2^depth leaves are evaluated for every token, as three contractions on the
+ * matrix cores (fp32 accumulation; the weighted hidden activations are rounded
+ * to bf16 before the last one).
+ *   mix      optional, device, [T, 2^depth] fp32: the leaf weights
+ *   entropy  optional, device, [2^depth - 1] fp32, heap order: batch mean of the
+ *            Bernoulli entropy (natural logarithm) of each node's choice score
+ *            (paragraph "Hardening")
+ *   dtype must be FFF_BF16 with D % 8 == 0 and 16-byte aligned rows (else
+ *   FFF_ERR_UNSUPPORTED); other arguments, ownership, asynchrony and errors as
+ *   for fff_forward_hard.  Needs about
+ *   4 T (2^(depth+1)) + 2 (T + O) 2^depth (leaf_width + 1) bytes of workspace,
+ *   allocated by the first call with larger sizes (FFF_ERR_WORKSPACE if that fails).
+ */
+int fff_forward_soft(const void* x, const void* node_w, const void* node_b,
+                     const void* leaf_w1, const void* leaf_b1, const void* leaf_w2,
+                     const void* leaf_b2, int depth, int leaf_width, int act,
+                     void* out, float* mix, float* entropy, void* stream,
+                     int64_t T, int64_t D, int64_t O, int dtype);
+
 /* Bytes of workspace a call with these sizes uses on the current device. */
 size_t fff_workspace_bytes(int64_t T, int depth);
 

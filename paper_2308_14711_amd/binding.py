@@ -41,6 +41,7 @@ def lib() -> ctypes.CDLL:
         L.fff_bucket.argtypes = [vp, i64, i32, vp, vp, vp, vp]
         L.fff_leaf_forward.argtypes = [vp] * 6 + [i32, i32, i32, vp, vp, i64, i64, i64, i32]
         L.fff_moe_top1_forward.argtypes = [vp] * 7 + [i32, i32, i32, vp, vp, vp, i64, i64, i64, i32]
+        L.fff_forward_soft.argtypes = [vp] * 7 + [i32, i32, i32, vp, vp, vp, vp, i64, i64, i64, i32]
         L.fff_workspace_bytes.argtypes = [i64, i32]
         L.fff_workspace_bytes.restype = ctypes.c_size_t
         L.fff_reserve_workspace.argtypes = [i64, i32]
@@ -138,6 +139,19 @@ def fff_moe_top1_forward(x, gate_w, gate_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, 
                                       _ptr(leaf_w2), _ptr(leaf_b2), log2_experts, leaf_width, act, _ptr(out),
                                       _ptr(expert_idx), _stream_handle(stream), T, D, O, _dtype_code(x)),
            "fff_moe_top1_forward")
+
+
+def fff_forward_soft(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, leaf_width, act, out,
+                     mix=None, entropy=None, stream=None) -> None:
+    """Forward_T: the soft mixture over all leaves.  mix [T, 2^depth] and entropy [2^depth - 1] are
+    optional float32 device outputs."""
+    _check_dense(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, mix, entropy)
+    T, D = x.shape
+    O = out.shape[1]
+    _check(lib().fff_forward_soft(_ptr(x), _ptr(node_w), _ptr(node_b), _ptr(leaf_w1), _ptr(leaf_b1),
+                                  _ptr(leaf_w2), _ptr(leaf_b2), depth, leaf_width, act, _ptr(out),
+                                  _ptr(mix), _ptr(entropy), _stream_handle(stream), T, D, O, _dtype_code(x)),
+           "fff_forward_soft")
 
 
 def fff_workspace_bytes(T: int, depth: int) -> int:

@@ -402,6 +402,32 @@ int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b, 
     return run_leaf_stage(p, ei, ws, s, true);
 }
 
+int fff_forward_soft(const void* x, const void* node_w, const void* node_b, const void* leaf_w1,
+                     const void* leaf_b1, const void* leaf_w2, const void* leaf_b2, int depth, int leaf_width,
+                     int act, void* out, float* mix, float* entropy, void* stream, int64_t T, int64_t D,
+                     int64_t O, int dtype) {
+    int rc = check_common(depth, T, D, dtype);
+    if (rc == FFF_OK) rc = check_leaf(depth, leaf_width, act, T, D, O);
+    if (rc != FFF_OK) return rc;
+    if (T == 0) return FFF_OK;
+    if (!x || !leaf_w1 || !leaf_b1 || !leaf_w2 || !leaf_b2 || !out) return FFF_ERR_NULL;
+    if (depth > 0 && (!node_w || !node_b)) return FFF_ERR_NULL;
+    const int64_t es = dtype == FFF_BF16 ? 2 : 4;
+    if (overlaps(x, T * D * es, out, T * O * es)) return FFF_ERR_ALIAS;
+    Problem p{x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, nullptr,
+              T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
+    if (!soft_shape_ok(p)) return FFF_ERR_UNSUPPORTED;
+    // every token meets every leaf: the intermediate matrices are T x 2^depth x (leaf_width + 1) wide
+    const int64_t words = soft_scratch_words(p);
+    if (words > kMaxElems / 4) return FFF_ERR_SHAPE;
+    g_last_error.clear();
+    Workspace ws;
+    Layout lay;
+    if ((rc = get_workspace(0, 0, &ws, &lay, words)) != FFF_OK) return rc;
+    hipError_t e = launch_forward_soft(p, ws.extra, mix, entropy, (hipStream_t)stream);
+    return e == hipSuccess ? FFF_OK : set_device_error(e, "soft forward kernel launch");
+}
+
 size_t fff_workspace_bytes(int64_t T, int depth) {
     if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH) return 0;
     return (size_t)layout_for(T, depth).total * sizeof(int32_t);

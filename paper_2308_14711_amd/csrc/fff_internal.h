@@ -102,6 +102,13 @@ bool moe_gate_shape_ok(const void* x, const void* gate_w, int64_t D, bool bf16);
 hipError_t launch_moe_gate(const void* x, const void* gate_w, const void* gate_b, int64_t T, int64_t D,
                            int64_t n_experts, int32_t* cand, int32_t* expert_idx, hipStream_t s);
 
+// Forward_T (fff_soft.hip): the soft mixture over all leaves on the matrix cores.  scratch holds
+// soft_scratch_words(p) 32-bit words; mix [T, 2^depth] and entropy [2^depth - 1] (fp32) are optional outputs.
+bool soft_shape_ok(const Problem& p);
+int64_t soft_scratch_words(const Problem& p);
+hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_out, float* entropy_out,
+                               hipStream_t s);
+
 // Whole forward pass in one launch, one token per lane group (any shape).
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 

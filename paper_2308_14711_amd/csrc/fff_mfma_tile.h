@@ -1,0 +1,133 @@
+// The 64 x 128 MFMA tile shared by the dense contractions of this library (the gating of the
+// mixture-of-experts comparator, the node and leaf contractions of the soft forward pass):
+// C[m0 .. m0+63][n0 .. n0+127] = A[M, K] . B[N, K]^T for bf16 operands that are both K-contiguous,
+// fp32 accumulation on v_mfma_f32_16x16x32_bf16.
+//
+// A block of 256 threads (4 waves) walks K in chunks of 64 through double-buffered LDS tiles
+// (16-byte pieces, coalesced loads, piece c of row r at slot 8 r + ((c + r / 2) mod 8): stores and
+// operand reads are both free of bank conflicts).  Wave w owns columns 32 w .. 32 w + 31 of the
+// tile and all 64 rows: acc[mt][nt], lane (j, kg) of which holds rows 16 mt + 4 kg + q (q = 0..3)
+// against column 32 w + 16 nt + j.
+#pragma once
+#include "fff_device.h"
+
+namespace fff {
+
+constexpr int kTileM = 64;      // rows (tokens) per block
+constexpr int kTileN = 128;     // columns per block
+constexpr int kTileK = 64;      // K elements per chunk (8 pieces of 16 bytes per row)
+
+// v or zeros, component by component (a conditional on the 16-byte struct itself is lowered
+// through memory)
+__device__ __forceinline__ uint4 keep_if(bool ok, const uint4& v) {
+    return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
+}
+
+__device__ __forceinline__ int tile_swz(int row, int piece) { return 8 * row + ((piece + (row >> 1)) & 7); }
+
+struct TileLds {
+    uint4 a[2][kTileM * 8];
+    uint4 b[2][kTileN * 8];
+};
+
+// A: M rows of lda elements, B: N rows of ldb elements (row starts 16-byte aligned, K a multiple
+// of 8); rows past M / N and K past the end count as zeros.  All 256 threads of the block call it.
+__device__ __forceinline__ void mfma_tile_64x128(const uint16_t* __restrict__ A, int64_t lda, int64_t M,
+                                                 const uint16_t* __restrict__ B, int64_t ldb, int64_t N, int K,
+                                                 int64_t m0, int64_t n0, TileLds& lds, f32x4_t (&acc)[4][2]) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int j = lane & 15, kg = lane >> 4;
+    const int D = K;
+    const int n_chunks = (K + kTileK - 1) / kTileK;
+    uint4 (&lds_a)[2][kTileM * 8] = lds.a;
+    uint4 (&lds_b)[2][kTileN * 8] = lds.b;
+    // loader roles: 2 pieces of the token tile, 4 of the expert tile (8 consecutive threads = one
+    // row's 128 bytes).  kDepth chunks are kept in flight in registers: with one chunk ahead the
+    // loop is a chain of memory round trips (12 of them for D = 768), since a chunk's arithmetic
+    // is only 16 MFMAs per wave.
+    // Loads are unconditional with clamped addresses; rows past the end and K past D are zeroed
+    // when the chunk goes to LDS.  (A predicated 16-byte load compiles to guarded dword loads with
+    // a wait each, and a select right after the load makes the wave wait for it there.)
+    constexpr int kDepth = 4;
+    const int pc = tid & 7;                      // this thread's piece of every row it loads
+    const int64_t ta0 = m0 + (tid >> 3), ta1 = ta0 + 32;
+    const int64_t eb0 = n0 + (tid >> 3), eb1 = eb0 + 32, eb2 = eb0 + 64, eb3 = eb0 + 96;
+    const uint16_t* const pa0 = A + (ta0 < M ? ta0 : M - 1) * lda + 8 * pc;
+    const uint16_t* const pa1 = A + (ta1 < M ? ta1 : M - 1) * lda + 8 * pc;
+    const uint16_t* const pb0 = B + (eb0 < N ? eb0 : N - 1) * ldb + 8 * pc;
+    const uint16_t* const pb1 = B + (eb1 < N ? eb1 : N - 1) * ldb + 8 * pc;
+    const uint16_t* const pb2 = B + (eb2 < N ? eb2 : N - 1) * ldb + 8 * pc;
+    const uint16_t* const pb3 = B + (eb3 < N ? eb3 : N - 1) * ldb + 8 * pc;
+    const bool va0 = ta0 < M, va1 = ta1 < M;
+    const bool vb0 = eb0 < N, vb1 = eb1 < N, vb2 = eb2 < N, vb3 = eb3 < N;
+    const int sa0 = tile_swz(tid >> 3, pc), sa1 = tile_swz((tid >> 3) + 32, pc);
+    const int sb0 = sa0, sb1 = sa1, sb2 = tile_swz((tid >> 3) + 64, pc), sb3 = tile_swz((tid >> 3) + 96, pc);
+    struct Chunk { uint4 a0, a1, b0, b1, b2, b3; };   // named members: they stay in registers
+#define FFF_TILE_FETCH(KC, Q)                                                   \
+    do {                                                                        \
+        const int koff_ = (KC) * kTileK + 8 * pc < D ? (KC) * kTileK : 0;       \
+        Q.a0 = *(const uint4*)(pa0 + koff_);                                    \
+        Q.a1 = *(const uint4*)(pa1 + koff_);                                    \
+        Q.b0 = *(const uint4*)(pb0 + koff_);                                    \
+        Q.b1 = *(const uint4*)(pb1 + koff_);                                    \
+        Q.b2 = *(const uint4*)(pb2 + koff_);                                    \
+        Q.b3 = *(const uint4*)(pb3 + koff_);                                    \
+    } while (0)
+#define FFF_TILE_STASH(KC, BUF, Q)                                              \
+    do {                                                                        \
+        const bool kin_ = (KC) * kTileK + 8 * pc < D;                           \
+        lds_a[BUF][sa0] = keep_if(kin_ && va0, Q.a0);                               \
+        lds_a[BUF][sa1] = keep_if(kin_ && va1, Q.a1);                               \
+        lds_b[BUF][sb0] = keep_if(kin_ && vb0, Q.b0);                               \
+        lds_b[BUF][sb1] = keep_if(kin_ && vb1, Q.b1);                               \
+        lds_b[BUF][sb2] = keep_if(kin_ && vb2, Q.b2);                               \
+        lds_b[BUF][sb3] = keep_if(kin_ && vb3, Q.b3);                               \
+    } while (0)
+
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // The loop body has no branches (the wait counters are only tracked along straight code):
+    // chunks past the end are fetched from a clamped address and stored as zeros, and the trip
+    // count is rounded up to a multiple of kDepth; the extra MFMAs add zeros.
+    Chunk c0, c1, c2, c3;
+    FFF_TILE_FETCH(0, c0);
+    FFF_TILE_FETCH(1, c1);
+    FFF_TILE_FETCH(2, c2);
+    FFF_TILE_FETCH(3, c3);
+    FFF_TILE_STASH(0, 0, c0);
+    __syncthreads();
+    // one chunk: refill the register slot the chunk came from, multiply out of LDS buffer BUF,
+    // put the next chunk into the other buffer.  Step u of a chunk gives lane group kg the piece
+    // 2 kg + u of every row (K is only a summation order).
+#define FFF_TILE_STEP(KC, BUF, CUR, NEXT)                                                                          \
+    do {                                                                                                           \
+        FFF_TILE_FETCH((KC) + kDepth, CUR);                                                                        \
+        _Pragma("unroll") for (int u = 0; u < 2; ++u) {                                                            \
+            bf16x8_t fa[4], fb[2];                                                                                 \
+            _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
+                fa[mt] = __builtin_bit_cast(bf16x8_t, lds_a[BUF][tile_swz(16 * mt + j, 2 * kg + u)]);                   \
+            _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)                                                       \
+                fb[nt] = __builtin_bit_cast(bf16x8_t, lds_b[BUF][tile_swz(32 * wv + 16 * nt + j, 2 * kg + u)]);         \
+            _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
+                _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)                                                   \
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);   \
+        }                                                                                                          \
+        FFF_TILE_STASH((KC) + 1, (BUF) ^ 1, NEXT);                                                                 \
+        __syncthreads();                                                                                           \
+    } while (0)
+    for (int kc0 = 0; kc0 < n_chunks; kc0 += kDepth) {
+        FFF_TILE_STEP(kc0 + 0, 0, c0, c1);
+        FFF_TILE_STEP(kc0 + 1, 1, c1, c2);
+        FFF_TILE_STEP(kc0 + 2, 0, c2, c3);
+        FFF_TILE_STEP(kc0 + 3, 1, c3, c0);
+    }
+#undef FFF_TILE_STEP
+#undef FFF_TILE_STASH
+#undef FFF_TILE_FETCH
+
+}
+
+}  // namespace fff

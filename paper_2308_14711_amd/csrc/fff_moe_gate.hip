@@ -15,13 +15,13 @@
 // the tile stays in L2 while the gating matrix streams from HBM once.
 #include "fff_device.h"
 #include "fff_internal.h"
+#include "fff_mfma_tile.h"
 
 namespace fff {
 namespace {
 
-constexpr int kGateTokens = 64;     // tokens per block
-constexpr int kGateExperts = 128;   // experts per block
-constexpr int kGateK = 64;          // K elements per chunk (8 pieces of 16 bytes per row)
+constexpr int kGateTokens = kTileM;     // tokens per block
+constexpr int kGateExperts = kTileN;    // experts per block
 
 struct GateArgs {
     const uint16_t* x;
@@ -32,14 +32,6 @@ struct GateArgs {
     int64_t T, G;
     int D, n_eblocks;
 };
-
-// v or zeros, component by component (a conditional on the 16-byte struct itself is lowered
-// through memory)
-__device__ __forceinline__ uint4 keep_if(bool ok, const uint4& v) {
-    return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
-}
-
-__device__ __forceinline__ int swz(int row, int piece) { return 8 * row + ((piece + (row >> 1)) & 7); }
 
 // (v, i) <- the better of (v, i) and (v2, i2): larger value, then lower index
 __device__ __forceinline__ void better(float& v, int32_t& i, float v2, int32_t i2) {
@@ -59,8 +51,7 @@ template <int N> __device__ __forceinline__ void row_step(float& v, int32_t& i) 
 }
 
 __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
-    __shared__ uint4 lds_a[2][kGateTokens * 8];
-    __shared__ uint4 lds_b[2][kGateExperts * 8];
+    __shared__ TileLds tile;
     __shared__ float part_v[4][kGateTokens];
     __shared__ int32_t part_i[4][kGateTokens];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -69,57 +60,8 @@ __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
     const int64_t t0 = (int64_t)(blockIdx.x / a.n_eblocks) * kGateTokens;
     const int64_t e0 = (int64_t)eb * kGateExperts;
     const int D = a.D;
-    const int n_chunks = (D + kGateK - 1) / kGateK;
-
-    // loader roles: 2 pieces of the token tile, 4 of the expert tile (8 consecutive threads = one
-    // row's 128 bytes).  kDepth chunks are kept in flight in registers: with one chunk ahead the
-    // loop is a chain of memory round trips (12 of them for D = 768), since a chunk's arithmetic
-    // is only 16 MFMAs per wave.
-    // Loads are unconditional with clamped addresses; rows past the end and K past D are zeroed
-    // when the chunk goes to LDS.  (A predicated 16-byte load compiles to guarded dword loads with
-    // a wait each, and a select right after the load makes the wave wait for it there.)
-    constexpr int kDepth = 4;
-    const int pc = tid & 7;                      // this thread's piece of every row it loads
-    const int64_t ta0 = t0 + (tid >> 3), ta1 = ta0 + 32;
-    const int64_t eb0 = e0 + (tid >> 3), eb1 = eb0 + 32, eb2 = eb0 + 64, eb3 = eb0 + 96;
-    const uint16_t* const pa0 = a.x + (ta0 < a.T ? ta0 : a.T - 1) * D + 8 * pc;
-    const uint16_t* const pa1 = a.x + (ta1 < a.T ? ta1 : a.T - 1) * D + 8 * pc;
-    const uint16_t* const pb0 = a.gate_w + (eb0 < a.G ? eb0 : a.G - 1) * D + 8 * pc;
-    const uint16_t* const pb1 = a.gate_w + (eb1 < a.G ? eb1 : a.G - 1) * D + 8 * pc;
-    const uint16_t* const pb2 = a.gate_w + (eb2 < a.G ? eb2 : a.G - 1) * D + 8 * pc;
-    const uint16_t* const pb3 = a.gate_w + (eb3 < a.G ? eb3 : a.G - 1) * D + 8 * pc;
-    const bool va0 = ta0 < a.T, va1 = ta1 < a.T;
-    const bool vb0 = eb0 < a.G, vb1 = eb1 < a.G, vb2 = eb2 < a.G, vb3 = eb3 < a.G;
-    const int sa0 = swz(tid >> 3, pc), sa1 = swz((tid >> 3) + 32, pc);
-    const int sb0 = sa0, sb1 = sa1, sb2 = swz((tid >> 3) + 64, pc), sb3 = swz((tid >> 3) + 96, pc);
-    struct Chunk { uint4 a0, a1, b0, b1, b2, b3; };   // named members: they stay in registers
-#define FFF_GATE_FETCH(KC, Q)                                                   \
-    do {                                                                        \
-        const int koff_ = (KC) * kGateK + 8 * pc < D ? (KC) * kGateK : 0;       \
-        Q.a0 = *(const uint4*)(pa0 + koff_);                                    \
-        Q.a1 = *(const uint4*)(pa1 + koff_);                                    \
-        Q.b0 = *(const uint4*)(pb0 + koff_);                                    \
-        Q.b1 = *(const uint4*)(pb1 + koff_);                                    \
-        Q.b2 = *(const uint4*)(pb2 + koff_);                                    \
-        Q.b3 = *(const uint4*)(pb3 + koff_);                                    \
-    } while (0)
-#define FFF_GATE_STASH(KC, BUF, Q)                                              \
-    do {                                                                        \
-        const bool kin_ = (KC) * kGateK + 8 * pc < D;                           \
-        lds_a[BUF][sa0] = keep_if(kin_ && va0, Q.a0);                               \
-        lds_a[BUF][sa1] = keep_if(kin_ && va1, Q.a1);                               \
-        lds_b[BUF][sb0] = keep_if(kin_ && vb0, Q.b0);                               \
-        lds_b[BUF][sb1] = keep_if(kin_ && vb1, Q.b1);                               \
-        lds_b[BUF][sb2] = keep_if(kin_ && vb2, Q.b2);                               \
-        lds_b[BUF][sb3] = keep_if(kin_ && vb3, Q.b3);                               \
-    } while (0)
 
     f32x4_t acc[4][2];
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
     // the biases of this lane's two experts are requested now, long before they are needed
     const float ninf = -__builtin_inff();
     float bias[2];
@@ -132,44 +74,7 @@ __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
         bias[nt] = !ok ? ninf : (a.gate_b ? bf16_to_f32(a.gate_b[e]) : 0.0f);
     }
 
-    // The loop body has no branches (the wait counters are only tracked along straight code):
-    // chunks past the end are fetched from a clamped address and stored as zeros, and the trip
-    // count is rounded up to a multiple of kDepth; the extra MFMAs add zeros.
-    Chunk c0, c1, c2, c3;
-    FFF_GATE_FETCH(0, c0);
-    FFF_GATE_FETCH(1, c1);
-    FFF_GATE_FETCH(2, c2);
-    FFF_GATE_FETCH(3, c3);
-    FFF_GATE_STASH(0, 0, c0);
-    __syncthreads();
-    // one chunk: refill the register slot the chunk came from, multiply out of LDS buffer BUF,
-    // put the next chunk into the other buffer.  Step u of a chunk gives lane group kg the piece
-    // 2 kg + u of every row (K is only a summation order).
-#define FFF_GATE_STEP(KC, BUF, CUR, NEXT)                                                                          \
-    do {                                                                                                           \
-        FFF_GATE_FETCH((KC) + kDepth, CUR);                                                                        \
-        _Pragma("unroll") for (int u = 0; u < 2; ++u) {                                                            \
-            bf16x8_t fa[4], fb[2];                                                                                 \
-            _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
-                fa[mt] = __builtin_bit_cast(bf16x8_t, lds_a[BUF][swz(16 * mt + j, 2 * kg + u)]);                   \
-            _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)                                                       \
-                fb[nt] = __builtin_bit_cast(bf16x8_t, lds_b[BUF][swz(32 * wv + 16 * nt + j, 2 * kg + u)]);         \
-            _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
-                _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)                                                   \
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);   \
-        }                                                                                                          \
-        FFF_GATE_STASH((KC) + 1, (BUF) ^ 1, NEXT);                                                                 \
-        __syncthreads();                                                                                           \
-    } while (0)
-    for (int kc0 = 0; kc0 < n_chunks; kc0 += kDepth) {
-        FFF_GATE_STEP(kc0 + 0, 0, c0, c1);
-        FFF_GATE_STEP(kc0 + 1, 1, c1, c2);
-        FFF_GATE_STEP(kc0 + 2, 0, c2, c3);
-        FFF_GATE_STEP(kc0 + 3, 1, c3, c0);
-    }
-#undef FFF_GATE_STEP
-#undef FFF_GATE_STASH
-#undef FFF_GATE_FETCH
+    mfma_tile_64x128(a.x, D, a.T, a.gate_w, D, a.G, D, t0, e0, tile, acc);
 
     // lane (j, kg) of tile (mt, nt) holds tokens 16 mt + 4 kg + q (q = 0..3) against expert
     // e0 + 32 wv + 16 nt + j: bias, then the best expert per token over the wave's 32

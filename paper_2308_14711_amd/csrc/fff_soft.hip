@@ -1,0 +1,252 @@
+// The soft forward pass of an FFF -- Forward_T of Algorithm 1: every node gives a choice score
+// c = sigmoid(w . x + b), the leaves are mixed with the products of the scores along their paths
+// (the stochastic vector over the leaves), out = sum_leaf mix[leaf] * Leaf_leaf(x).  This is the
+// pass used in training and for the hardening diagnostics (batch mean entropy of the choice
+// scores per node, paragraph "Hardening"); unlike Forward_I it is dense, so it runs on the matrix
+// cores as three contractions over the shared 64 x 128 MFMA tile:
+//
+//   nodes   C[t][n]   = sigmoid(x[t] . node_w[n] + node_b[n])                       fp32, [T, 2^d - 1]
+//   mix     M[t][l]   = prod over the path of leaf l of (bit ? c : 1 - c)           fp32, [T, 2^d]
+//   hidden  H[t][k]   = act(x[t] . W1[k] + b1[k]) * M[t][k / l]   (k = leaf * l + neuron)   bf16
+//           H[t][2^d l + leaf] = M[t][leaf]                          (carries the output bias)
+//   out     out[t][o] = H[t] . W2x[o]   with W2x[o] = (W2[.][o], b2[.][o]): W2 and b2 transposed
+//                                                                     once per call into [O, K2]
+//
+// so that the weighting by the mixture and the bias both ride inside the last contraction.
+#include "fff_device.h"
+#include "fff_internal.h"
+#include "fff_mfma_tile.h"
+
+namespace fff {
+namespace {
+
+struct SoftArgs {
+    const uint16_t* x;
+    const uint16_t* node_w;
+    const uint16_t* node_b;
+    const uint16_t* w1;
+    const uint16_t* b1;
+    const uint16_t* w2;
+    const uint16_t* b2;
+    float* choice;        // [T][NN]
+    float* mix;           // [T][NL]
+    uint16_t* hid;        // [T][K2]
+    uint16_t* w2x;        // [O][K2]
+    uint16_t* out;        // [T][O]
+    int64_t T;
+    int D, O, depth, L, act;
+    int64_t NN, NL, K2;   // K2 = NL * (L + 1) rounded up to a multiple of 8
+};
+
+__device__ __forceinline__ int64_t tile_row0(int64_t n_col_blocks) { return (int64_t)(blockIdx.x / n_col_blocks) * kTileM; }
+__device__ __forceinline__ int64_t tile_col0(int64_t n_col_blocks) { return (int64_t)(blockIdx.x % n_col_blocks) * kTileN; }
+
+// nodes: choice scores
+__global__ __launch_bounds__(256) void soft_nodes_kernel(const SoftArgs a) {
+    __shared__ TileLds tile;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15, kg = lane >> 4;
+    const int64_t ncb = (a.NN + kTileN - 1) / kTileN;
+    const int64_t t0 = tile_row0(ncb), n0 = tile_col0(ncb);
+    f32x4_t acc[4][2];
+    mfma_tile_64x128(a.x, a.D, a.T, a.node_w, a.D, a.NN, a.D, t0, n0, tile, acc);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int64_t n = n0 + 32 * wv + 16 * nt + j;
+        if (n >= a.NN) continue;
+        const float b = bf16_to_f32(a.node_b[n]);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t t = t0 + 16 * mt + 4 * kg + q;
+                if (t < a.T) a.choice[t * a.NN + n] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
+            }
+    }
+}
+
+// mixture weights: one thread per (token, leaf); also the bias columns of the hidden matrix
+__global__ __launch_bounds__(256) void soft_mix_kernel(const SoftArgs a) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= a.T * a.NL) return;
+    const int64_t t = i / a.NL, leaf = i % a.NL;
+    const float* c = a.choice + t * a.NN;
+    float m = 1.0f;
+    for (int lvl = 0; lvl < a.depth; ++lvl) {
+        const int64_t pos = leaf >> (a.depth - lvl);                  // the path's node at this level
+        const int bit = (int)((leaf >> (a.depth - 1 - lvl)) & 1);
+        const float cs = c[(((int64_t)1 << lvl) - 1) + pos];
+        m *= bit ? cs : 1.0f - cs;
+    }
+    a.mix[i] = m;
+    a.hid[t * a.K2 + a.NL * a.L + leaf] = f32_to_bf16(m);
+    // the padding columns up to K2 (fewer than 8) are cleared by the thread of leaf 0
+    if (leaf == 0)
+        for (int64_t k = a.NL * (a.L + 1); k < a.K2; ++k) a.hid[t * a.K2 + k] = 0;
+}
+
+// hidden: act(x . W1 + b1) scaled by the mixture weight of the neuron's leaf
+__global__ __launch_bounds__(256) void soft_hidden_kernel(const SoftArgs a) {
+    __shared__ TileLds tile;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15, kg = lane >> 4;
+    const int64_t NH = a.NL * a.L;
+    const int64_t ncb = (NH + kTileN - 1) / kTileN;
+    const int64_t t0 = tile_row0(ncb), n0 = tile_col0(ncb);
+    f32x4_t acc[4][2];
+    mfma_tile_64x128(a.x, a.D, a.T, a.w1, a.D, NH, a.D, t0, n0, tile, acc);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int64_t n = n0 + 32 * wv + 16 * nt + j;
+        if (n >= NH) continue;
+        const float b = bf16_to_f32(a.b1[n]);
+        const int64_t leaf = n / a.L;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t t = t0 + 16 * mt + 4 * kg + q;
+                if (t < a.T) a.hid[t * a.K2 + n] = f32_to_bf16(activate(acc[mt][nt][q] + b, a.act) * a.mix[t * a.NL + leaf]);
+            }
+    }
+}
+
+// W2x[o][k] = W2[k][o] for k < NL * L, b2[k - NL * L][o] for the next NL, zeros up to K2.
+// A 32 x 32 tile through LDS: reads run along o, writes along k.
+__global__ __launch_bounds__(256) void soft_w2x_kernel(const SoftArgs a) {
+    __shared__ uint16_t t32[32][33];
+    const int64_t kb = (a.K2 + 31) / 32;
+    const int64_t k0 = (int64_t)(blockIdx.x % kb) * 32, o0 = (int64_t)(blockIdx.x / kb) * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    const int64_t NH = a.NL * a.L;
+    for (int r = ty; r < 32; r += 8) {
+        const int64_t k = k0 + r, o = o0 + tx;
+        uint16_t v = 0;
+        if (o < a.O) {
+            if (k < NH) v = a.w2[k * a.O + o];
+            else if (k < NH + a.NL) v = a.b2[(k - NH) * a.O + o];
+        }
+        t32[r][tx] = v;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int64_t o = o0 + r, k = k0 + tx;
+        if (o < a.O && k < a.K2) a.w2x[o * a.K2 + k] = t32[tx][r];
+    }
+}
+
+// out: the weighted leaf outputs and biases in one contraction over K2
+__global__ __launch_bounds__(256) void soft_out_kernel(const SoftArgs a) {
+    __shared__ TileLds tile;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15, kg = lane >> 4;
+    const int64_t ncb = ((int64_t)a.O + kTileN - 1) / kTileN;
+    const int64_t t0 = tile_row0(ncb), n0 = tile_col0(ncb);
+    f32x4_t acc[4][2];
+    mfma_tile_64x128(a.hid, a.K2, a.T, a.w2x, a.K2, a.O, (int)a.K2, t0, n0, tile, acc);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int64_t o = n0 + 32 * wv + 16 * nt + j;
+        if (o >= a.O) continue;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t t = t0 + 16 * mt + 4 * kg + q;
+                if (t < a.T) a.out[t * a.O + o] = f32_to_bf16(acc[mt][nt][q]);
+            }
+    }
+}
+
+// batch mean of the Bernoulli entropy of every node's choice score: one block per node, a fixed
+// order of additions (so the result does not depend on scheduling)
+__global__ __launch_bounds__(256) void soft_entropy_kernel(const float* __restrict__ choice, int64_t T, int64_t NN,
+                                                           float* __restrict__ entropy) {
+    __shared__ float part[256];
+    const int64_t n = blockIdx.x;
+    float s = 0.0f;
+    for (int64_t t = threadIdx.x; t < T; t += 256) {
+        const float c = choice[t * NN + n];
+        const float h0 = c > 0.0f ? -c * __logf(c) : 0.0f;
+        const float h1 = c < 1.0f ? -(1.0f - c) * __logf(1.0f - c) : 0.0f;
+        s += h0 + h1;
+    }
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int d = 128; d > 0; d >>= 1) {
+        if ((int)threadIdx.x < d) part[threadIdx.x] += part[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) entropy[n] = part[0] / (float)T;
+}
+
+}  // namespace
+
+// bf16, D a multiple of 8, 16-byte aligned rows of x, node_w, leaf_w1
+bool soft_shape_ok(const Problem& p) {
+    return p.bf16 && vec_ok(p.x, p.D, true) && (p.depth == 0 || vec_ok(p.node_w, p.D, true)) &&
+           vec_ok(p.leaf_w1, p.D, true) && p.D < (1 << 30) && p.O < (1 << 30);
+}
+
+static int64_t soft_k2(const Problem& p) {
+    const int64_t NL = (int64_t)1 << p.depth;
+    return (NL * (p.L + 1) + 7) / 8 * 8;
+}
+
+// 32-bit words of scratch: choice scores, mixture weights, hidden matrix, transposed output weights
+int64_t soft_scratch_words(const Problem& p) {
+    const int64_t NL = (int64_t)1 << p.depth, NN = NL - 1, K2 = soft_k2(p);
+    auto up = [](int64_t w) { return (w + 63) / 64 * 64; };
+    return up(p.T * (NN > 0 ? NN : 1)) + up(p.T * NL) + up((p.T * K2 + 1) / 2) + up((p.O * K2 + 1) / 2);
+}
+
+// mix (optional, [T, 2^d] fp32) and entropy (optional, [2^d - 1] fp32) are caller buffers
+hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_out, float* entropy_out,
+                               hipStream_t s) {
+    if (p.T == 0) return hipSuccess;
+    auto up = [](int64_t w) { return (w + 63) / 64 * 64; };
+    SoftArgs a;
+    a.NL = (int64_t)1 << p.depth;
+    a.NN = a.NL - 1;
+    a.K2 = soft_k2(p);
+    a.x = (const uint16_t*)p.x;
+    a.node_w = (const uint16_t*)p.node_w;
+    a.node_b = (const uint16_t*)p.node_b;
+    a.w1 = (const uint16_t*)p.leaf_w1;
+    a.b1 = (const uint16_t*)p.leaf_b1;
+    a.w2 = (const uint16_t*)p.leaf_w2;
+    a.b2 = (const uint16_t*)p.leaf_b2;
+    a.out = (uint16_t*)p.out;
+    a.T = p.T;
+    a.D = (int)p.D;
+    a.O = (int)p.O;
+    a.depth = p.depth;
+    a.L = p.L;
+    a.act = p.act;
+    int32_t* w = scratch;
+    a.choice = (float*)w;
+    w += up(p.T * (a.NN > 0 ? a.NN : 1));
+    a.mix = mix_out ? mix_out : (float*)w;
+    w += up(p.T * a.NL);
+    a.hid = (uint16_t*)w;
+    w += up((p.T * a.K2 + 1) / 2);
+    a.w2x = (uint16_t*)w;
+    const int64_t mb = (p.T + kTileM - 1) / kTileM;
+    hipError_t e;
+    if (a.NN > 0) {
+        soft_nodes_kernel<<<dim3((unsigned)(mb * ((a.NN + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    soft_mix_kernel<<<dim3((unsigned)((p.T * a.NL + 255) / 256)), dim3(256), 0, s>>>(a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    soft_hidden_kernel<<<dim3((unsigned)(mb * ((a.NL * a.L + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    soft_w2x_kernel<<<dim3((unsigned)(((a.K2 + 31) / 32) * ((p.O + 31) / 32))), dim3(256), 0, s>>>(a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    soft_out_kernel<<<dim3((unsigned)(mb * ((p.O + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (entropy_out && a.NN > 0) {
+        soft_entropy_kernel<<<dim3((unsigned)a.NN), dim3(256), 0, s>>>(a.choice, p.T, a.NN, entropy_out);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace fff

@@ -99,3 +99,20 @@ def test_options(L):
     F.fff_set_option("bucketing", 1)
     with pytest.raises(F.FffError):
         F.fff_set_option("no_such_option", 1)
+
+
+def test_forward_soft_rejects_bad_arguments_on_the_host(L):
+    OK, NULL, SHAPE, RANGE, UNSUP = 0, 1, 2, 4, 5
+    soft = lambda **kw: L.fff_forward_soft(
+        kw.get("x", ctypes.c_void_p(256)), kw.get("node_w", ctypes.c_void_p(1 << 20)), ctypes.c_void_p(2 << 20),
+        ctypes.c_void_p(3 << 20), ctypes.c_void_p(4 << 20), ctypes.c_void_p(5 << 20), ctypes.c_void_p(6 << 20),
+        kw.get("depth", 3), 2, kw.get("act", 0), kw.get("out", ctypes.c_void_p(7 << 20)), None, None, None,
+        kw.get("T", 4), kw.get("D", 16), 8, kw.get("dtype", 1))
+    assert soft(T=0) == OK
+    assert soft(x=None) == NULL
+    assert soft(node_w=None) == NULL
+    assert soft(depth=25) == RANGE
+    assert soft(act=9) == UNSUP
+    assert soft(dtype=0) == UNSUP           # bf16 only
+    assert soft(D=12) == UNSUP              # rows must be whole 16-byte vectors
+    assert soft(T=1 << 20, depth=24, out=ctypes.c_void_p(1 << 44)) == SHAPE   # the dense intermediates would not fit any device

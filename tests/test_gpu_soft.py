@@ -1,0 +1,85 @@
+"""GPU parity of the soft forward pass (Forward_T of Algorithm 1) against the CPU oracle, through
+the C ABI: output rows, the mixture weights over the leaves, and the batch mean entropy of the
+node choice scores."""
+import numpy as np
+import pytest
+
+import fff_workloads as W
+import oracle
+from fff_testlib import TOL, oracle_inputs, out_to_f64, to_device
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # name,          T,    D,   O,   depth, L, act
+    ("small",        300,  64,  48,  4, 3,  W.ACT_GELU),
+    ("depth0",       130,  128, 136, 0, 5,  W.ACT_RELU),
+    ("k_tail_deep",  200,  200, 24,  6, 2,  W.ACT_GELU),
+    ("bert_rows",    65,   768, 768, 3, 8,  W.ACT_GELU),
+    ("wide_leaves",  1000, 96,  40,  2, 32, W.ACT_RELU),
+    ("one_token",    1,    64,  8,   5, 1,  W.ACT_GELU),
+    ("odd_k2",       77,   72,  200, 1, 2,  W.ACT_GELU),      # 2 leaves x 3 columns = 6, padded to 8
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_forward_soft_against_the_oracle(case):
+    import torch
+    import paper_2308_14711_amd as F
+    name, T, D, O, depth, L, act = case
+    print("\n[case] soft %s T=%d D=%d O=%d depth=%d L=%d act=%d seed 21" % (name, T, D, O, depth, L, act), flush=True)
+    w = W.make_layer(name, T, D, O, depth, L, act, W.DTYPE_BF16, seed=21)
+    dev = to_device(w)
+    NL, NN = 1 << depth, (1 << depth) - 1
+    out = torch.full((T, O), float("nan"), dtype=torch.bfloat16, device="cuda")
+    mix = torch.full((T, NL), float("nan"), dtype=torch.float32, device="cuda")
+    ent = torch.full((max(NN, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    nw = dev["node_w"] if depth else None
+    nb = dev["node_b"] if depth else None
+    for rep in range(2):        # twice: the second call reuses the workspace
+        F.fff_forward_soft(dev["x"], nw, nb, dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"], dev["leaf_b2"],
+                           depth, L, act, out, mix, ent if depth else None)
+        torch.cuda.synchronize()
+    ref_out, ref_mix = oracle.forward_soft(*oracle_inputs(w), depth, L, act)
+    got = out_to_f64(out)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref_out).max(axis=1) / np.maximum(np.abs(ref_out).max(axis=1), 1e-30)
+    gm = mix.cpu().numpy().astype(np.float64)
+    mix_err = np.abs(gm - ref_mix).max()
+    assert mix_err <= 1e-4, "mixture weights off by %.3e" % mix_err
+    assert np.allclose(gm.sum(axis=1), 1.0, atol=1e-4)
+    assert err.max() <= TOL[W.DTYPE_BF16], "row error %.3e" % err.max()
+    ent_err = 0.0
+    if depth:
+        ref_ent = oracle.node_entropy(w.bits["x"], w.bits["node_w"], w.bits["node_b"], depth)
+        ent_err = np.abs(ent.cpu().numpy().astype(np.float64) - ref_ent).max()
+        assert ent_err <= 1e-4, "entropies off by %.3e" % ent_err
+    print("  soft %s: max row error %.2e, mixture %.1e, entropy %.1e" % (name, err.max(), mix_err, ent_err), flush=True)
+
+
+def test_forward_soft_without_optional_outputs_and_after_hardening():
+    """mix and entropy are optional; with node weights scaled up the soft pass approaches the hard one."""
+    import torch
+    import paper_2308_14711_amd as F
+    w = W.make_layer("soft_hard", 400, 128, 64, 4, 4, W.ACT_GELU, W.DTYPE_BF16, seed=22)
+    # harden: scale the node weights and biases by 2^10 (exact in bf16)
+    for k in ("node_w", "node_b"):
+        w.f32[k] = w.f32[k] * 1024.0
+        w.bits[k] = W.bf16_round(w.f32[k])
+    dev = to_device(w)
+    out = torch.full((w.T, w.O), float("nan"), dtype=torch.bfloat16, device="cuda")
+    F.fff_forward_soft(dev["x"], dev["node_w"], dev["node_b"], dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"],
+                       dev["leaf_b2"], w.depth, w.leaf_width, w.act, out)
+    hard = torch.empty_like(out)
+    F.fff_forward_hard(dev["x"], dev["node_w"], dev["node_b"], dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"],
+                       dev["leaf_b2"], w.depth, w.leaf_width, w.act, hard, None)
+    torch.cuda.synchronize()
+    ref_out, ref_mix = oracle.forward_soft(*oracle_inputs(w), w.depth, w.leaf_width, w.act)
+    got = out_to_f64(out)
+    err = np.abs(got - ref_out).max(axis=1) / np.maximum(np.abs(ref_out).max(axis=1), 1e-30)
+    assert err.max() <= TOL[W.DTYPE_BF16]
+    decided = ref_mix.max(axis=1) > 0.999999          # tokens whose every decision is saturated
+    assert decided.sum() > w.T // 2
+    h = out_to_f64(hard)
+    gap = np.abs(got[decided] - h[decided]).max(axis=1) / np.maximum(np.abs(h[decided]).max(axis=1), 1e-30)
+    assert gap.max() <= TOL[W.DTYPE_BF16]
