@@ -181,6 +181,63 @@ def depth_sweep(args, np, torch, W, F, with_moe=False):
         "sweep": rows}))
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+
+
+def soft_bench(args, np, torch, W, F):
+    """Forward_T of the chosen workload: every token against every leaf.  One step = one call of
+    fff_forward_soft (node scores, mixture weights, weighted hidden activations, output rows, per-node
+    entropies).  The roofline is the matrix cores': flops of the three contractions over time."""
+    import oracle
+    w = W.config(args.config, keep_f32=False)
+    assert w.dtype == W.DTYPE_BF16, "the soft pass runs on the bf16 matrix cores"
+    NL, NN = 1 << w.depth, (1 << w.depth) - 1
+    dev = {k: torch.from_numpy(np.ascontiguousarray(w.device_array(k)).view(np.int16)).cuda().view(torch.bfloat16)
+           for k in W.TENSORS}
+    out = torch.empty((w.T, w.O), dtype=torch.bfloat16, device="cuda")
+    mix = torch.empty((w.T, NL), dtype=torch.float32, device="cuda")
+    ent = torch.empty((max(NN, 1),), dtype=torch.float32, device="cuda")
+
+    def step():
+        F.fff_forward_soft(dev["x"], dev["node_w"] if w.depth else None, dev["node_b"] if w.depth else None,
+                           dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"], dev["leaf_b2"], w.depth, w.leaf_width,
+                           w.act, out, mix, ent if w.depth else None)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    K2 = (NL * (w.leaf_width + 1) + 7) // 8 * 8
+    flops = 2.0 * w.T * (w.D * NN + w.D * NL * w.leaf_width + K2 * w.O)
+    tflops = flops / (ms * 1e-3) / 1e12
+    # the oracle on a prefix of the batch: parity of those rows, and its rate
+    n = min(w.T, 1024)
+    ins = [np.ascontiguousarray(w.device_array(k)) for k in W.TENSORS]
+    ins[0] = np.ascontiguousarray(ins[0][:n])
+    t1 = time.perf_counter()
+    ref_out, ref_mix = oracle.forward_soft(*ins, w.depth, w.leaf_width, w.act)
+    cpu_s = time.perf_counter() - t1
+    got = out[:n].float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref_out).max(axis=1) / np.maximum(np.abs(ref_out).max(axis=1), 1e-30)
+    mix_err = float(np.abs(mix[:n].cpu().numpy().astype(np.float64) - ref_mix).max())
+    print(json.dumps({
+        "metric": "fff_soft_forward_tokens_per_s", "value": round(w.T / (ms * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s, soft pass over all %d leaves" % (w.name, w.note, NL), "T": w.T, "D": w.D,
+                   "O": w.O, "depth": w.depth, "leaf_width": w.leaf_width, "seed": 0},
+        "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "flops": flops},
+        "cpu_baseline": {"value": round(n / cpu_s, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+                         "kind": "oracle", "sample": "first %d tokens of %s, one pass of Forward_T, fp64" % (n, w.name),
+                         "seconds": round(cpu_s, 3)},
+        "parity": {"rows_checked": n, "max_rel_row_err": float(err.max()), "max_mixture_err": mix_err}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -196,6 +253,9 @@ def main():
                     help="depth: the small-batch latency sweep (time per call against tree depth) instead of a "
                          "workload; experts: the same sweep with the mixture-of-experts lookup (one engaged "
                          "expert) timed beside the tree lookup on the same leaves")
+    ap.add_argument("--soft", action="store_true",
+                    help="time the soft forward pass (Forward_T: all leaves, dense, MFMA-bound) of --config "
+                         "instead of the hard one")
     ap.add_argument("--sweep-batch", type=int, default=256)
     ap.add_argument("--sweep-leaf-width", type=int, default=32)
     ap.add_argument("--sweep-min-depth", type=int, default=1)
@@ -222,6 +282,10 @@ def main():
 
     if args.sweep in ("depth", "experts"):
         depth_sweep(args, np, torch, W, F, with_moe=args.sweep == "experts")
+        return
+
+    if args.soft:
+        soft_bench(args, np, torch, W, F)
         return
 
     w = W.config(args.config, keep_f32=False)

@@ -32,6 +32,10 @@ struct TileLds {
 
 // A: M rows of lda elements, B: N rows of ldb elements (row starts 16-byte aligned, K a multiple
 // of 8); rows past M / N and K past the end count as zeros.  All 256 threads of the block call it.
+// kDepth (2 or 4): chunks kept in flight in registers -- 4 for launches of few blocks, whose time is
+// one block's chain of memory round trips; 2 where many blocks share a CU and registers are
+// better spent on a third resident block.
+template <int kDepth>
 __device__ __forceinline__ void mfma_tile_64x128(const uint16_t* __restrict__ A, int64_t lda, int64_t M,
                                                  const uint16_t* __restrict__ B, int64_t ldb, int64_t N, int K,
                                                  int64_t m0, int64_t n0, TileLds& lds, f32x4_t (&acc)[4][2]) {
@@ -48,7 +52,7 @@ __device__ __forceinline__ void mfma_tile_64x128(const uint16_t* __restrict__ A,
     // Loads are unconditional with clamped addresses; rows past the end and K past D are zeroed
     // when the chunk goes to LDS.  (A predicated 16-byte load compiles to guarded dword loads with
     // a wait each, and a select right after the load makes the wave wait for it there.)
-    constexpr int kDepth = 4;
+    static_assert(kDepth == 2 || kDepth == 4, "two or four chunks in flight");
     const int pc = tid & 7;                      // this thread's piece of every row it loads
     const int64_t ta0 = m0 + (tid >> 3), ta1 = ta0 + 32;
     const int64_t eb0 = n0 + (tid >> 3), eb1 = eb0 + 32, eb2 = eb0 + 64, eb3 = eb0 + 96;
@@ -95,8 +99,10 @@ __device__ __forceinline__ void mfma_tile_64x128(const uint16_t* __restrict__ A,
     Chunk c0, c1, c2, c3;
     FFF_TILE_FETCH(0, c0);
     FFF_TILE_FETCH(1, c1);
-    FFF_TILE_FETCH(2, c2);
-    FFF_TILE_FETCH(3, c3);
+    if (kDepth == 4) {
+        FFF_TILE_FETCH(2, c2);
+        FFF_TILE_FETCH(3, c3);
+    }
     FFF_TILE_STASH(0, 0, c0);
     __syncthreads();
     // one chunk: refill the register slot the chunk came from, multiply out of LDS buffer BUF,
@@ -119,6 +125,11 @@ __device__ __forceinline__ void mfma_tile_64x128(const uint16_t* __restrict__ A,
         __syncthreads();                                                                                           \
     } while (0)
     for (int kc0 = 0; kc0 < n_chunks; kc0 += kDepth) {
+        if (kDepth == 2) {
+            FFF_TILE_STEP(kc0 + 0, 0, c0, c1);
+            FFF_TILE_STEP(kc0 + 1, 1, c1, c0);
+            continue;
+        }
         FFF_TILE_STEP(kc0 + 0, 0, c0, c1);
         FFF_TILE_STEP(kc0 + 1, 1, c1, c2);
         FFF_TILE_STEP(kc0 + 2, 0, c2, c3);
@@ -128,6 +139,40 @@ __device__ __forceinline__ void mfma_tile_64x128(const uint16_t* __restrict__ A,
 #undef FFF_TILE_STASH
 #undef FFF_TILE_FETCH
 
+}
+
+// Epilogue: the block's 64 x 128 results as bf16, staged through LDS (the first 16 KB of the tile
+// buffers, free once mfma_tile_64x128 has returned) so that they leave as 16-byte pieces, 16
+// consecutive threads on one row.  value(r, c, v) maps row r, column c of the tile and the
+// accumulated v to the number stored; rows past M and columns past N are dropped.
+template <typename Value>
+__device__ __forceinline__ void tile_store_bf16(TileLds& lds, const f32x4_t (&acc)[4][2], uint16_t* __restrict__ C,
+                                                int64_t ldc, int64_t M, int64_t N, int64_t m0, int64_t n0,
+                                                Value value) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int j = lane & 15, kg = lane >> 4;
+    uint16_t* st = (uint16_t*)lds.a;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r = 16 * mt + 4 * kg + q, c = 32 * wv + 16 * nt + j;
+                st[r * kTileN + c] = f32_to_bf16(value(r, c, acc[mt][nt][q]));
+            }
+    __syncthreads();
+    const bool vec = (ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(C) & 15u) == 0;
+    for (int idx = tid; idx < kTileM * (kTileN / 8); idx += 256) {
+        const int r = idx >> 4, pc = idx & 15;
+        const int64_t t = m0 + r, n = n0 + 8 * pc;
+        if (t >= M || n >= N) continue;
+        if (vec && n + 8 <= N) {
+            *(uint4*)(C + t * ldc + n) = *(const uint4*)(st + r * kTileN + 8 * pc);
+        } else {
+            for (int e = 0; e < 8 && n + e < N; ++e) C[t * ldc + n + e] = st[r * kTileN + 8 * pc + e];
+        }
+    }
 }
 
 }  // namespace fff

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
         bias[nt] = !ok ? ninf : (a.gate_b ? bf16_to_f32(a.gate_b[e]) : 0.0f);
     }
 
-    mfma_tile_64x128(a.x, D, a.T, a.gate_w, D, a.G, D, t0, e0, tile, acc);
+    mfma_tile_64x128<4>(a.x, D, a.T, a.gate_w, D, a.G, D, t0, e0, tile, acc);
 
     // lane (j, kg) of tile (mt, nt) holds tokens 16 mt + 4 kg + q (q = 0..3) against expert
     // e0 + 32 wv + 16 nt + j: bias, then the best expert per token over the wave's 32

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void soft_nodes_kernel(const SoftArgs a) {
     const int64_t ncb = (a.NN + kTileN - 1) / kTileN;
     const int64_t t0 = tile_row0(ncb), n0 = tile_col0(ncb);
     f32x4_t acc[4][2];
-    mfma_tile_64x128(a.x, a.D, a.T, a.node_w, a.D, a.NN, a.D, t0, n0, tile, acc);
+    mfma_tile_64x128<2>(a.x, a.D, a.T, a.node_w, a.D, a.NN, a.D, t0, n0, tile, acc);
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const int64_t n = n0 + 32 * wv + 16 * nt + j;
@@ -92,21 +92,30 @@ __global__ __launch_bounds__(256) void soft_hidden_kernel(const SoftArgs a) {
     const int64_t ncb = (NH + kTileN - 1) / kTileN;
     const int64_t t0 = tile_row0(ncb), n0 = tile_col0(ncb);
     f32x4_t acc[4][2];
-    mfma_tile_64x128(a.x, a.D, a.T, a.w1, a.D, NH, a.D, t0, n0, tile, acc);
+    mfma_tile_64x128<2>(a.x, a.D, a.T, a.w1, a.D, NH, a.D, t0, n0, tile, acc);
+    // the mixture weights this tile needs (64 tokens x the leaves of its 128 columns, at most 128)
+    // go through the second tile buffer, read along a row of the weights
+    float* mixt = (float*)tile.b;
+    const int64_t last = n0 + kTileN - 1 < NH - 1 ? n0 + kTileN - 1 : NH - 1;
+    const int64_t leaf_lo = n0 / a.L;
+    const int n_leaf = (int)(last / a.L - leaf_lo + 1);
+    for (int idx = threadIdx.x; idx < kTileM * n_leaf; idx += 256) {
+        const int r = idx / n_leaf, c = idx % n_leaf;
+        mixt[idx] = t0 + r < a.T ? a.mix[(t0 + r) * a.NL + leaf_lo + c] : 0.0f;
+    }
+    float bias[2];
+    int lcol[2];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const int64_t n = n0 + 32 * wv + 16 * nt + j;
-        if (n >= NH) continue;
-        const float b = bf16_to_f32(a.b1[n]);
-        const int64_t leaf = n / a.L;
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t t = t0 + 16 * mt + 4 * kg + q;
-                if (t < a.T) a.hid[t * a.K2 + n] = f32_to_bf16(activate(acc[mt][nt][q] + b, a.act) * a.mix[t * a.NL + leaf]);
-            }
+        bias[nt] = n < NH ? bf16_to_f32(a.b1[n]) : 0.0f;
+        lcol[nt] = n < NH ? (int)(n / a.L - leaf_lo) : 0;
     }
+    __syncthreads();
+    tile_store_bf16(tile, acc, a.hid, a.K2, a.T, NH, t0, n0, [&](int r, int c, float v) {
+        const int nt = (c >> 4) & 1;
+        return activate(v + bias[nt], a.act) * mixt[r * n_leaf + lcol[nt]];
+    });
 }
 
 // W2x[o][k] = W2[k][o] for k < NL * L, b2[k - NL * L][o] for the next NL, zeros up to K2.
@@ -140,41 +149,39 @@ __global__ __launch_bounds__(256) void soft_out_kernel(const SoftArgs a) {
     const int64_t ncb = ((int64_t)a.O + kTileN - 1) / kTileN;
     const int64_t t0 = tile_row0(ncb), n0 = tile_col0(ncb);
     f32x4_t acc[4][2];
-    mfma_tile_64x128(a.hid, a.K2, a.T, a.w2x, a.K2, a.O, (int)a.K2, t0, n0, tile, acc);
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int64_t o = n0 + 32 * wv + 16 * nt + j;
-        if (o >= a.O) continue;
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t t = t0 + 16 * mt + 4 * kg + q;
-                if (t < a.T) a.out[t * a.O + o] = f32_to_bf16(acc[mt][nt][q]);
-            }
+    mfma_tile_64x128<2>(a.hid, a.K2, a.T, a.w2x, a.K2, a.O, (int)a.K2, t0, n0, tile, acc);
+    tile_store_bf16(tile, acc, a.out, a.O, a.T, a.O, t0, n0, [](int, int, float v) { return v; });
+}
+
+// batch mean of the Bernoulli entropy of every node's choice score, in two passes with a fixed
+// order of additions (so the result does not depend on scheduling): a block sums kEntTokens
+// tokens for every node (thread = node, so the reads run along a row of scores), then one thread
+// per node adds the blocks' partial sums in block order.
+constexpr int kEntTokens = 256;
+
+__global__ __launch_bounds__(256) void soft_entropy_part_kernel(const float* __restrict__ choice, int64_t T, int64_t NN,
+                                                                float* __restrict__ part) {
+    const int64_t t0 = (int64_t)blockIdx.x * kEntTokens;
+    const int64_t t1 = t0 + kEntTokens < T ? t0 + kEntTokens : T;
+    for (int64_t n = threadIdx.x; n < NN; n += 256) {
+        float s = 0.0f;
+        for (int64_t t = t0; t < t1; ++t) {
+            const float c = choice[t * NN + n];
+            const float h0 = c > 0.0f ? -c * __logf(c) : 0.0f;
+            const float h1 = c < 1.0f ? -(1.0f - c) * __logf(1.0f - c) : 0.0f;
+            s += h0 + h1;
+        }
+        part[(int64_t)blockIdx.x * NN + n] = s;
     }
 }
 
-// batch mean of the Bernoulli entropy of every node's choice score: one block per node, a fixed
-// order of additions (so the result does not depend on scheduling)
-__global__ __launch_bounds__(256) void soft_entropy_kernel(const float* __restrict__ choice, int64_t T, int64_t NN,
-                                                           float* __restrict__ entropy) {
-    __shared__ float part[256];
-    const int64_t n = blockIdx.x;
+__global__ __launch_bounds__(256) void soft_entropy_sum_kernel(const float* __restrict__ part, int64_t n_parts, int64_t T,
+                                                               int64_t NN, float* __restrict__ entropy) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= NN) return;
     float s = 0.0f;
-    for (int64_t t = threadIdx.x; t < T; t += 256) {
-        const float c = choice[t * NN + n];
-        const float h0 = c > 0.0f ? -c * __logf(c) : 0.0f;
-        const float h1 = c < 1.0f ? -(1.0f - c) * __logf(1.0f - c) : 0.0f;
-        s += h0 + h1;
-    }
-    part[threadIdx.x] = s;
-    __syncthreads();
-    for (int d = 128; d > 0; d >>= 1) {
-        if ((int)threadIdx.x < d) part[threadIdx.x] += part[threadIdx.x + d];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) entropy[n] = part[0] / (float)T;
+    for (int64_t b = 0; b < n_parts; ++b) s += part[b * NN + n];
+    entropy[n] = s / (float)T;
 }
 
 }  // namespace
@@ -194,7 +201,8 @@ static int64_t soft_k2(const Problem& p) {
 int64_t soft_scratch_words(const Problem& p) {
     const int64_t NL = (int64_t)1 << p.depth, NN = NL - 1, K2 = soft_k2(p);
     auto up = [](int64_t w) { return (w + 63) / 64 * 64; };
-    return up(p.T * (NN > 0 ? NN : 1)) + up(p.T * NL) + up((p.T * K2 + 1) / 2) + up((p.O * K2 + 1) / 2);
+    return up(p.T * (NN > 0 ? NN : 1)) + up(p.T * NL) + up((p.T * K2 + 1) / 2) + up((p.O * K2 + 1) / 2) +
+           up((p.T + kEntTokens - 1) / kEntTokens * (NN > 0 ? NN : 1));
 }
 
 // mix (optional, [T, 2^d] fp32) and entropy (optional, [2^d - 1] fp32) are caller buffers
@@ -228,6 +236,8 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
     a.hid = (uint16_t*)w;
     w += up((p.T * a.K2 + 1) / 2);
     a.w2x = (uint16_t*)w;
+    w += up((p.O * a.K2 + 1) / 2);
+    float* ent_part = (float*)w;
     const int64_t mb = (p.T + kTileM - 1) / kTileM;
     hipError_t e;
     if (a.NN > 0) {
@@ -243,7 +253,11 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
     soft_out_kernel<<<dim3((unsigned)(mb * ((p.O + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (entropy_out && a.NN > 0) {
-        soft_entropy_kernel<<<dim3((unsigned)a.NN), dim3(256), 0, s>>>(a.choice, p.T, a.NN, entropy_out);
+        const int64_t n_parts = (p.T + kEntTokens - 1) / kEntTokens;
+        soft_entropy_part_kernel<<<dim3((unsigned)n_parts), dim3(256), 0, s>>>(a.choice, p.T, a.NN, ent_part);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        soft_entropy_sum_kernel<<<dim3((unsigned)((a.NN + 255) / 256)), dim3(256), 0, s>>>(ent_part, n_parts, p.T, a.NN,
+                                                                                         entropy_out);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;
