@@ -155,9 +155,9 @@ __global__ __launch_bounds__(256) void soft_out_kernel(const SoftArgs a) {
 
 // batch mean of the Bernoulli entropy of every node's choice score, in two passes with a fixed
 // order of additions (so the result does not depend on scheduling): a block sums kEntTokens
-// tokens for every node (thread = node, so the reads run along a row of scores), then one thread
-// per node adds the blocks' partial sums in block order.
-constexpr int kEntTokens = 256;
+// tokens for every node (thread = node, so the reads run along a row of scores), then one block
+// per node adds the partial sums (strided over its threads, then a fixed tree).
+constexpr int kEntTokens = 32;
 
 __global__ __launch_bounds__(256) void soft_entropy_part_kernel(const float* __restrict__ choice, int64_t T, int64_t NN,
                                                                 float* __restrict__ part) {
@@ -177,11 +177,17 @@ __global__ __launch_bounds__(256) void soft_entropy_part_kernel(const float* __r
 
 __global__ __launch_bounds__(256) void soft_entropy_sum_kernel(const float* __restrict__ part, int64_t n_parts, int64_t T,
                                                                int64_t NN, float* __restrict__ entropy) {
-    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (n >= NN) return;
+    __shared__ float red[256];
+    const int64_t n = blockIdx.x;       // one block per node: strided partial sums, then a fixed tree
     float s = 0.0f;
-    for (int64_t b = 0; b < n_parts; ++b) s += part[b * NN + n];
-    entropy[n] = s / (float)T;
+    for (int64_t b = threadIdx.x; b < n_parts; b += 256) s += part[b * NN + n];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int d = 128; d > 0; d >>= 1) {
+        if ((int)threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) entropy[n] = red[0] / (float)T;
 }
 
 }  // namespace
@@ -256,8 +262,7 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
         const int64_t n_parts = (p.T + kEntTokens - 1) / kEntTokens;
         soft_entropy_part_kernel<<<dim3((unsigned)n_parts), dim3(256), 0, s>>>(a.choice, p.T, a.NN, ent_part);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        soft_entropy_sum_kernel<<<dim3((unsigned)((a.NN + 255) / 256)), dim3(256), 0, s>>>(ent_part, n_parts, p.T, a.NN,
-                                                                                         entropy_out);
+        soft_entropy_sum_kernel<<<dim3((unsigned)a.NN), dim3(256), 0, s>>>(ent_part, n_parts, p.T, a.NN, entropy_out);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;
