@@ -10,8 +10,14 @@ resident in HBM.  Prints ONE JSON line.
 Beside the headline tokens/s the line carries: the roofline position of the
 dominant kernel (algorithmic bytes per launch / its average duration measured
 with HIP events recorded on the call's stream inside the library), the same
-for every stage and for the whole path, the CPU oracle timed on this host, and
-an equal-training-width dense feedforward on the same GPU for the speedup.
+for every stage and for the whole path, the spread of the timing, the CPU
+oracle timed on this host (all cores, and one core), and an
+equal-training-width dense feedforward on the same GPU for the speedup.
+
+Other modes, each printing one JSON line of its own:
+    --sweep depth     small-batch latency against tree depth (the paper's speed experiment)
+    --sweep experts   the same with the mixture-of-experts lookup (one engaged expert) beside it
+    --soft            the soft pass (Forward_T, all leaves) of --config, against the MFMA roofline
 """
 import argparse
 import json

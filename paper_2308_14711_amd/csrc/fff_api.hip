@@ -530,6 +530,6 @@ const char* fff_status_string(int status) {
 
 const char* fff_last_device_error(void) { return g_last_error.c_str(); }
 
-int fff_version(void) { return 100; }
+int fff_version(void) { return 200; }
 
 }  // extern "C"

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void soft_mix_kernel(const SoftArgs a) {
 // hidden: act(x . W1 + b1) scaled by the mixture weight of the neuron's leaf
 __global__ __launch_bounds__(256) void soft_hidden_kernel(const SoftArgs a) {
     __shared__ TileLds tile;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15, kg = lane >> 4;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15;
     const int64_t NH = a.NL * a.L;
     const int64_t ncb = (NH + kTileN - 1) / kTileN;
     const int64_t t0 = tile_row0(ncb), n0 = tile_col0(ncb);
@@ -145,7 +145,6 @@ __global__ __launch_bounds__(256) void soft_w2x_kernel(const SoftArgs a) {
 // out: the weighted leaf outputs and biases in one contraction over K2
 __global__ __launch_bounds__(256) void soft_out_kernel(const SoftArgs a) {
     __shared__ TileLds tile;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15, kg = lane >> 4;
     const int64_t ncb = ((int64_t)a.O + kTileN - 1) / kTileN;
     const int64_t t0 = tile_row0(ncb), n0 = tile_col0(ncb);
     f32x4_t acc[4][2];
