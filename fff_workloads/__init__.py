@@ -32,6 +32,7 @@ DTYPE_BF16 = 1
 _TAGS = {
     "x": 1, "node_w": 2, "node_b": 3, "leaf_w1": 4, "leaf_b1": 5,
     "leaf_w2": 6, "leaf_b2": 7, "perm": 8, "gate_w": 9, "gate_b": 10,
+    "node_w1": 11, "node_b1": 12, "node_w2": 13, "node_b2": 14, "ln_gamma": 15, "ln_beta": 16,
 }
 
 
@@ -267,6 +268,31 @@ def moe_gate(n_experts: int, D: int, dtype: int, seed: int = 0):
     bf = dtype == DTYPE_BF16
     return (_uniform(seed, "gate_w", (n_experts, D), bD, as_bf16_bits=bf),
             _uniform(seed, "gate_b", (n_experts,), bD, as_bf16_bits=bf))
+
+
+def wide_nodes(depth: int, node_size: int, D: int, dtype: int, seed: int = 0):
+    """Node networks of `node_size` hidden neurons for a tree of the given depth (the <D, n, 1>
+    networks of the Definition, heap order): node_w1 [NN, n, D] and node_b1 [NN, n] drawn
+    U(-1/sqrt(D), 1/sqrt(D)), node_w2 [NN, n] U(-1/sqrt(n), 1/sqrt(n)), node_b2 [NN] a tenth of
+    that (small, so that the tokens spread over the leaves).  Returns the arrays whose bytes are
+    uploaded (uint16 bf16 bits or fp32)."""
+    NN = (1 << depth) - 1
+    bD, bn = 1.0 / np.sqrt(D), 1.0 / np.sqrt(node_size)
+    bf = dtype == DTYPE_BF16
+    return (_uniform(seed, "node_w1", (NN, node_size, D), bD, as_bf16_bits=bf),
+            _uniform(seed, "node_b1", (NN, node_size), bD, as_bf16_bits=bf),
+            _uniform(seed, "node_w2", (NN, node_size), bn, as_bf16_bits=bf),
+            _uniform(seed, "node_b2", (NN,), 0.1 * bn, as_bf16_bits=bf))
+
+
+def layer_norm_params(D: int, dtype: int, seed: int = 0):
+    """Scale and shift of a layer normalisation over D features: gamma U(0.75, 1.25), beta
+    U(-0.1, 0.1).  Returns the arrays whose bytes are uploaded."""
+    g = _uniform(seed, "ln_gamma", (D,), 0.25) + np.float32(1.0)
+    b = _uniform(seed, "ln_beta", (D,), 0.1)
+    if dtype == DTYPE_BF16:
+        return bf16_round(g), bf16_round(b)
+    return g, b
 
 
 CONFIG_NAMES = ("C1", "C2", "C2c", "C3", "C4", "C5")

@@ -54,6 +54,8 @@ def _load():
         _lib.fff_oracle_bucket.argtypes = [vp, i64, i32, vp, vp, vp]
         _lib.fff_oracle_node_entropy.argtypes = [vp, vp, vp, i32, i64, i64, i32, vp]
         _lib.fff_oracle_moe_top1.argtypes = [vp] * 7 + [i64, i32, i32, i64, i64, i64, i32, vp, vp, vp]
+        _lib.fff_oracle_forward_block.argtypes = ([vp] * 3 + [f64] + [vp] * 8 + [i32] * 6 + [i64] * 3 +
+                                                  [i32, vp, vp, vp])
         _lib.fff_oracle_set_threads.argtypes = [i32]
         _lib.fff_oracle_set_threads.restype = None
         for n in ("training_size", "inference_size"):
@@ -185,6 +187,43 @@ def moe_top1(x, gate_w, gate_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, leaf_width, 
                                      _p(leaf_b2), G, leaf_width, act, T, D, O, dt, _p(out), _p(idx), _p(margin))
     if rc:
         raise ValueError("fff_oracle_moe_top1: bad arguments (%d)" % rc)
+    return out, idx, margin
+
+
+def forward_block(x, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2, leaf_w1, leaf_b1,
+                  leaf_w2, leaf_b2, depth, node_size, leaf_width, act, residual: bool,
+                  want_out: bool = True) -> Tuple[Optional[np.ndarray], np.ndarray, np.ndarray]:
+    """Forward_I with nodes of `node_size` hidden neurons, on the layer-normalised input when
+    ln_gamma/ln_beta are given (None, None: no normalisation), plus x when `residual`.
+    node_w1 [NN, n, D], node_b1 [NN, n], node_w2 [NN, n], node_b2 [NN].
+    Returns (out [T,O] fp64 or None, leaf_idx [T] int32, margin [T] fp64)."""
+    x, leaf_w1, leaf_b1, leaf_w2, leaf_b2 = map(_c, (x, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    T, D, O = _shapes(x, leaf_w1, leaf_w2, depth, leaf_width)
+    NN = (1 << depth) - 1
+    if depth == 0:
+        node_w1 = np.zeros((0, node_size, D), x.dtype)
+        node_b1 = np.zeros((0, node_size), x.dtype)
+        node_w2 = np.zeros((0, node_size), x.dtype)
+        node_b2 = np.zeros((0,), x.dtype)
+    node_w1, node_b1, node_w2, node_b2 = map(_c, (node_w1, node_b1, node_w2, node_b2))
+    assert node_w1.shape == (NN, node_size, D) and node_b1.shape == (NN, node_size)
+    assert node_w2.shape == (NN, node_size) and node_b2.shape == (NN,)
+    assert leaf_b1.shape == (1 << depth, leaf_width) and leaf_b2.shape == (1 << depth, O)
+    norm = ln_gamma is not None
+    assert norm == (ln_beta is not None)
+    ln_gamma, ln_beta = _c(ln_gamma), _c(ln_beta)
+    if norm:
+        assert ln_gamma.shape == (D,) and ln_beta.shape == (D,)
+    dt = _dtype_code((x, ln_gamma, ln_beta, node_w1, node_b1, node_w2, node_b2, leaf_w1, leaf_b1, leaf_w2, leaf_b2))
+    out = np.empty((T, O), np.float64) if want_out else None
+    idx = np.empty((T,), np.int32)
+    margin = np.empty((T,), np.float64)
+    rc = _load().fff_oracle_forward_block(_p(x), _p(ln_gamma), _p(ln_beta), float(ln_eps), _p(node_w1),
+                                          _p(node_b1), _p(node_w2), _p(node_b2), _p(leaf_w1), _p(leaf_b1),
+                                          _p(leaf_w2), _p(leaf_b2), depth, node_size, leaf_width, act,
+                                          int(norm), int(bool(residual)), T, D, O, dt, _p(out), _p(idx), _p(margin))
+    if rc:
+        raise ValueError("fff_oracle_forward_block: bad arguments (%d)" % rc)
     return out, idx, margin
 
 

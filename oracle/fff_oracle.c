@@ -22,6 +22,9 @@
  *                            noiseless gating (section "Inference speed
  *                            comparison"): argmax of the gating logits, then
  *                            that expert's feedforward output.
+ *   fff_oracle_forward_block Forward_I for nodes of size n >= 1 (the Definition's
+ *                            <D, n, 1> node networks), with the layer normalised
+ *                            input and the residual sum of a transformer block.
  *   fff_oracle_bucket        per-leaf token lists (count, exclusive offsets,
  *                            stable order).  Not in the paper; it is the plain
  *                            definition of what the bucketing stage produces.
@@ -30,7 +33,9 @@
  *
  * Readings of the paper used here (the paper leaves these open):
  *   - node size n = 1 (the paper uses n = 1 in all its experiments): a node is
- *     one neuron, logit = w . x + b, output c = sigmoid(logit).  c >= 1/2 is
+ *     one neuron, logit = w . x + b, output c = sigmoid(logit) (the multiply-
+ *     accumulate and compare of paragraph "Inference complexity"); nodes with a
+ *     hidden layer of n neurons are fff_oracle_forward_block's.  c >= 1/2 is
  *     decided as logit >= 0, which is the same predicate without the rounding
  *     of a floating-point sigmoid (the paper's implementation note also
  *     compares the logit to 0).
@@ -54,7 +59,10 @@
  * invariance, a hand-worked two-token example; for the mixture of experts:
  * one-hot gating rows (argmax by scalar compares), a depth-1 FFF written as two
  * experts, identical experts, a library argmax on tiny inputs, expert
- * permutation, the tie and NaN rules.  Numeric output values of a forward
+ * permutation, the tie and NaN rules; for the block: a two-neuron node that
+ * reduces to the linear one, a library layer normalisation, shift and scale
+ * invariance, dead hidden neurons routed by the output bias alone, neuron
+ * permutation, the residual difference, a hand-worked example.  Numeric output values of a forward
  * pass are not printed anywhere in the paper.
  */
 #include <math.h>
@@ -324,6 +332,123 @@ int fff_oracle_moe_top1(const void *x, const void *gate_w, const void *gate_b, c
             margin[t] = (n_experts < 2 || !(second > -INFINITY)) ? INFINITY : (sc > 0.0 ? (best - second) / sc : 0.0);
         }
         if (out) leaf_eval(x, t * D, leaf_w1, leaf_b1, leaf_w2, leaf_b2, arg, leaf_width, act, D, O, dtype, h, out + t * O);
+        free(h);
+    }
+    return err;
+}
+
+/*
+ * Forward_I for nodes of size n >= 1, inside a pre-norm residual block.
+ *
+ * The Definition makes a node a <D, n, 1> feedforward network with a sigmoid on
+ * its output: n hidden neurons (input weights u_j, bias a_j, the activation),
+ * one output weight v_j each and an output bias c,
+ *     logit = c + sum_j v_j * act(u_j . z + a_j),   node output = sigmoid(logit),
+ * and Forward_I goes to child 2i+1 when that output is >= 1/2 (logit >= 0).
+ * node_w1 [NN, n, D], node_b1 [NN, n], node_w2 [NN, n], node_b2 [NN], heap order.
+ *
+ * In a transformer (section "Fast feedforward layers as building blocks") the
+ * layer stands where the feedforward layer stands: z = LayerNorm(x) feeds both
+ * the nodes and the leaf, and the block returns x + FFF(z).  The paper does not
+ * spell the block out; this is the standard pre-norm arrangement:
+ *     mean = sum_j x_j / D,  var = sum_j (x_j - mean)^2 / D   (divisor D),
+ *     z_j = (x_j - mean) / sqrt(var + eps) * gamma_j + beta_j.
+ * norm = 0 skips the normalisation (z = x); residual = 0 returns FFF(z) alone
+ * (residual = 1 needs O == D).
+ *
+ * margin [T] (optional): smallest |logit| / (|c| + sum_j |v_j| (sum |terms of
+ * u_j . z| + |a_j|)) over the path, as for fff_oracle_forward_hard.
+ */
+static void layer_norm(const void *x, int64_t xoff, const void *gamma, const void *beta, double eps,
+                       int64_t D, int dtype, double *z) {
+    double mean = 0.0, var = 0.0;
+    for (int64_t j = 0; j < D; ++j) mean += ld(x, xoff + j, dtype);
+    mean /= (double)D;
+    for (int64_t j = 0; j < D; ++j) {
+        const double c = ld(x, xoff + j, dtype) - mean;
+        var += c * c;
+    }
+    var /= (double)D;
+    for (int64_t j = 0; j < D; ++j)
+        z[j] = (ld(x, xoff + j, dtype) - mean) / sqrt(var + eps) * ld(gamma, j, dtype) + ld(beta, j, dtype);
+}
+
+static double wide_node_logit(const double *z, const void *w1, const void *b1, const void *w2,
+                              const void *b2, int64_t row, int n, int act, int64_t D, int dtype,
+                              double *scale) {
+    double logit = ld(b2, row, dtype);
+    double sc = fabs(logit);
+    for (int j = 0; j < n; ++j) {
+        const int64_t neuron = row * n + j;
+        double s = 0.0, a = 0.0;
+        for (int64_t k = 0; k < D; ++k) {
+            const double t = ld(w1, neuron * D + k, dtype) * z[k];
+            s += t;
+            a += fabs(t);
+        }
+        const double bias = ld(b1, neuron, dtype);
+        const double v = ld(w2, neuron, dtype);
+        logit += v * activation(s + bias, act);
+        sc += fabs(v) * (a + fabs(bias));
+    }
+    *scale = sc;
+    return logit;
+}
+
+/* y[0..O) = leaf N_{d,k}(z) for an input vector already in fp64 */
+static void leaf_eval_vec(const double *z, const void *w1, const void *b1, const void *w2,
+                          const void *b2, int64_t k, int L, int act, int64_t D, int64_t O, int dtype,
+                          double *h, double *y) {
+    for (int r = 0; r < L; ++r) {
+        double s = 0.0;
+        for (int64_t j = 0; j < D; ++j) s += ld(w1, (k * L + r) * D + j, dtype) * z[j];
+        h[r] = activation(s + ld(b1, k * L + r, dtype), act);
+    }
+    for (int64_t o = 0; o < O; ++o) {
+        double s = 0.0;
+        for (int r = 0; r < L; ++r) s += h[r] * ld(w2, (k * L + r) * O + o, dtype);
+        y[o] = s + ld(b2, k * O + o, dtype);
+    }
+}
+
+int fff_oracle_forward_block(const void *x, const void *ln_gamma, const void *ln_beta, double ln_eps,
+                             const void *node_w1, const void *node_b1, const void *node_w2,
+                             const void *node_b2, const void *leaf_w1, const void *leaf_b1,
+                             const void *leaf_w2, const void *leaf_b2, int depth, int node_size,
+                             int leaf_width, int act, int norm, int residual, int64_t T, int64_t D,
+                             int64_t O, int dtype, double *out, int32_t *leaf_idx, double *margin) {
+    if (!args_ok(depth, leaf_width, act, T, D, O, dtype) || node_size < 1 || (residual && O != D) ||
+        (norm && !(ln_eps >= 0.0)))
+        return 1;
+    int err = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 16)
+#endif
+    for (int64_t t = 0; t < T; ++t) {
+        double *z = (double *)malloc(sizeof(double) * (size_t)D);
+        double *h = (double *)malloc(sizeof(double) * (size_t)leaf_width);
+        if (!z || !h) { err = 2; free(z); free(h); continue; }
+        if (norm) layer_norm(x, t * D, ln_gamma, ln_beta, ln_eps, D, dtype, z);
+        else for (int64_t j = 0; j < D; ++j) z[j] = ld(x, t * D + j, dtype);
+        int64_t n = 0;
+        double mg = INFINITY;
+        for (int m = 0; m < depth; ++m) {
+            double scale;
+            const int64_t row = (((int64_t)1 << m) - 1) + n;
+            const double logit = wide_node_logit(z, node_w1, node_b1, node_w2, node_b2, row, node_size,
+                                                 act, D, dtype, &scale);
+            const double rel = scale > 0.0 ? fabs(logit) / scale : 0.0;
+            if (rel < mg) mg = rel;
+            n = logit >= 0.0 ? 2 * n + 1 : 2 * n;
+        }
+        if (leaf_idx) leaf_idx[t] = (int32_t)n;
+        if (margin) margin[t] = mg;
+        if (out) {
+            leaf_eval_vec(z, leaf_w1, leaf_b1, leaf_w2, leaf_b2, n, leaf_width, act, D, O, dtype, h, out + t * O);
+            if (residual)
+                for (int64_t o = 0; o < O; ++o) out[t * O + o] += ld(x, t * D + o, dtype);
+        }
+        free(z);
         free(h);
     }
     return err;

@@ -9,6 +9,7 @@ import pytest
 import oracle
 import test_oracle_pins as pins
 import test_oracle_moe_pins as moe_pins
+import test_oracle_block_pins as block_pins
 
 SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "fff_oracle.c")
 
@@ -44,6 +45,21 @@ MUTATIONS = [
     ("entropy_one_sided", "sum += h0 + h1;\n            }\n            entropy[", "sum += h0;\n            }\n            entropy["),
     ("entropy_not_a_mean", "entropy[(((int64_t)1 << m) - 1) + n] = T > 0 ? sum / (double)T : 0.0;", "entropy[(((int64_t)1 << m) - 1) + n] = sum;"),
     ("entropy_level_order", "entropy[(((int64_t)1 << m) - 1) + n] =", "entropy[(((int64_t)1 << m) - 1) + (((int64_t)1 << m) - 1 - n)] ="),
+    ("block_variance_unbiased", "var /= (double)D;", "var /= (double)(D - 1);"),
+    ("block_mean_not_subtracted", "z[j] = (ld(x, xoff + j, dtype) - mean) / sqrt(var + eps)", "z[j] = ld(x, xoff + j, dtype) / sqrt(var + eps)"),
+    ("block_eps_outside_root", "/ sqrt(var + eps) * ld(gamma, j, dtype)", "/ (sqrt(var) + eps) * ld(gamma, j, dtype)"),
+    ("block_gamma_beta_swapped", "* ld(gamma, j, dtype) + ld(beta, j, dtype);", "* ld(beta, j, dtype) + ld(gamma, j, dtype);"),
+    ("block_node_output_bias_dropped", "double logit = ld(b2, row, dtype);\n    double sc", "double logit = 0.0 * ld(b2, row, dtype);\n    double sc"),
+    ("block_node_hidden_bias_dropped", "logit += v * activation(s + bias, act);", "logit += v * activation(s, act);"),
+    ("block_node_not_activated", "logit += v * activation(s + bias, act);", "logit += v * (s + bias);"),
+    ("block_node_output_weight_index", "const double v = ld(w2, neuron, dtype);", "const double v = ld(w2, row * n, dtype);"),
+    ("block_node_neuron_stride", "const int64_t neuron = row * n + j;", "const int64_t neuron = row + j;"),
+    ("block_children_swapped", "n = logit >= 0.0 ? 2 * n + 1 : 2 * n;", "n = logit >= 0.0 ? 2 * n : 2 * n + 1;"),
+    ("block_strict_tie", "n = logit >= 0.0 ? 2 * n + 1 : 2 * n;", "n = logit > 0.0 ? 2 * n + 1 : 2 * n;"),
+    ("block_residual_dropped", "out[t * O + o] += ld(x, t * D + o, dtype);", "out[t * O + o] += 0.0;"),
+    ("block_residual_normalised", "out[t * O + o] += ld(x, t * D + o, dtype);", "out[t * O + o] += z[o];"),
+    ("block_leaf_reads_raw_input", "leaf_eval_vec(z, leaf_w1,", "leaf_eval(x, t * D, leaf_w1,"),
+    ("block_margin_scale_without_weight", "sc += fabs(v) * (a + fabs(bias));", "sc += (a + fabs(bias));"),
     ("bf16_widen_shift", "uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 16;", "uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 15;"),
 ]
 
@@ -71,6 +87,16 @@ PINS = [
     moe_pins.test_moe_expert_permutation_permutes_the_indices_only,
     moe_pins.test_moe_ties_take_the_lowest_index_and_nan_never_wins,
     moe_pins.test_moe_bf16_bits_are_widened_exactly,
+    block_pins.test_block_hand_worked_example,
+    block_pins.test_two_relu_neurons_make_the_linear_node,
+    block_pins.test_block_against_library_layer_norm_and_products,
+    block_pins.test_layer_norm_is_numpy_standardisation_then_affine,
+    block_pins.test_shift_and_scale_of_the_input_do_not_matter_under_layer_norm,
+    block_pins.test_residual_adds_the_unnormalised_input,
+    block_pins.test_dead_hidden_neurons_leave_the_output_bias_to_decide,
+    block_pins.test_permuting_a_nodes_hidden_neurons_changes_nothing,
+    block_pins.test_single_hidden_neuron_and_output_weight_by_scalar_arithmetic,
+    block_pins.test_depth_zero_block_is_norm_ff_residual,
 ]
 
 
