@@ -175,6 +175,38 @@ int fff_forward_soft(const void* x, const void* node_w, const void* node_b,
                      void* out, float* mix, float* entropy, void* stream,
                      int64_t T, int64_t D, int64_t O, int dtype);
 
+/*
+ * fff_forward_block: Forward_I (Algorithm 1) for nodes of size n >= 1, as a
+ * pre-norm residual transformer layer.  The Definition makes a node a
+ * <D, n, 1> feedforward network with a sigmoid on its output:
+ *     logit = node_b2[i] + sum_j node_w2[i][j] * act(node_w1[i][j] . z + node_b1[i][j]),
+ * and the walk goes to child 2i+2 when logit >= 0 (node output >= 1/2), else
+ * to 2i+1; the leaf reached is evaluated on z as in fff_forward_hard.  Standing
+ * in a transformer (section "Fast feedforward layers as building blocks") the
+ * network reads the layer-normalised token and the block adds the token back:
+ *     z = (x - mean) / sqrt(var + ln_eps) * ln_gamma + ln_beta   (var with divisor D),
+ *     out = FFF(z) + x.
+ * z is kept in fp32 registers: it is never rounded to `dtype` nor stored.
+ *   ln_gamma, ln_beta  device, [D], or both NULL: no normalisation (z = x)
+ *   ln_eps             >= 0
+ *   node_w1 [2^depth - 1, node_size, D], node_b1 and node_w2 [2^depth - 1,
+ *   node_size], node_b2 [2^depth - 1], heap order, `act` also on the node's
+ *   hidden neurons; may be NULL when depth == 0
+ *   residual           non-zero adds x (needs O == D, else FFF_ERR_SHAPE)
+ *   out [T, O]; may be x itself (same pointer, O == D), any other overlap is
+ *   FFF_ERR_ALIAS; leaf_idx [T] int32 may be NULL
+ *   Rows must be 16-byte aligned with D and O multiples of 8 (bf16) or 4 (fp32),
+ *   at most 4096 (bf16) or 2048 (fp32) features: else FFF_ERR_UNSUPPORTED.
+ *   Needs no workspace.  Other arguments, ownership, asynchrony and errors as
+ *   for fff_forward_hard.
+ */
+int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, float ln_eps,
+                      const void* node_w1, const void* node_b1, const void* node_w2,
+                      const void* node_b2, const void* leaf_w1, const void* leaf_b1,
+                      const void* leaf_w2, const void* leaf_b2, int depth, int node_size,
+                      int leaf_width, int act, int residual, void* out, int32_t* leaf_idx,
+                      void* stream, int64_t T, int64_t D, int64_t O, int dtype);
+
 /* Bytes of workspace a call with these sizes uses on the current device. */
 size_t fff_workspace_bytes(int64_t T, int depth);
 

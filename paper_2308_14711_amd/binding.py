@@ -42,6 +42,8 @@ def lib() -> ctypes.CDLL:
         L.fff_leaf_forward.argtypes = [vp] * 6 + [i32, i32, i32, vp, vp, i64, i64, i64, i32]
         L.fff_moe_top1_forward.argtypes = [vp] * 7 + [i32, i32, i32, vp, vp, vp, i64, i64, i64, i32]
         L.fff_forward_soft.argtypes = [vp] * 7 + [i32, i32, i32, vp, vp, vp, vp, i64, i64, i64, i32]
+        L.fff_forward_block.argtypes = ([vp] * 3 + [ctypes.c_float] + [vp] * 8 + [i32] * 5 + [vp, vp, vp] +
+                                        [i64, i64, i64, i32])
         L.fff_workspace_bytes.argtypes = [i64, i32]
         L.fff_workspace_bytes.restype = ctypes.c_size_t
         L.fff_reserve_workspace.argtypes = [i64, i32]
@@ -152,6 +154,24 @@ def fff_forward_soft(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, dept
                                   _ptr(leaf_w2), _ptr(leaf_b2), depth, leaf_width, act, _ptr(out),
                                   _ptr(mix), _ptr(entropy), _stream_handle(stream), T, D, O, _dtype_code(x)),
            "fff_forward_soft")
+
+
+def fff_forward_block(x, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2, leaf_w1, leaf_b1,
+                      leaf_w2, leaf_b2, depth, node_size, leaf_width, act, residual, out, leaf_idx=None,
+                      stream=None) -> None:
+    """Forward_I with nodes of `node_size` hidden neurons as a pre-norm residual layer:
+    out = FFF(LayerNorm(x)) (+ x when `residual`); ln_gamma = ln_beta = None skips the
+    normalisation.  out may be x itself."""
+    _check_dense(x, ln_gamma, ln_beta, node_w1, node_b1, node_w2, node_b2, leaf_w1, leaf_b1, leaf_w2, leaf_b2,
+                 out, leaf_idx)
+    T, D = x.shape
+    O = out.shape[1]
+    _check(lib().fff_forward_block(_ptr(x), _ptr(ln_gamma), _ptr(ln_beta), float(ln_eps), _ptr(node_w1),
+                                   _ptr(node_b1), _ptr(node_w2), _ptr(node_b2), _ptr(leaf_w1), _ptr(leaf_b1),
+                                   _ptr(leaf_w2), _ptr(leaf_b2), depth, node_size, leaf_width, act,
+                                   int(bool(residual)), _ptr(out), _ptr(leaf_idx), _stream_handle(stream),
+                                   T, D, O, _dtype_code(x)),
+           "fff_forward_block")
 
 
 def fff_workspace_bytes(T: int, depth: int) -> int:

@@ -428,6 +428,38 @@ int fff_forward_soft(const void* x, const void* node_w, const void* node_b, cons
     return e == hipSuccess ? FFF_OK : set_device_error(e, "soft forward kernel launch");
 }
 
+int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, float ln_eps,
+                      const void* node_w1, const void* node_b1, const void* node_w2, const void* node_b2,
+                      const void* leaf_w1, const void* leaf_b1, const void* leaf_w2, const void* leaf_b2,
+                      int depth, int node_size, int leaf_width, int act, int residual, void* out,
+                      int32_t* leaf_idx, void* stream, int64_t T, int64_t D, int64_t O, int dtype) {
+    int rc = check_common(depth, T, D, dtype);
+    if (rc == FFF_OK) rc = check_leaf(depth, leaf_width, act, T, D, O);
+    if (rc != FFF_OK) return rc;
+    if (node_size < 1 || node_size > kMaxLeafWidth) return FFF_ERR_RANGE;
+    if ((((int64_t)1 << depth) - 1) * node_size > kMaxElems / D) return FFF_ERR_SHAPE;
+    if (residual && O != D) return FFF_ERR_SHAPE;
+    if ((ln_gamma != nullptr) != (ln_beta != nullptr)) return FFF_ERR_NULL;
+    if (ln_gamma && !(ln_eps >= 0.0f)) return FFF_ERR_RANGE;
+    if (T == 0) return FFF_OK;
+    if (!x || !leaf_w1 || !leaf_b1 || !leaf_w2 || !leaf_b2 || !out) return FFF_ERR_NULL;
+    if (depth > 0 && (!node_w1 || !node_b1 || !node_w2 || !node_b2)) return FFF_ERR_NULL;
+    const int64_t es = dtype == FFF_BF16 ? 2 : 4;
+    // in place (out == x with rows of one width) is fine: a wave reads its token before it writes it
+    if (!(out == x && O == D) && overlaps(x, T * D * es, out, T * O * es)) return FFF_ERR_ALIAS;
+    if (leaf_idx && overlaps(leaf_idx, T * 4, out, T * O * es)) return FFF_ERR_ALIAS;
+    Problem p{x, nullptr, nullptr, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, leaf_idx,
+              T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
+    if (!block_shape_ok(x, out, leaf_w1, leaf_w2, D, O, p.bf16) || !vec_ok(node_w1, D, p.bf16) ||
+        (ln_gamma && (!vec_ok(ln_gamma, D, p.bf16) || !vec_ok(ln_beta, D, p.bf16))) ||
+        !vec_ok(leaf_b2, O, p.bf16))
+        return FFF_ERR_UNSUPPORTED;
+    g_last_error.clear();
+    hipError_t e = launch_forward_block(p, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2,
+                                        node_size, residual != 0, leaf_idx, (hipStream_t)stream);
+    return e == hipSuccess ? FFF_OK : set_device_error(e, "block kernel launch");
+}
+
 size_t fff_workspace_bytes(int64_t T, int depth) {
     if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH) return 0;
     return (size_t)layout_for(T, depth).total * sizeof(int32_t);

@@ -116,3 +116,27 @@ def test_forward_soft_rejects_bad_arguments_on_the_host(L):
     assert soft(dtype=0) == UNSUP           # bf16 only
     assert soft(D=12) == UNSUP              # rows must be whole 16-byte vectors
     assert soft(T=1 << 20, depth=24, out=ctypes.c_void_p(1 << 44)) == SHAPE   # the dense intermediates would not fit any device
+
+
+def test_forward_block_rejects_bad_arguments_on_the_host(L):
+    OK, NULL, SHAPE, RANGE, UNSUP, ALIAS = 0, 1, 2, 4, 5, 8
+    p = lambda mb: ctypes.c_void_p(mb << 20)
+    blk = lambda **kw: L.fff_forward_block(
+        kw.get("x", p(1)), kw.get("gamma", p(2)), kw.get("beta", p(3)), kw.get("eps", 1e-5),
+        kw.get("node_w1", p(4)), p(5), p(6), p(7), p(8), p(9), p(10), p(11),
+        kw.get("depth", 3), kw.get("n", 2), 2, kw.get("act", 0), kw.get("residual", 1),
+        kw.get("out", p(12)), None, None, kw.get("T", 4), kw.get("D", 16), kw.get("O", 16), kw.get("dtype", 1))
+    assert blk(T=0) == OK
+    assert blk(x=None) == NULL
+    assert blk(node_w1=None) == NULL
+    assert blk(gamma=None) == NULL                    # scale without shift
+    assert blk(beta=None) == NULL
+    assert blk(eps=-1.0) == RANGE
+    assert blk(eps=float("nan")) == RANGE
+    assert blk(n=0) == RANGE
+    assert blk(depth=25) == RANGE
+    assert blk(O=8) == SHAPE                          # the residual sum needs rows of one width
+    assert blk(act=9) == UNSUP
+    assert blk(D=12, O=12) == UNSUP                   # rows must be whole 16-byte vectors
+    assert blk(D=4104, O=4104) == UNSUP               # longer than a wave holds in registers
+    assert blk(out=ctypes.c_void_p((1 << 20) + 32)) == ALIAS
