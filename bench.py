@@ -18,6 +18,8 @@ Other modes, each printing one JSON line of its own:
     --sweep depth     small-batch latency against tree depth (the paper's speed experiment)
     --sweep experts   the same with the mixture-of-experts lookup (one engaged expert) beside it
     --soft            the soft pass (Forward_T, all leaves) of --config, against the MFMA roofline
+    --block           the pre-norm residual layer with nodes of --node-size hidden neurons on the
+                      shapes of --config
 """
 import argparse
 import json
@@ -244,6 +246,85 @@ def soft_bench(args, np, torch, W, F):
         "parity": {"rows_checked": n, "max_rel_row_err": float(err.max()), "max_mixture_err": mix_err}}))
 
 
+def block_bench(args, np, torch, W, F):
+    """Forward_I with nodes of --node-size hidden neurons as a pre-norm residual layer, on the shapes of
+    the chosen workload (bf16 ones with O = D).  One step = one call of fff_forward_block = one kernel;
+    its duration comes from events on the stream of the calls.  Roofline: HBM, every tensor once."""
+    import oracle
+    w = W.config(args.config, keep_f32=False)
+    assert w.O == w.D, "the residual sum needs rows of one width"
+    n, eps = args.node_size, 1e-5
+    nodes = W.wide_nodes(w.depth, n, w.D, w.dtype)
+    ln = W.layer_norm_params(w.D, w.dtype)
+    leaves = [np.ascontiguousarray(w.device_array(k)) for k in ("leaf_w1", "leaf_b1", "leaf_w2", "leaf_b2")]
+    x = np.ascontiguousarray(w.device_array("x"))
+
+    def up(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    d_ln, d_nodes, d_leaves = [up(a) for a in ln], [up(a) for a in nodes], [up(a) for a in leaves]
+    sets = args.sets or 4            # rotate token and output buffers so that no step finds its rows cached
+    xs = [up(x) for _ in range(sets)]
+    outs = [torch.empty_like(xs[0]) for _ in range(sets)]
+    idx = torch.empty((w.T,), dtype=torch.int32, device="cuda")
+
+    def step(i):
+        F.fff_forward_block(xs[i % sets], d_ln[0], d_ln[1], eps, *d_nodes, *d_leaves, w.depth, n, w.leaf_width,
+                            w.act, True, outs[i % sets], idx)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    es = 2 if w.dtype == W.DTYPE_BF16 else 4
+    NN, NL = (1 << w.depth) - 1, 1 << w.depth
+    weight_bytes = es * (NN * (n * w.D + 2 * n + 1) + NL * (w.leaf_width * (w.D + w.O + 1) + w.O) + 2 * w.D)
+    alg = es * w.T * (w.D + w.O) + 4 * w.T + weight_bytes
+    gbs = alg / (kernel_ms * 1e-3) / 1e9
+    # rows a token meets on its way: what the kernel asks of the caches per token
+    row_bytes = es * (w.depth * n * w.D + w.leaf_width * (w.D + w.O))
+    # the oracle on a prefix of the batch: parity of those rows, and its rate
+    m = w.T
+    step(0)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ref_out, ref_idx, margin = oracle.forward_block(x[:m], ln[0], ln[1], eps, *nodes, *leaves, w.depth, n,
+                                                    w.leaf_width, w.act, True)
+    cpu_s = time.perf_counter() - t1
+    got = outs[0][:m].float().cpu().numpy().astype(np.float64)
+    gi = idx[:m].cpu().numpy()
+    same = gi == ref_idx
+    assert (margin[~same] < 1e-4).all(), "routing differs outside the margin"
+    err = (np.abs(got - ref_out).max(axis=1) / np.maximum(np.abs(ref_out).max(axis=1), 1e-30))[same]
+    print(json.dumps({
+        "metric": "fff_block_tokens_per_s", "value": round(w.T / (ms * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == W.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": "%s shapes as a pre-norm residual layer, nodes of %d hidden neurons" % (w.name, n),
+                   "T": w.T, "D": w.D, "O": w.O, "depth": w.depth, "node_size": n, "leaf_width": w.leaf_width,
+                   "seed": 0, "buffer_sets": sets},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "block_kernel",
+                     "kernel_ms": round(kernel_ms, 5), "algorithmic_bytes": alg,
+                     "weight_row_bytes_per_token": row_bytes},
+        "cpu_baseline": {"value": round(m / cpu_s, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+                         "kind": "oracle", "sample": "the whole batch of %d tokens, one pass, fp64" % m,
+                         "seconds": round(cpu_s, 3)},
+        "parity": {"rows_checked": int(same.sum()), "routed_differently_inside_margin": int((~same).sum()),
+                   "max_rel_row_err": float(err.max())}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -262,6 +343,10 @@ def main():
     ap.add_argument("--soft", action="store_true",
                     help="time the soft forward pass (Forward_T: all leaves, dense, MFMA-bound) of --config "
                          "instead of the hard one")
+    ap.add_argument("--block", action="store_true",
+                    help="time the pre-norm residual layer with nodes of --node-size hidden neurons "
+                         "(fff_forward_block) on the shapes of --config")
+    ap.add_argument("--node-size", type=int, default=4)
     ap.add_argument("--sweep-batch", type=int, default=256)
     ap.add_argument("--sweep-leaf-width", type=int, default=32)
     ap.add_argument("--sweep-min-depth", type=int, default=1)
@@ -292,6 +377,10 @@ def main():
 
     if args.soft:
         soft_bench(args, np, torch, W, F)
+        return
+
+    if args.block:
+        block_bench(args, np, torch, W, F)
         return
 
     w = W.config(args.config, keep_f32=False)
