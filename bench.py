@@ -42,6 +42,7 @@ MEASURED_TRAFFIC = {
     ("C3", "staged", "leaf_hidden"): 82.7e6,
     ("C3", "staged", "leaf_output"): 85.9e6,
     ("C5", "fused", "walk_fused"): 1645.3e6,   # profiles/large_skewed_fff_fused_C5.md
+    ("C3", "block_n4", "block_kernel"): 1042.0e6,   # profiles/vit_block_layer_wide_nodes_C3.md
 }
 
 
@@ -287,10 +288,6 @@ def block_bench(args, np, torch, W, F):
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     kernel_ms = e0.elapsed_time(e1) / args.steps
     es = 2 if w.dtype == W.DTYPE_BF16 else 4
-    NN, NL = (1 << w.depth) - 1, 1 << w.depth
-    weight_bytes = es * (NN * (n * w.D + 2 * n + 1) + NL * (w.leaf_width * (w.D + w.O + 1) + w.O) + 2 * w.D)
-    alg = es * w.T * (w.D + w.O) + 4 * w.T + weight_bytes
-    gbs = alg / (kernel_ms * 1e-3) / 1e9
     # rows a token meets on its way: what the kernel asks of the caches per token
     row_bytes = es * (w.depth * n * w.D + w.leaf_width * (w.D + w.O))
     # the oracle on a prefix of the batch: parity of those rows, and its rate
@@ -303,6 +300,13 @@ def block_bench(args, np, torch, W, F):
     cpu_s = time.perf_counter() - t1
     got = outs[0][:m].float().cpu().numpy().astype(np.float64)
     gi = idx[:m].cpu().numpy()
+    # algorithmic bytes: x, out and leaf_idx once, the layer-norm vectors, and every node network and
+    # leaf block that some token touches, once
+    touched = algorithmic_bytes(w, ref_idx)
+    weight_bytes = es * (touched["u_node"] * (n * w.D + 2 * n + 1) + 2 * w.D +
+                         touched["u_leaf"] * (w.leaf_width * (w.D + w.O + 1) + w.O))
+    alg = es * w.T * (w.D + w.O) + 4 * w.T + weight_bytes
+    gbs = alg / (kernel_ms * 1e-3) / 1e9
     same = gi == ref_idx
     assert (margin[~same] < 1e-4).all(), "routing differs outside the margin"
     err = (np.abs(got - ref_out).max(axis=1) / np.maximum(np.abs(ref_out).max(axis=1), 1e-30))[same]
@@ -315,7 +319,9 @@ def block_bench(args, np, torch, W, F):
                    "T": w.T, "D": w.D, "O": w.O, "depth": w.depth, "node_size": n, "leaf_width": w.leaf_width,
                    "seed": 0, "buffer_sets": sets},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "block_kernel",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4),
+                     "traffic": None if args.opt else MEASURED_TRAFFIC.get((w.name, "block_n%d" % n, "block_kernel")),
+                     "kernel": "block_kernel",
                      "kernel_ms": round(kernel_ms, 5), "algorithmic_bytes": alg,
                      "weight_row_bytes_per_token": row_bytes},
         "cpu_baseline": {"value": round(m / cpu_s, 1), "unit": "tokens/s", "cores": oracle.num_threads(),

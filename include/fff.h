@@ -197,10 +197,8 @@ int fff_forward_soft(const void* x, const void* node_w, const void* node_b,
  *   FFF_ERR_ALIAS; leaf_idx [T] int32 may be NULL
  *   Rows must be 16-byte aligned with D and O multiples of 8 (bf16) or 4 (fp32),
  *   at most 4096 (bf16) or 2048 (fp32) features: else FFF_ERR_UNSUPPORTED.
- *   Large batches over more leaf weights than an L2 holds run as three stages
- *   (see option "block_path") and use the workspace like fff_forward_hard; z is
- *   then computed twice, identically.  Other arguments, ownership, asynchrony
- *   and errors as for fff_forward_hard.
+ *   Needs no workspace.  Other arguments, ownership, asynchrony and errors as
+ *   for fff_forward_hard.
  */
 int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, float ln_eps,
                       const void* node_w1, const void* node_b1, const void* node_w2,
@@ -248,12 +246,6 @@ int fff_release_workspace(void);
  *   "last_path"      read it after a call: the path (1, 2, 3 or 4) fff_forward_hard took
  *   "last_leaf_path" read it after a staged call: 1 = its leaf stage ran the gather kernel,
  *                    2 = the two tile kernels
- *   "block_path"     fff_forward_block: 0 = choose (default), 1 = one launch, a wave per token
- *                    from load to store, 2 = descent, bucketing, then the leaf networks over
- *                    the tokens in leaf order (the token is read and normalised twice, the
- *                    leaf rows stay in the caches).  The default takes 2 when T > 8192, a
- *                    leaf sees >= 16 tokens on average and the leaf weights exceed 3 MB
- *   "last_block_path" read it after a call: which of the two fff_forward_block took
  *   "bucket_kernel"  0 = choose by size (default: the token-chunk kernel up to 131072 tokens
  *                    and 4096 leaves, then the leaf-range kernel up to 2^21 tokens and 2^19
  *                    leaves, then the chunk-matrix kernels), 1 = the leaf-range kernel when the

@@ -32,8 +32,6 @@ struct Options {
     int64_t bucket_kernel = 0;   // 0 auto, 1 leaf-range kernel, 2 chunk-matrix kernels, 3 token-chunk kernel
     int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
     int64_t last_leaf_path = 0;  // read-only: leaf stage of the last staged call (1 gather kernel, 2 tile kernels)
-    int64_t block_path = 0;      // fff_forward_block: 0 auto, 1 one launch, 2 descent / bucketing / leaves in leaf order
-    int64_t last_block_path = 0; // read-only: what the last fff_forward_block call took
     int64_t token_max_T = 512;   // batches up to this many tokens (6x where no fused launch fits) go one block per token
 } g_opt;
 
@@ -457,34 +455,9 @@ int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, 
         !vec_ok(leaf_b2, O, p.bf16))
         return FFF_ERR_UNSUPPORTED;
     g_last_error.clear();
-    hipStream_t s = (hipStream_t)stream;
-    // One launch keeps a token in registers from its load to its store, but asks the caches for
-    // every leaf row once per token; once the leaf weights outgrow the 4 MB L2 of an XCD those
-    // reads go out to memory.  Then: descent, bucketing by leaf, and the leaf networks over the
-    // tokens in leaf order, where neighbouring waves meet the same rows and an XCD a fixed eighth
-    // of the leaves (the token is read and normalised twice, which is the cheaper side).
-    const int64_t leaf_bytes = ((int64_t)1 << depth) * leaf_width * (D + O) * es;
-    const bool staged = g_opt.block_path == 2 ||
-                        (g_opt.block_path == 0 && depth > 0 && T > 8192 && (T >> depth) >= 16 &&
-                         leaf_bytes > ((int64_t)3 << 20));
-    g_opt.last_block_path = staged ? 2 : 1;
-    hipError_t e;
-    if (!staged) {
-        e = launch_forward_block(p, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2, node_size,
-                                 residual != 0, leaf_idx, s);
-        return e == hipSuccess ? FFF_OK : set_device_error(e, "block kernel launch");
-    }
-    Workspace ws;
-    Layout lay;
-    if ((rc = get_workspace(T, depth, &ws, &lay)) != FFF_OK) return rc;
-    int32_t* li = leaf_idx ? leaf_idx : ws.leaf_idx;
-    e = launch_forward_block(p, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2, node_size,
-                             residual != 0, li, s, 1);
-    if (e != hipSuccess) return set_device_error(e, "block descent kernel launch");
-    if ((rc = run_bucket(li, T, depth, ws, nullptr, nullptr, ws.perm, ws.slot_leaf, s)) != FFF_OK) return rc;
-    e = launch_forward_block(p, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2, node_size,
-                             residual != 0, nullptr, s, 2, ws.perm, ws.slot_leaf);
-    return e == hipSuccess ? FFF_OK : set_device_error(e, "block leaf kernel launch");
+    hipError_t e = launch_forward_block(p, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2,
+                                        node_size, residual != 0, leaf_idx, (hipStream_t)stream);
+    return e == hipSuccess ? FFF_OK : set_device_error(e, "block kernel launch");
 }
 
 size_t fff_workspace_bytes(int64_t T, int depth) {
@@ -530,16 +503,13 @@ static int64_t* option_slot(const char* name) {
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
     if (!std::strcmp(name, "last_path")) return &g_opt.last_path;
     if (!std::strcmp(name, "last_leaf_path")) return &g_opt.last_leaf_path;
-    if (!std::strcmp(name, "block_path")) return &g_opt.block_path;
-    if (!std::strcmp(name, "last_block_path")) return &g_opt.last_block_path;
     return nullptr;
 }
 
 int fff_set_option(const char* name, int64_t value) {
     int64_t* s = option_slot(name);
     if (!s || value < 0) return FFF_ERR_UNSUPPORTED;
-    if (s == &g_opt.last_path || s == &g_opt.last_leaf_path || s == &g_opt.last_block_path)
-        return FFF_ERR_UNSUPPORTED;   // read-only
+    if (s == &g_opt.last_path || s == &g_opt.last_leaf_path) return FFF_ERR_UNSUPPORTED;   // read-only
     *s = value;
     return FFF_OK;
 }

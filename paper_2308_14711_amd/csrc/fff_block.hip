@@ -32,16 +32,11 @@ struct BlockArgs {
     const void* leaf_w2;
     const void* leaf_b2;
     void* out;
-    int32_t* leaf_idx;     // may be null (not in kModeDescend)
-    const int32_t* order;      // kModeLeaves: token of every slot, slots grouped by leaf
-    const int32_t* slot_leaf;  // kModeLeaves: leaf of every slot
+    int32_t* leaf_idx;     // may be null
     int64_t T;
-    int D, O, depth, n, L, act, residual, mode;
+    int D, O, depth, n, L, act, residual;
     float eps;
 };
-
-// what one launch does with a token
-enum { kModeWhole = 0, kModeDescend = 1, kModeLeaves = 2 };
 
 // neurons whose rows are in flight together: up to 8 pieces per lane at a time
 constexpr int batch_for(int nv) { return nv >= 8 ? 1 : nv >= 4 ? 2 : 4; }
@@ -96,19 +91,7 @@ __global__ __launch_bounds__(256) void block_kernel(const BlockArgs a) {
         vo[i] = oko[i] ? v : po - 1;
     }
 
-    // kModeWhole, kModeDescend: waves stride over the tokens.  kModeLeaves: a block takes a run of
-    // consecutive slots (tokens grouped by leaf, so its waves and its neighbours on the same XCD
-    // meet the same leaf rows), the blocks of one XCD together one contiguous eighth of the slots.
-    int64_t it = wave, it_end = a.T, it_step = n_waves;
-    if (a.mode == kModeLeaves) {
-        const int64_t chunk = (a.T + gridDim.x - 1) / gridDim.x;
-        const int64_t lo = xcd_contiguous_block() * chunk;
-        it = lo + threadIdx.x / kWave;
-        it_end = lo + chunk < a.T ? lo + chunk : a.T;
-        it_step = blockDim.x / kWave;
-    }
-    for (; it < it_end; it += it_step) {
-        const int64_t t = a.mode == kModeLeaves ? __builtin_amdgcn_readfirstlane(a.order[it]) : it;
+    for (int64_t t = wave; t < a.T; t += n_waves) {
         float z[NV][E];
         const uint4* xrow = (const uint4*)a.x + t * pd;
 #pragma unroll
@@ -174,8 +157,7 @@ __global__ __launch_bounds__(256) void block_kernel(const BlockArgs a) {
 
         // descent: node i (heap order) has hidden neurons i n .. i n + n - 1
         int64_t node = 0;
-        if (a.mode == kModeLeaves) node = first_leaf_row + __builtin_amdgcn_readfirstlane(a.slot_leaf[it]);
-        for (int m = 0; m < (a.mode == kModeLeaves ? 0 : a.depth); ++m) {
+        for (int m = 0; m < a.depth; ++m) {
             float logit = Elem<BF16>::load(a.node_b2, node);
             for (int j0 = 0; j0 < a.n; j0 += kBatch) {
                 const int cnt = a.n - j0 < kBatch ? a.n - j0 : kBatch;
@@ -195,8 +177,7 @@ __global__ __launch_bounds__(256) void block_kernel(const BlockArgs a) {
             node = __builtin_amdgcn_readfirstlane((int)node);
         }
         const int64_t leaf = node - first_leaf_row;
-        if (a.leaf_idx && a.mode != kModeLeaves && lane == 0) a.leaf_idx[t] = (int32_t)leaf;
-        if (a.mode == kModeDescend) continue;
+        if (a.leaf_idx && lane == 0) a.leaf_idx[t] = (int32_t)leaf;
 
         // leaf: hidden neurons in batches, each batch added to the output row at once
         float y[NV][E];
@@ -273,12 +254,9 @@ bool block_shape_ok(const void* x, const void* out, const void* leaf_w1, const v
 hipError_t launch_forward_block(const Problem& p, const void* gamma, const void* beta, float eps,
                                 const void* node_w1, const void* node_b1, const void* node_w2,
                                 const void* node_b2, int node_size, bool residual, int32_t* leaf_idx,
-                                hipStream_t s, int stage, const int32_t* order, const int32_t* slot_leaf) {
+                                hipStream_t s) {
     if (p.T == 0) return hipSuccess;
     BlockArgs a;
-    a.mode = stage == 1 ? kModeDescend : stage == 2 ? kModeLeaves : kModeWhole;
-    a.order = order;
-    a.slot_leaf = slot_leaf;
     a.x = p.x;
     a.gamma = gamma;
     a.beta = beta;
@@ -309,7 +287,6 @@ hipError_t launch_forward_block(const Problem& p, const void* gamma, const void*
     int64_t blocks = (p.T + 3) / 4;
     const int64_t cap = 256 * 16;
     if (blocks > cap) blocks = cap;
-    blocks = (blocks + kXcds - 1) / kXcds * kXcds;   // kModeLeaves deals whole eighths to the XCDs
     return p.bf16 ? pick<true>(a, nv, blocks, s) : pick<false>(a, nv, blocks, s);
 }
 

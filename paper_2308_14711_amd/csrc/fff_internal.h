@@ -112,16 +112,12 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
 // Forward_I with nodes of `node_size` hidden neurons on the layer-normalised token (gamma null:
 // no normalisation), plus the token itself when `residual` (fff_block.hip); one launch, a wave per
 // token.  p.node_w / p.node_b are not used.  Needs block_shape_ok.
-// stage 0: everything.  stage 1: the descent alone (leaf_idx must be given).  stage 2: the leaf
-// networks and the output rows alone, for tokens grouped by leaf: slot i holds token order[i]
-// at leaf slot_leaf[i] (as the bucketing stage writes them).
 bool block_shape_ok(const void* x, const void* out, const void* leaf_w1, const void* leaf_w2, int64_t D,
                     int64_t O, bool bf16);
 hipError_t launch_forward_block(const Problem& p, const void* gamma, const void* beta, float eps,
                                 const void* node_w1, const void* node_b1, const void* node_w2,
                                 const void* node_b2, int node_size, bool residual, int32_t* leaf_idx,
-                                hipStream_t s, int stage = 0, const int32_t* order = nullptr,
-                                const int32_t* slot_leaf = nullptr);
+                                hipStream_t s);
 
 // Whole forward pass in one launch, one token per lane group (any shape).
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);

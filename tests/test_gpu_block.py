@@ -75,8 +75,7 @@ def _path_is_legitimate(z, nodes, depth, n, act, leaf):
     return True
 
 
-def _check(case, seed=5, in_place=False, want_idx=True, path=0):
-    """path: 0 = the library's choice, 1 = one launch, 2 = descent / bucketing / leaves in leaf order."""
+def _check(case, seed=5, in_place=False, want_idx=True):
     import torch
     import paper_2308_14711_amd as F
     name, T, D, O, depth, n, L, act, dtype, norm, residual = case
@@ -91,14 +90,8 @@ def _check(case, seed=5, in_place=False, want_idx=True, path=0):
     else:
         out = torch.full((T, O), float("nan"), dtype=d_x.dtype, device="cuda")
     idx = torch.full((T,), -9, dtype=torch.int32, device="cuda") if want_idx else None
-    F.fff_set_option("block_path", path)
-    try:
-        F.fff_forward_block(d_x, d_ln[0], d_ln[1], eps, *d_nodes, *d_leaves, depth, n, L, act, residual, out, idx)
-        torch.cuda.synchronize()
-    finally:
-        F.fff_set_option("block_path", 0)
-    took = F.fff_get_option("last_block_path")
-    assert path == 0 or took == path
+    F.fff_forward_block(d_x, d_ln[0], d_ln[1], eps, *d_nodes, *d_leaves, depth, n, L, act, residual, out, idx)
+    torch.cuda.synchronize()
     ref_out, ref_idx, margin = oracle.forward_block(x, ln[0], ln[1], eps, *nodes, *leaves, depth, n, L, act, residual)
     got = out_to_f64(out)
     assert got.shape == ref_out.shape and np.isfinite(got).all()
@@ -123,37 +116,24 @@ def _check(case, seed=5, in_place=False, want_idx=True, path=0):
     scale = np.maximum(np.abs(ref_out).max(axis=1), 1e-30)
     err = (np.abs(got - ref_out).max(axis=1) / scale)[keep]
     assert err.max(initial=0.0) <= TOL[dtype], "row %d off by %.3e" % (int(np.argmax(err)), err.max())
-    print("  block %s: path %d, %d margin tokens, %d routed differently, %d leaves used, max row error %.2e" % (
-        name, took, int((margin < ROUTING_MARGIN).sum()), n_diff, len(set(ref_idx.tolist())), err.max(initial=0.0)), flush=True)
+    print("  block %s: %d margin tokens, %d routed differently, %d leaves used, max row error %.2e" % (
+        name, int((margin < ROUTING_MARGIN).sum()), n_diff, len(set(ref_idx.tolist())), err.max(initial=0.0)), flush=True)
     return ref_idx
 
 
-@pytest.mark.parametrize("path", [1, 2], ids=["one_launch", "leaf_order"])
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
-def test_block_against_the_oracle(case, path):
-    print("\n[case] block %s T=%d D=%d O=%d depth=%d n=%d L=%d act=%d dtype=%d norm=%s residual=%s seed 5" % case
-          + " path %d" % path, flush=True)
-    ref_idx = _check(case, path=path)
+def test_block_against_the_oracle(case):
+    print("\n[case] block %s T=%d D=%d O=%d depth=%d n=%d L=%d act=%d dtype=%d norm=%s residual=%s seed 5" % case, flush=True)
+    ref_idx = _check(case)
     if case[4] >= 3 and case[1] >= 200:
         assert len(set(ref_idx.tolist())) >= 4, "the workload does not spread over the leaves"
 
 
-@pytest.mark.parametrize("path", [1, 2], ids=["one_launch", "leaf_order"])
-def test_block_in_place_and_without_an_index_buffer(path):
-    print("\n[case] block in place (out = x), then without leaf_idx, path %d" % path, flush=True)
-    _check(("in_place", 900, 768, 768, 6, 3, 4, W.ACT_GELU, BF16, True, True), in_place=True, path=path)
-    _check(("in_place_f32", 300, 128, 128, 4, 2, 2, W.ACT_RELU, F32, True, True), in_place=True, path=path)
-    _check(("no_idx", 900, 768, 768, 6, 3, 4, W.ACT_GELU, BF16, True, True), want_idx=False, path=path)
-
-
-def test_block_default_takes_the_leaf_order_path_for_a_large_batch_over_many_leaf_weights():
-    print("\n[case] block default path, T=20000 D=768 depth=7 n=2 L=8 (3 MB of leaf weights: one launch), "
-          "then depth=8 (6 MB: leaf order)", flush=True)
-    import paper_2308_14711_amd as F
-    _check(("auto_small", 20000, 768, 768, 7, 2, 8, W.ACT_GELU, BF16, True, True))
-    assert F.fff_get_option("last_block_path") == 1
-    _check(("auto_large", 20000, 768, 768, 8, 2, 8, W.ACT_GELU, BF16, True, True))
-    assert F.fff_get_option("last_block_path") == 2
+def test_block_in_place_and_without_an_index_buffer():
+    print("\n[case] block in place (out = x), then without leaf_idx", flush=True)
+    _check(("in_place", 900, 768, 768, 6, 3, 4, W.ACT_GELU, BF16, True, True), in_place=True)
+    _check(("in_place_f32", 300, 128, 128, 4, 2, 2, W.ACT_RELU, F32, True, True), in_place=True)
+    _check(("no_idx", 900, 768, 768, 6, 3, 4, W.ACT_GELU, BF16, True, True), want_idx=False)
 
 
 def test_block_two_relu_neurons_route_like_the_linear_node():
