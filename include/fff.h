@@ -186,7 +186,9 @@ int fff_forward_soft(const void* x, const void* node_w, const void* node_b,
  * network reads the layer-normalised token and the block adds the token back:
  *     z = (x - mean) / sqrt(var + ln_eps) * ln_gamma + ln_beta   (var with divisor D),
  *     out = FFF(z) + x.
- * z is kept in fp32 registers: it is never rounded to `dtype` nor stored.
+ * z stays in registers (fp32, or for bf16 rows of up to 1024 features a pair of
+ * bf16 rows hi + lo carrying 16 mantissa bits): it is never rounded to `dtype`
+ * nor stored.
  *   ln_gamma, ln_beta  device, [D], or both NULL: no normalisation (z = x)
  *   ln_eps             >= 0
  *   node_w1 [2^depth - 1, node_size, D], node_b1 and node_w2 [2^depth - 1,

@@ -6,13 +6,14 @@
 // (section "Fast feedforward layers as building blocks") the network sees the layer-normalised
 // token z = LayerNorm(x) and the block returns x + FFF(z).
 //
-// One wave owns a token from the load of x to the store of the output row.  The row lives in
-// fp32 registers (lane l holds the 16-byte pieces l, l + 64, ...), so the normalisation is two
-// wave sums and the normalised row is never rounded or written anywhere.  Every weight row the
-// token meets (n per node, l + l for the leaf) is one coalesced 16-byte load per lane; the rows
-// of up to four neurons are requested together so that their latencies overlap, and their four
-// dot products are reduced over the wave together.  All decisions come out of wave sums that
-// give every lane the same bits, so the tree index is wave-uniform.
+// A token stays with the same lanes from the load of x to the store of its output row: the
+// normalisation is two sums over those lanes and the normalised row is never written anywhere.
+// Every weight row the token meets (n per node, l + l for the leaf) is one coalesced 16-byte load
+// per lane and piece; the rows of a few neurons are requested together so that their latencies
+// overlap.  All decisions come out of sums that give every lane of the token the same bits.
+// Two kernels: rows of up to 128 pieces (1024 bf16 / 512 fp32 features) give a token the 16 lanes
+// of a DPP row, four tokens to a wave (block_group_kernel); longer rows give it a whole wave and
+// keep the row in fp32 (block_kernel).
 #include "fff_device.h"
 #include "fff_internal.h"
 
@@ -227,6 +228,228 @@ __global__ __launch_bounds__(256) void block_kernel(const BlockArgs a) {
     }
 }
 
+// Lanes 0..3 of every aligned group of four ("quad") hold a, b, c, d: every lane gets lane Q's value.
+template <int Q> __device__ __forceinline__ float quad_pick(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), Q * 0x55, 0xf, 0xf, false));
+}
+// ... and their sum, the same bits in all four (each step adds the same two partial sums in both
+// lanes of a pair)
+__device__ __forceinline__ float quad_sum(float v) {
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));   // lanes 1 0 3 2
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));   // lanes 2 3 0 1
+    return v;
+}
+
+// Rows of up to 16 NV pieces: a token is owned by the 16 lanes of one DPP row, four tokens to a
+// wave, so a weight-row instruction serves four tokens and a dot product is reduced with four row
+// steps.  The normalised row is kept as two packed bf16 rows, z = hi + lo with hi = bf16(z) and
+// lo = bf16(z - hi) (TWO; a relative 2^-17 of each element, below the fp32 accumulation noise of
+// a 768-term dot product), so that the dot products run on the packed dot instruction against the
+// weights as loaded: half the instructions of unpack-and-multiply, in the registers of one fp32
+// row.  Without normalisation a bf16 token is its own hi row (TWO = false); fp32 rows stay fp32.
+// The sums of a batch of neurons are spread over the lanes of a quad, so that one evaluation of
+// the activation serves the batch.
+template <bool BF16, int NV, bool TWO>
+__global__ __launch_bounds__(256) void block_group_kernel(const BlockArgs a) {
+    typedef Piece<BF16> P;
+    constexpr int E = P::kElems;
+    constexpr int kLpt = 16;                            // lanes per token
+    constexpr int kGroups = 256 / kLpt;                 // tokens a block holds at a time
+    constexpr int kRows = NV >= 6 ? 2 : 4;              // weight rows requested together per token
+    static_assert(BF16 || !TWO, "fp32 rows are kept as they are");
+    const int sub = threadIdx.x & (kLpt - 1);
+    const int quad = threadIdx.x & 3;
+    const int grp_in_block = threadIdx.x / kLpt;
+    const int pd = a.D / E, po = a.O / E;
+    const int64_t first_leaf_row = ((int64_t)1 << a.depth) - 1;
+
+    int vd[NV], vo[NV];
+    bool okd[NV], oko[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int v = sub + kLpt * i;
+        okd[i] = v < pd;
+        oko[i] = v < po;
+        vd[i] = okd[i] ? v : pd - 1;
+        vo[i] = oko[i] ? v : po - 1;
+    }
+
+    for (int64_t t = (int64_t)blockIdx.x * kGroups + grp_in_block; t < a.T; t += (int64_t)gridDim.x * kGroups) {
+        const uint4* xrow = (const uint4*)a.x + t * pd;
+        uint4 zh[NV], zl[TWO ? NV : 1];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) zh[i] = keep_if(okd[i], xrow[vd[i]]);
+        if (a.gamma) {
+            float f[NV][E];
+            float s = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                P::unpack(zh[i], f[i]);
+#pragma unroll
+                for (int e = 0; e < E; ++e) s += f[i][e];
+            }
+            const float mean = group_sum<kLpt>(s) / (float)a.D;
+            float q = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const float c = okd[i] ? f[i][e] - mean : 0.0f;
+                    q = fmaf(c, c, q);
+                }
+            const float var = group_sum<kLpt>(q) / (float)a.D;
+            const float rstd = 1.0f / sqrtf(var + a.eps);
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                float g[E], b[E];
+                P::unpack(((const uint4*)a.gamma)[vd[i]], g);
+                P::unpack(((const uint4*)a.beta)[vd[i]], b);
+#pragma unroll
+                for (int e = 0; e < E; ++e) f[i][e] = okd[i] ? fmaf((f[i][e] - mean) * rstd, g[e], b[e]) : 0.0f;
+                zh[i] = P::pack(f[i]);
+                if (TWO) {
+                    float hi[E];
+                    P::unpack(zh[i], hi);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) hi[e] = f[i][e] - hi[e];
+                    zl[TWO ? i : 0] = P::pack(hi);
+                }
+            }
+        } else if (TWO) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) zl[TWO ? i : 0] = make_uint4(0, 0, 0, 0);
+        }
+
+        // z . row for the pieces of one weight row, summed over the token's 16 lanes
+        auto dotz = [&](const uint4 (&w)[NV]) {
+            float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                a0 = Elem<BF16>::dot(zh[i], w[i], a0);
+                if (TWO) a1 = Elem<BF16>::dot(zl[TWO ? i : 0], w[i], a1);
+            }
+            return a0 + a1;
+        };
+
+        int64_t node = 0;
+        // nodes of one hidden neuron (the usual case) go a row at a time
+        for (int m = 0; m < (a.n != 1 ? 0 : a.depth); ++m) {
+            uint4 w[NV];
+#pragma unroll
+            for (int i = 0; i < NV; ++i) w[i] = ((const uint4*)a.node_w1)[node * pd + vd[i]];
+            const float pre = group_sum<kLpt>(dotz(w)) + Elem<BF16>::load(a.node_b1, node);
+            const float logit = fmaf(Elem<BF16>::load(a.node_w2, node), activate(pre, a.act), Elem<BF16>::load(a.node_b2, node));
+            node = 2 * node + (logit >= 0.0f ? 2 : 1);
+        }
+        for (int m = 0; m < (a.n == 1 ? 0 : a.depth); ++m) {
+            float logit = Elem<BF16>::load(a.node_b2, node);
+            for (int j0 = 0; j0 < a.n; j0 += kRows) {
+                // the rows of up to kRows hidden neurons are requested together; past the node's last
+                // neuron the last row is asked for again (same addresses, no new traffic to L2) and
+                // its result dropped -- a batch without conditionals keeps the register count down
+                const int cnt = a.n - j0 < kRows ? a.n - j0 : kRows;
+                uint4 w[kRows][NV];
+#pragma unroll
+                for (int j = 0; j < kRows; ++j) {
+                    const int64_t row = node * a.n + j0 + (j < cnt ? j : cnt - 1);
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) w[j][i] = ((const uint4*)a.node_w1)[row * pd + vd[i]];
+                }
+                float sj[kRows];
+#pragma unroll
+                for (int j = 0; j < kRows; ++j) sj[j] = dotz(w[j]);
+#pragma unroll
+                for (int j = 0; j < kRows; ++j) sj[j] = group_sum<kLpt>(sj[j]);
+                // every lane holds all the batch's sums; lane q of each quad takes neuron q through
+                // the activation, so one evaluation serves the whole batch (kRows <= 4)
+                float mine = sj[0];
+#pragma unroll
+                for (int j = 1; j < kRows; ++j) mine = quad == j ? sj[j] : mine;
+                const bool live = quad < cnt;
+                const int64_t neuron = node * a.n + j0 + (live ? quad : 0);
+                const float h = activate(mine + Elem<BF16>::load(a.node_b1, neuron), a.act);
+                logit += quad_sum(live ? Elem<BF16>::load(a.node_w2, neuron) * h : 0.0f);
+            }
+            // the 16 lanes of a token hold the same bits, so they take the same child
+            node = 2 * node + (logit >= 0.0f ? 2 : 1);
+        }
+        const int64_t leaf = node - first_leaf_row;
+        if (a.leaf_idx && sub == 0) a.leaf_idx[t] = (int32_t)leaf;
+
+        float y[NV][E];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) P::unpack(((const uint4*)a.leaf_b2)[leaf * po + vo[i]], y[i]);
+        for (int r0 = 0; r0 < a.L; r0 += kRows) {
+            const int cnt = a.L - r0 < kRows ? a.L - r0 : kRows;
+            float h[kRows];
+            {
+                uint4 w[kRows][NV];
+#pragma unroll
+                for (int j = 0; j < kRows; ++j) {
+                    const int64_t row = leaf * a.L + r0 + (j < cnt ? j : cnt - 1);
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) w[j][i] = ((const uint4*)a.leaf_w1)[row * pd + vd[i]];
+                }
+#pragma unroll
+                for (int j = 0; j < kRows; ++j) h[j] = dotz(w[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < kRows; ++j) h[j] = group_sum<kLpt>(h[j]);
+            uint4 w2[kRows][NV];
+#pragma unroll
+            for (int j = 0; j < kRows; ++j) {
+                const int64_t row = leaf * a.L + r0 + (j < cnt ? j : cnt - 1);
+#pragma unroll
+                for (int i = 0; i < NV; ++i) w2[j][i] = ((const uint4*)a.leaf_w2)[row * po + vo[i]];
+            }
+            // one activation for the batch, as in the nodes; then every lane picks up each neuron's
+            float mine = h[0];
+#pragma unroll
+            for (int j = 1; j < kRows; ++j) mine = quad == j ? h[j] : mine;
+            const bool live = quad < cnt;
+            const float hq = live ? activate(mine + Elem<BF16>::load(a.leaf_b1, leaf * a.L + r0 + (live ? quad : 0)), a.act)
+                                  : 0.0f;
+            h[0] = quad_pick<0>(hq);
+            if constexpr (kRows > 1) h[1] = quad_pick<1>(hq);
+            if constexpr (kRows > 2) h[2] = quad_pick<2>(hq);
+            if constexpr (kRows > 3) h[3] = quad_pick<3>(hq);
+#pragma unroll
+            for (int j = 0; j < kRows; ++j) {
+#pragma unroll
+                for (int i = 0; i < NV; ++i) {
+                    float f[E];
+                    P::unpack(w2[j][i], f);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) y[i][e] = fmaf(h[j], f[e], y[i][e]);
+                }
+            }
+        }
+        uint4* orow = (uint4*)a.out + t * po;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            if (a.residual) {
+                float f[E];
+                P::unpack(xrow[vo[i]], f);
+#pragma unroll
+                for (int e = 0; e < E; ++e) y[i][e] += f[e];
+            }
+            if (oko[i]) orow[vo[i]] = P::pack(y[i]);
+        }
+    }
+}
+
+template <bool BF16, int NV, bool TWO> hipError_t run_group(const BlockArgs& a, int64_t blocks, hipStream_t s) {
+    block_group_kernel<BF16, NV, TWO><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
+    return hipGetLastError();
+}
+
+template <bool BF16, bool TWO> hipError_t pick_group(const BlockArgs& a, int nv, int64_t blocks, hipStream_t s) {
+    if (nv <= 2) return run_group<BF16, 2, TWO>(a, blocks, s);
+    if (nv <= 4) return run_group<BF16, 4, TWO>(a, blocks, s);
+    if (nv <= 6) return run_group<BF16, 6, TWO>(a, blocks, s);
+    return run_group<BF16, 8, TWO>(a, blocks, s);
+}
+
 template <bool BF16, int NV> hipError_t run(const BlockArgs& a, int64_t blocks, hipStream_t s) {
     block_kernel<BF16, NV><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
     return hipGetLastError();
@@ -241,6 +464,7 @@ template <bool BF16> hipError_t pick(const BlockArgs& a, int nv, int64_t blocks,
 
 }  // namespace
 
+constexpr int kGroupMaxPieces = 8 * 16;      // longest row the 16-lanes-per-token kernel holds
 constexpr int kBlockMaxPieces = 8 * kWave;   // 16-byte pieces of the longest row a wave holds
 
 // rows of 16-byte pieces, at most 512 of them (4096 bf16 or 2048 fp32 features)
@@ -287,6 +511,14 @@ hipError_t launch_forward_block(const Problem& p, const void* gamma, const void*
     int64_t blocks = (p.T + 3) / 4;
     const int64_t cap = 256 * 16;
     if (blocks > cap) blocks = cap;
+    if (pieces <= kGroupMaxPieces) {
+        // sixteen lanes a token, sixteen tokens a block
+        int64_t gblocks = (p.T + 15) / 16;
+        if (gblocks > cap) gblocks = cap;
+        const int gnv = (int)((pieces + 15) / 16);
+        if (!p.bf16) return pick_group<false, false>(a, gnv, gblocks, s);
+        return gamma ? pick_group<true, true>(a, gnv, gblocks, s) : pick_group<true, false>(a, gnv, gblocks, s);
+    }
     return p.bf16 ? pick<true>(a, nv, blocks, s) : pick<false>(a, nv, blocks, s);
 }
 

@@ -97,6 +97,12 @@ __device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
     __builtin_nontemporal_store(u, (u32x4_t*)p);
 }
 
+// v or zeros, component by component (a conditional on the 16-byte struct itself is lowered
+// through memory)
+__device__ __forceinline__ uint4 keep_if(bool ok, const uint4& v) {
+    return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
+}
+
 // Workgroups are dealt to the 8 XCDs round-robin (block b runs on XCD b mod 8) and every XCD
 // has its own L2.  Work that is ordered by leaf wants consecutive items on one XCD, since they
 // read the same weight rows: block b takes logical index (b mod 8) * (grid / 8) + b / 8, which

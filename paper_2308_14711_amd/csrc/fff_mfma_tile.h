@@ -17,12 +17,6 @@ constexpr int kTileM = 64;      // rows (tokens) per block
 constexpr int kTileN = 128;     // columns per block
 constexpr int kTileK = 64;      // K elements per chunk (8 pieces of 16 bytes per row)
 
-// v or zeros, component by component (a conditional on the 16-byte struct itself is lowered
-// through memory)
-__device__ __forceinline__ uint4 keep_if(bool ok, const uint4& v) {
-    return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
-}
-
 __device__ __forceinline__ int tile_swz(int row, int piece) { return 8 * row + ((piece + (row >> 1)) & 7); }
 
 struct TileLds {
