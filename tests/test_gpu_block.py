@@ -28,6 +28,10 @@ CASES = [
     ("more_than_waves", 16389, 64,   64,   4,     2, 2,  W.ACT_RELU,  BF16,  True,  True),
     ("many_neurons",    400,   256,  256,  3,     9, 11, W.ACT_GELU,  F32,   True,  True),
     ("deep",            2000,  256,  256,  12,    2, 1,  W.ACT_RELU,  BF16,  True,  True),
+    ("group_max_bf16",  300,   1024, 1024, 4,     3, 5,  W.ACT_GELU,  BF16,  True,  True),
+    ("group_ragged8",   257,   800,  1000, 3,     2, 3,  W.ACT_RELU,  BF16,  True,  False),
+    ("group_max_f32",   200,   512,  384,  3,     6, 7,  W.ACT_GELU,  F32,   True,  False),
+    ("group_f32_six",   150,   384,  384,  5,     1, 2,  W.ACT_RELU,  F32,   False, True),
 ]
 
 
