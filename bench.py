@@ -198,7 +198,7 @@ def soft_bench(args, np, torch, W, F):
     fff_forward_soft (node scores, mixture weights, weighted hidden activations, output rows, per-node
     entropies).  The roofline is the matrix cores': flops of the three contractions over time."""
     import oracle
-    w = W.config(args.config, keep_f32=False)
+    w = W.config(args.config, keep_f32=False, T=args.tokens or None)
     assert w.dtype == W.DTYPE_BF16, "the soft pass runs on the bf16 matrix cores"
     NL, NN = 1 << w.depth, (1 << w.depth) - 1
     dev = {k: torch.from_numpy(np.ascontiguousarray(w.device_array(k)).view(np.int16)).cuda().view(torch.bfloat16)
@@ -252,7 +252,7 @@ def block_bench(args, np, torch, W, F):
     the chosen workload (bf16 ones with O = D).  One step = one call of fff_forward_block = one kernel;
     its duration comes from events on the stream of the calls.  Roofline: HBM, every tensor once."""
     import oracle
-    w = W.config(args.config, keep_f32=False)
+    w = W.config(args.config, keep_f32=False, T=args.tokens or None)
     assert w.O == w.D, "the residual sum needs rows of one width"
     n, eps = args.node_size, 1e-5
     nodes = W.wide_nodes(w.depth, n, w.D, w.dtype)
@@ -325,7 +325,7 @@ def block_bench(args, np, torch, W, F):
                    "seed": 0, "buffer_sets": sets},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None if args.opt else MEASURED_TRAFFIC.get((w.name, "block_n%d" % n, kernel)),
+                     "traffic": None if (args.opt or args.tokens) else MEASURED_TRAFFIC.get((w.name, "block_n%d" % n, kernel)),
                      "kernel": kernel,
                      "kernel_ms": round(kernel_ms, 5), "algorithmic_bytes": alg,
                      "weight_row_bytes_per_token": row_bytes},
@@ -342,6 +342,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C4", help="workload: C1 C2 C2c C3 C4 C5")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="token count in place of the workload's own (same recipe; 0 = as defined)")
     ap.add_argument("--sets", type=int, default=0, help="distinct x/out buffer sets to rotate (0 = auto)")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value (repeatable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -394,7 +396,7 @@ def main():
         block_bench(args, np, torch, W, F)
         return
 
-    w = W.config(args.config, keep_f32=False)
+    w = W.config(args.config, keep_f32=False, T=args.tokens or None)
     tdt = torch.bfloat16 if w.dtype == W.DTYPE_BF16 else torch.float32
 
     def up(a):
@@ -501,7 +503,7 @@ def main():
     roofline = None
     if dom:
         launch = path_names.get(F.fff_get_option("last_path"), "?")
-        traffic = None if args.opt else MEASURED_TRAFFIC.get((w.name, launch, dom))
+        traffic = None if (args.opt or args.tokens) else MEASURED_TRAFFIC.get((w.name, launch, dom))
         roofline = {"bound": "hbm", "kernel": dom, "achieved": stages[dom]["GBps"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": stages[dom]["frac"], "traffic": traffic}
     path_gbs = alg["path"] / (ms_per_step * 1e-3) / 1e9

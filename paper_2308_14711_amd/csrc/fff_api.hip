@@ -217,7 +217,11 @@ int run_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& w
         e = launch_bucket_hist(leaf_idx, T, depth, count, offset, perm, slot_leaf, s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
     }
-    if (g_opt.bucket_kernel != 2 && bucket_onepass_ok(T, depth)) {
+    // beyond the token-chunk kernel's sizes: the leaf-range kernel reads leaf_idx once per block of
+    // leaves, which pays for many leaves; for few leaves (up to 4096) and many tokens the chunk-matrix
+    // kernels are faster (806912 tokens over 256 leaves: 102 against 224 us; 201728: 47 against 72 us)
+    const bool few_leaves = g_opt.bucket_kernel == 0 && depth <= 12;
+    if (g_opt.bucket_kernel != 2 && !few_leaves && bucket_onepass_ok(T, depth)) {
         e = launch_bucket_onepass(leaf_idx, T, depth, count, offset, perm, slot_leaf, s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
     }

@@ -38,6 +38,17 @@ def test_named_workloads(name):
     _log(name, check_against_oracle(w, out, idx))
 
 
+def test_batch_beyond_the_token_chunk_bucketing():
+    """A staged call whose batch is too large for the one-launch bucketing kernels' fast case:
+    the chunk-matrix kernels run inside fff_forward_hard."""
+    import paper_2308_14711_amd as F
+    print("\n[case] large batch T=150001 D=256 O=128 depth=6 L=8 bf16 seed 4, staged", flush=True)
+    w = W.make_layer("large_batch", 150001, 256, 128, 6, 8, W.ACT_GELU, W.DTYPE_BF16, seed=4)
+    out, idx = run_forward(w)
+    assert F.fff_get_option("last_path") == 2
+    _log("large_batch", check_against_oracle(w, out, idx))
+
+
 @pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
 def test_large_skewed_workload(path, c5_workload):
     """C5 at full size (2.4 GB of leaf weights, Zipf leaf occupancy), both launch configurations."""
@@ -197,7 +208,8 @@ def test_runs_on_a_side_stream():
                                           (11, 65536, "u"), (15, 16384, "zipf"), (20, 10000, "u"),
                                           (6, 4096, "one"), (19, 70001, "zipf"), (10, 300000, "u"),
                                           (8, 50432, "u"), (12, 131072, "zipf"), (12, 131071, "u"), (2, 63, "u"),
-                                          (9, 16385, "zipf"), (3, 65535, "one"), (3, 65536, "one")])
+                                          (9, 16385, "zipf"), (3, 65535, "one"), (3, 65536, "one"),
+                                          (8, 806912, "u"), (12, 131073, "zipf")])
 @pytest.mark.parametrize("kernel", [0, 1, 2, 3])
 def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
     import torch
