@@ -20,6 +20,7 @@ Other modes, each printing one JSON line of its own:
     --soft            the soft pass (Forward_T, all leaves) of --config, against the MFMA roofline
     --block           the pre-norm residual layer with nodes of --node-size hidden neurons on the
                       shapes of --config
+    --probe gather    the row-gather microbenchmark (random row fetches against table size)
 """
 import argparse
 import json
@@ -336,6 +337,39 @@ def block_bench(args, np, torch, W, F):
                    "max_rel_row_err": float(err.max())}}))
 
 
+def gather_probe(args, np, torch, F):
+    """The row-gather microbenchmark behind the roofline discussion (fff_probe_gather): random rows of
+    --probe-row-bytes out of zero-filled tables from well inside one XCD's L2 to beyond the last-level
+    cache, as a dependent chain with four rows in flight per 16 lanes.  One JSON line."""
+    rb = args.probe_row_bytes
+    sink = torch.zeros((4,), dtype=torch.int32, device="cuda")
+    sizes = []
+    for log_rows in range(8, 19):
+        rows = 1 << log_rows
+        if rows * rb > (1 << 30):
+            break
+        table = torch.zeros((rows * rb,), dtype=torch.uint8, device="cuda")
+        blocks, iters = 512, 32
+        res = {}
+        for dep in (0, 1):
+            for _ in range(2):
+                nbytes = F.fff_probe_gather(table, rb, 4, blocks, iters, dep, sink)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                F.fff_probe_gather(table, rb, 4, blocks, iters, dep, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            res["dependent" if dep else "independent"] = round(nbytes * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 2)
+        sizes.append({"table_MB": round(rows * rb / 1e6, 1), "rows": rows, "TBps": res})
+        del table
+    print(json.dumps({"metric": "row_gather_rate", "unit": "TB/s", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": "random %d-byte rows, 16 lanes per row, 4 rows in flight, %d blocks of 512"
+                                 % (rb, 512)},
+                      "tables": sizes}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -356,6 +390,9 @@ def main():
     ap.add_argument("--soft", action="store_true",
                     help="time the soft forward pass (Forward_T: all leaves, dense, MFMA-bound) of --config "
                          "instead of the hard one")
+    ap.add_argument("--probe", choices=["gather"], default=None,
+                    help="gather: the row-gather microbenchmark (rate of random row fetches against table size)")
+    ap.add_argument("--probe-row-bytes", type=int, default=1536)
     ap.add_argument("--block", action="store_true",
                     help="time the pre-norm residual layer with nodes of --node-size hidden neurons "
                          "(fff_forward_block) on the shapes of --config")
@@ -386,6 +423,10 @@ def main():
 
     if args.sweep in ("depth", "experts"):
         depth_sweep(args, np, torch, W, F, with_moe=args.sweep == "experts")
+        return
+
+    if args.probe == "gather":
+        gather_probe(args, np, torch, F)
         return
 
     if args.soft:

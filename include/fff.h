@@ -262,6 +262,20 @@ int fff_set_option(const char* name, int64_t value);
 int fff_get_option(const char* name, int64_t* value);
 
 /*
+ * fff_probe_gather: a measuring stick for the roofline discussion, not a step of
+ * the method.  Launches `blocks` blocks of 512 threads; every 16 lanes read,
+ * `iters` times, `rows_in_flight` (1 or 4) rows of `row_bytes` bytes picked at
+ * random from `table` (device, table_rows rows, a power of two, 16-byte aligned,
+ * row_bytes a multiple of 16; fill it with zeros) -- the access pattern of a
+ * tree walk, one row per token and level.  `dependent` non-zero makes each row
+ * index wait for the data of the previous one.  The caller times the launch;
+ * bytes moved = blocks * 32 * iters * rows_in_flight * row_bytes.  `sink`: 4
+ * bytes of device memory (never written for a table of zeros).
+ */
+int fff_probe_gather(const void* table, int64_t table_rows, int64_t row_bytes, int rows_in_flight,
+                     int64_t blocks, int iters, int dependent, void* sink, void* stream);
+
+/*
  * Waits for, sums and clears the stage events recorded since the last call:
  * ms[0..3] = total milliseconds of descent, bucketing, the leaf stage's first
  * kernel and its second (the MFMA tile path computes hidden activations, then

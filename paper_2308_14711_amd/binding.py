@@ -44,6 +44,7 @@ def lib() -> ctypes.CDLL:
         L.fff_forward_soft.argtypes = [vp] * 7 + [i32, i32, i32, vp, vp, vp, vp, i64, i64, i64, i32]
         L.fff_forward_block.argtypes = ([vp] * 3 + [ctypes.c_float] + [vp] * 8 + [i32] * 5 + [vp, vp, vp] +
                                         [i64, i64, i64, i32])
+        L.fff_probe_gather.argtypes = [vp, i64, i64, i32, i64, i32, i32, vp, vp]
         L.fff_workspace_bytes.argtypes = [i64, i32]
         L.fff_workspace_bytes.restype = ctypes.c_size_t
         L.fff_reserve_workspace.argtypes = [i64, i32]
@@ -172,6 +173,17 @@ def fff_forward_block(x, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, n
                                    int(bool(residual)), _ptr(out), _ptr(leaf_idx), _stream_handle(stream),
                                    T, D, O, _dtype_code(x)),
            "fff_forward_block")
+
+
+def fff_probe_gather(table, row_bytes: int, rows_in_flight: int, blocks: int, iters: int, dependent: bool,
+                     sink, stream=None) -> int:
+    """Row-gather microbenchmark over `table` (a zero-filled byte tensor whose size is a power of two
+    rows of row_bytes).  Returns the bytes the launch reads."""
+    _check_dense(table, sink)
+    rows = table.numel() * table.element_size() // row_bytes
+    _check(lib().fff_probe_gather(_ptr(table), rows, row_bytes, rows_in_flight, blocks, iters, int(bool(dependent)),
+                                  _ptr(sink), _stream_handle(stream)), "fff_probe_gather")
+    return blocks * 32 * iters * rows_in_flight * row_bytes
 
 
 def fff_workspace_bytes(T: int, depth: int) -> int:

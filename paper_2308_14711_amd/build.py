@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libfff_hip.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["fff_api.hip", "fff_walk.hip", "fff_bucket.hip", "fff_leaf.hip", "fff_leaf_tiles.hip",
-           "fff_token_block.hip", "fff_moe_gate.hip", "fff_soft.hip", "fff_block.hip"]
+           "fff_token_block.hip", "fff_moe_gate.hip", "fff_soft.hip", "fff_block.hip", "fff_probe.hip"]
 HEADERS = ["fff_device.h", "fff_internal.h", "fff_mfma_tile.h", os.path.join("..", "..", "include", "fff.h")]
 
 # packed fp32 VALU forms are switched off on purpose: some of them have given wrong results on

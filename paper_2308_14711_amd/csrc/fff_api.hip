@@ -464,6 +464,20 @@ int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, 
     return e == hipSuccess ? FFF_OK : set_device_error(e, "block kernel launch");
 }
 
+int fff_probe_gather(const void* table, int64_t table_rows, int64_t row_bytes, int rows_in_flight,
+                     int64_t blocks, int iters, int dependent, void* sink, void* stream) {
+    if (!table || !sink) return FFF_ERR_NULL;
+    if (table_rows < 1 || (table_rows & (table_rows - 1)) != 0 || table_rows > ((int64_t)1 << 30)) return FFF_ERR_RANGE;
+    if (row_bytes < 16 || row_bytes % 16 != 0 || row_bytes > ((int64_t)1 << 20)) return FFF_ERR_SHAPE;
+    if (blocks < 1 || blocks > ((int64_t)1 << 20) || iters < 1 || iters > (1 << 24)) return FFF_ERR_RANGE;
+    if (rows_in_flight != 1 && rows_in_flight != 4) return FFF_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(table) & 15u) != 0) return FFF_ERR_UNSUPPORTED;
+    g_last_error.clear();
+    hipError_t e = launch_gather_probe(table, table_rows, (int)(row_bytes / 16), rows_in_flight, blocks, iters,
+                                       dependent != 0, (uint32_t*)sink, (hipStream_t)stream);
+    return e == hipSuccess ? FFF_OK : set_device_error(e, "gather probe launch");
+}
+
 size_t fff_workspace_bytes(int64_t T, int depth) {
     if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH) return 0;
     return (size_t)layout_for(T, depth).total * sizeof(int32_t);

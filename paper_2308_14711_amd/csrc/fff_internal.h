@@ -119,6 +119,12 @@ hipError_t launch_forward_block(const Problem& p, const void* gamma, const void*
                                 const void* node_b2, int node_size, bool residual, int32_t* leaf_idx,
                                 hipStream_t s);
 
+// Row-gather microbenchmark (fff_probe.hip): `blocks` blocks of 512 threads, every 16 lanes read
+// `iters` times `rows_in_flight` (1 or 4) random rows of `pieces` 16-byte pieces from a table of
+// table_rows rows (a power of two).
+hipError_t launch_gather_probe(const void* table, int64_t table_rows, int pieces, int rows_in_flight,
+                               int64_t blocks, int iters, bool dependent, uint32_t* sink, hipStream_t s);
+
 // Whole forward pass in one launch, one token per lane group (any shape).
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 

@@ -140,3 +140,18 @@ def test_forward_block_rejects_bad_arguments_on_the_host(L):
     assert blk(D=12, O=12) == UNSUP                   # rows must be whole 16-byte vectors
     assert blk(D=4104, O=4104) == UNSUP               # longer than a wave holds in registers
     assert blk(out=ctypes.c_void_p((1 << 20) + 32)) == ALIAS
+
+
+def test_probe_gather_rejects_bad_arguments_on_the_host(L):
+    OK, NULL, SHAPE, RANGE, UNSUP = 0, 1, 2, 4, 5
+    p = lambda mb: ctypes.c_void_p(mb << 20)
+    probe = lambda **kw: L.fff_probe_gather(kw.get("table", p(1)), kw.get("rows", 1024), kw.get("row_bytes", 1536),
+                                            kw.get("k", 4), kw.get("blocks", 8), kw.get("iters", 2), 1,
+                                            kw.get("sink", p(64)), None)
+    assert probe(table=None) == NULL
+    assert probe(sink=None) == NULL
+    assert probe(rows=1000) == RANGE                  # a power of two
+    assert probe(row_bytes=100) == SHAPE
+    assert probe(k=3) == UNSUP
+    assert probe(blocks=0) == RANGE
+    assert probe(iters=0) == RANGE
