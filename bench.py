@@ -549,6 +549,40 @@ def main():
                     "unit": "GB/s", "frac": stages[dom]["frac"], "traffic": traffic}
     path_gbs = alg["path"] / (ms_per_step * 1e-3) / 1e9
 
+    # the fused launch fetches weight rows per token; how fast such rows can come at all depends on
+    # whether the weight table fits an L2: measure random row fetches over tables of the next smaller
+    # and next larger power-of-two row count (fff_probe_gather) and report the time the launch's
+    # gathered rows alone would take at those rates
+    if roofline and dom == "walk_fused" and w.O == w.D:
+        es = 2 if w.dtype == W.DTYPE_BF16 else 4
+        rb = w.D * es
+        if rb % 16 == 0:
+            top = F.fff_get_option("last_walk_top")
+            rows_per_token = (w.depth - top) + 2 * w.leaf_width + 1          # node rows past LDS, W1, W2, b2
+            table_rows = max(1, alg["u_node"] - ((1 << top) - 1)) + alg["u_leaf"] * (2 * w.leaf_width + 1)
+            gathered = float(w.T) * rows_per_token * rb
+            sink = torch.zeros((4,), dtype=torch.int32, device="cuda")
+            bracket = []
+            lo = 1 << max(0, int(np.floor(np.log2(table_rows))))
+            for rows in (lo, 2 * lo):
+                table = torch.zeros((rows * rb,), dtype=torch.uint8, device="cuda")
+                for _ in range(2):
+                    nbytes = F.fff_probe_gather(table, rb, 4, 512, 16, True, sink)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(5):
+                    F.fff_probe_gather(table, rb, 4, 512, 16, True, sink)
+                e1.record()
+                torch.cuda.synchronize()
+                rate = nbytes * 5 / (e0.elapsed_time(e1) * 1e-3)
+                bracket.append({"table_MB": round(rows * rb / 1e6, 1), "TBps": round(rate / 1e12, 2),
+                                "ms_for_gathered_rows": round(gathered / rate * 1e3, 4)})
+                del table
+            roofline["gather_bound"] = {"weight_rows_MB": round(table_rows * rb / 1e6, 1),
+                                        "rows_per_token": rows_per_token, "gathered_bytes": gathered,
+                                        "measured_on_tables": bracket}
+
     # parity spot check of the timed configuration against the oracle
     got_idx = idx.cpu().numpy()
     mism = np.nonzero(got_idx != ref_idx)[0]

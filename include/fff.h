@@ -246,6 +246,8 @@ int fff_release_workspace(void);
  *   "bucketing"      1 (default) = the leaf kernel visits tokens grouped by leaf,
  *                    0 = in token order (no bucketing stage)
  *   "last_path"      read it after a call: the path (1, 2, 3 or 4) fff_forward_hard took
+ *   "last_walk_top"  read it after a call: the tree levels the last descent or fused launch kept
+ *                    in LDS
  *   "last_leaf_path" read it after a staged call: 1 = its leaf stage ran the gather kernel,
  *                    2 = the two tile kernels
  *   "bucket_kernel"  0 = choose by size (default: the token-chunk kernel up to 131072 tokens

@@ -516,6 +516,7 @@ static int64_t* option_slot(const char* name) {
     if (!std::strcmp(name, "walk_top")) return &g_walk_tuning.top;
     if (!std::strcmp(name, "walk_bpc")) return &g_walk_tuning.bpc;
     if (!std::strcmp(name, "walk_prefetch")) return &g_walk_tuning.prefetch;
+    if (!std::strcmp(name, "last_walk_top")) return &g_walk_tuning.last_top;
     if (!std::strcmp(name, "bucketing")) return &g_opt.bucketing;
     if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
@@ -527,7 +528,8 @@ static int64_t* option_slot(const char* name) {
 int fff_set_option(const char* name, int64_t value) {
     int64_t* s = option_slot(name);
     if (!s || value < 0) return FFF_ERR_UNSUPPORTED;
-    if (s == &g_opt.last_path || s == &g_opt.last_leaf_path) return FFF_ERR_UNSUPPORTED;   // read-only
+    if (s == &g_opt.last_path || s == &g_opt.last_leaf_path || s == &g_walk_tuning.last_top)
+        return FFF_ERR_UNSUPPORTED;   // read-only
     *s = value;
     return FFF_OK;
 }

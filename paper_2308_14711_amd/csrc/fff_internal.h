@@ -54,6 +54,7 @@ struct WalkTuning {
     int64_t top = 0;     // k + 1 forces at most k LDS-staged levels
     int64_t bpc = 0;     // persistent blocks per compute unit
     int64_t prefetch = 0; // 1: request the next tile's token rows one iteration ahead
+    int64_t last_top = 0; // read-only: tree levels the last walk launch kept in LDS
 };
 extern WalkTuning g_walk_tuning;
 bool walk_shape_ok(const Problem& p);

@@ -368,6 +368,7 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     a.O = p.O;
     a.depth = p.depth;
     a.top = top;
+    g_walk_tuning.last_top = top;
     a.nvec = (int)(p.D / Elem<BF16>::kPerVec);
     a.L = p.L;
     a.act = p.act;
