@@ -194,3 +194,57 @@ def test_block_nan_token_is_routed_like_the_oracle_and_spoils_only_its_own_row()
     rows = np.arange(64) != 17
     assert np.isfinite(got[rows]).all() and np.array_equal(gi[rows], ref_idx[rows])
     assert np.isnan(got[17]).any()
+
+
+def test_block_captured_in_a_hip_graph_and_replayed():
+    """The call enqueues one kernel and allocates nothing: it can be captured, and every replay, with
+    eager work and synchronisations in between, must reproduce the eager result bit for bit."""
+    import torch
+    import paper_2308_14711_amd as F
+    print("\n[case] block in a HIP graph, T=2500 D=768 depth=6 n=3 L=4 seed 12", flush=True)
+    case = ("graph", 2500, 768, 768, 6, 3, 4, W.ACT_GELU, BF16, True, True)
+    name, T, D, O, depth, n, L, act, dtype, norm, residual = case
+    x, ln, nodes, leaves = _inputs(name, T, D, O, depth, n, L, act, dtype, norm, 12)
+    d_x, d_ln = _upload(x), [_upload(a) for a in ln]
+    d_nodes, d_leaves = [_upload(a) for a in nodes], [_upload(a) for a in leaves]
+    eager = torch.empty((T, O), dtype=torch.bfloat16, device="cuda")
+    eager_idx = torch.empty((T,), dtype=torch.int32, device="cuda")
+    F.fff_forward_block(d_x, d_ln[0], d_ln[1], 1e-5, *d_nodes, *d_leaves, depth, n, L, act, residual, eager, eager_idx)
+    torch.cuda.synchronize()
+    out, idx = torch.zeros_like(eager), torch.zeros_like(eager_idx)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        F.fff_forward_block(d_x, d_ln[0], d_ln[1], 1e-5, *d_nodes, *d_leaves, depth, n, L, act, residual, out, idx)
+    for rep in range(4):
+        out.fill_(float("nan"))
+        idx.fill_(-1)
+        scratch = torch.randn(1 << 16, device="cuda").sum().item()      # eager work between replays
+        assert scratch == scratch
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), "replay %d differs" % rep
+        assert torch.equal(idx, eager_idx)
+
+
+def _random_block_cases(count, seed):
+    """Seeded random shapes over both kernels: piece counts on either side of every template
+    boundary, node sizes and leaf widths around the batch sizes, with and without the
+    normalisation and the residual."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        dtype = BF16 if rng.random() < 0.6 else F32
+        per = 8 if dtype == BF16 else 4
+        pieces = int(rng.choice([rng.integers(1, 33), rng.integers(33, 129), rng.integers(129, 300)], p=[0.4, 0.4, 0.2]))
+        D = per * pieces
+        residual = bool(rng.random() < 0.5)
+        O = D if residual else per * int(rng.integers(1, 140))
+        cases.append(("rnd%02d" % i, int(rng.integers(1, 700)), D, O, int(rng.integers(0, 8)), int(rng.integers(1, 8)),
+                      int(rng.integers(1, 10)), int(rng.integers(0, 2)), dtype, bool(rng.random() < 0.7), residual))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_block_cases(24, 2024), ids=lambda c: c[0])
+def test_block_random_shapes(case):
+    print("\n[case] block %s T=%d D=%d O=%d depth=%d n=%d L=%d act=%d dtype=%d norm=%s residual=%s seed 9" % case, flush=True)
+    _check(case, seed=9)
