@@ -34,6 +34,10 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(_build.LIB):
             _build.build_library(force=True)
+        # PyTorch ships a HIP runtime of its own; the tensors and streams handed to this library
+        # live in that one.  Loading torch first makes the library bind to the same runtime instance
+        # (a process that loaded the library first ended up with two, and the second saw no device).
+        import torch  # noqa: F401
         L = ctypes.CDLL(_build.LIB)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
         L.fff_forward_hard.argtypes = [vp] * 7 + [i32, i32, i32, vp, vp, vp, i64, i64, i64, i32]

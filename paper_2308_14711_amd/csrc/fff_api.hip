@@ -90,6 +90,14 @@ Layout layout_for(int64_t T, int depth, int64_t extra_words = 0) {
     return l;
 }
 
+// Called once the host-side checks have passed: forgets the message of an earlier failure and
+// any error another user of the HIP runtime left in this thread's last-error slot, so that the
+// launch checks below report this call's errors only.
+void begin_device_call() {
+    g_last_error.clear();
+    (void)hipGetLastError();
+}
+
 int set_device_error(hipError_t e, const char* what) {
     g_last_error = std::string(what) + ": " + hipGetErrorString(e);
     return FFF_ERR_DEVICE;
@@ -297,7 +305,7 @@ int fff_forward_hard(const void* x, const void* node_w, const void* node_b, cons
     Problem p{x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, leaf_idx,
               T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
     hipStream_t s = (hipStream_t)stream;
-    g_last_error.clear();
+    begin_device_call();
 
     const int path = choose_path(p);
     g_opt.last_path = path;
@@ -337,7 +345,7 @@ int fff_descend(const void* x, const void* node_w, const void* node_b, int depth
     if (depth > 0 && (!node_w || !node_b)) return FFF_ERR_NULL;
     Problem p{x, node_w, node_b, nullptr, nullptr, nullptr, nullptr, nullptr, leaf_idx,
               T, D, 1, depth, 1, 0, dtype == FFF_BF16};
-    g_last_error.clear();
+    begin_device_call();
     hipError_t e = launch_descend(p, leaf_idx, (hipStream_t)stream);
     return e == hipSuccess ? FFF_OK : set_device_error(e, "descent kernel launch");
 }
@@ -346,7 +354,7 @@ int fff_bucket(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, in
                int32_t* perm, void* stream) {
     if (depth < 0 || depth > FFF_MAX_DEPTH || T < 0 || T > kMaxTokens) return FFF_ERR_RANGE;
     if (T > 0 && !leaf_idx) return FFF_ERR_NULL;
-    g_last_error.clear();
+    begin_device_call();
     Workspace ws;
     Layout lay;
     int rc = get_workspace(T, depth, &ws, &lay);
@@ -366,7 +374,7 @@ int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1, co
     if (overlaps(x, T * D * es, out, T * O * es)) return FFF_ERR_ALIAS;
     Problem p{x, nullptr, nullptr, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, nullptr,
               T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
-    g_last_error.clear();
+    begin_device_call();
     return run_leaf_any(p, leaf_idx, (hipStream_t)stream);
 }
 
@@ -385,7 +393,7 @@ int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b, 
     const int64_t G = (int64_t)1 << log2_experts;
     Problem p{x, nullptr, nullptr, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, nullptr,
               T, D, O, log2_experts, leaf_width, act, dtype == FFF_BF16};
-    g_last_error.clear();
+    begin_device_call();
     hipStream_t s = (hipStream_t)stream;
     Workspace ws;
     Layout lay;
@@ -424,7 +432,7 @@ int fff_forward_soft(const void* x, const void* node_w, const void* node_b, cons
     // every token meets every leaf: the intermediate matrices are T x 2^depth x (leaf_width + 1) wide
     const int64_t words = soft_scratch_words(p);
     if (words > kMaxElems / 4) return FFF_ERR_SHAPE;
-    g_last_error.clear();
+    begin_device_call();
     Workspace ws;
     Layout lay;
     if ((rc = get_workspace(0, 0, &ws, &lay, words)) != FFF_OK) return rc;
@@ -458,7 +466,7 @@ int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, 
         (ln_gamma && (!vec_ok(ln_gamma, D, p.bf16) || !vec_ok(ln_beta, D, p.bf16))) ||
         !vec_ok(leaf_b2, O, p.bf16))
         return FFF_ERR_UNSUPPORTED;
-    g_last_error.clear();
+    begin_device_call();
     hipError_t e = launch_forward_block(p, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2,
                                         node_size, residual != 0, leaf_idx, (hipStream_t)stream);
     return e == hipSuccess ? FFF_OK : set_device_error(e, "block kernel launch");
@@ -472,7 +480,7 @@ int fff_probe_gather(const void* table, int64_t table_rows, int64_t row_bytes, i
     if (blocks < 1 || blocks > ((int64_t)1 << 20) || iters < 1 || iters > (1 << 24)) return FFF_ERR_RANGE;
     if (rows_in_flight != 1 && rows_in_flight != 4) return FFF_ERR_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(table) & 15u) != 0) return FFF_ERR_UNSUPPORTED;
-    g_last_error.clear();
+    begin_device_call();
     hipError_t e = launch_gather_probe(table, table_rows, (int)(row_bytes / 16), rows_in_flight, blocks, iters,
                                        dependent != 0, (uint32_t*)sink, (hipStream_t)stream);
     return e == hipSuccess ? FFF_OK : set_device_error(e, "gather probe launch");
@@ -485,7 +493,7 @@ size_t fff_workspace_bytes(int64_t T, int depth) {
 
 int fff_reserve_workspace(int64_t T, int depth) {
     if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH) return FFF_ERR_RANGE;
-    g_last_error.clear();
+    begin_device_call();
     Workspace ws;
     Layout lay;
     return get_workspace(T, depth, &ws, &lay);

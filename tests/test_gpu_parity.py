@@ -385,3 +385,24 @@ def test_nan_tokens_go_left_and_do_not_disturb_their_neighbours(path):
     assert np.array_equal(gi[safe], ref_idx[safe])
     err = np.abs(got[safe] - ref_out[safe]).max(axis=1) / np.maximum(np.abs(ref_out[safe]).max(axis=1), 1e-30)
     assert np.isfinite(got[ok]).all() and err.max() <= TOL[W.DTYPE_BF16]
+
+
+def test_loading_the_library_before_torch_in_a_fresh_process():
+    """PyTorch brings a HIP runtime of its own; a process that loads this library first must still end
+    up with one runtime (the binding imports torch before it opens the library)."""
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import sys; sys.path.insert(0, %r); sys.path.insert(0, %r)\n"
+        "import paper_2308_14711_amd as F\n"
+        "F.lib()\n"
+        "import fff_workloads as W\n"
+        "from fff_testlib import run_forward, check_against_oracle\n"
+        "w = W.make_layer('order', 15, 153, 64, 6, 9, W.ACT_GELU, W.DTYPE_BF16, seed=1)\n"
+        "out, idx = run_forward(w)\n"
+        "print(check_against_oracle(w, out, idx))\n"
+    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), os.path.dirname(os.path.abspath(__file__)))
+    print("\n[case] fresh process: library first, torch second", flush=True)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
