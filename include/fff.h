@@ -197,9 +197,10 @@ int fff_forward_soft(const void* x, const void* node_w, const void* node_b,
  *   residual           non-zero adds x (needs O == D, else FFF_ERR_SHAPE)
  *   out [T, O]; may be x itself (same pointer, O == D), any other overlap is
  *   FFF_ERR_ALIAS; leaf_idx [T] int32 may be NULL
- *   Rows must be 16-byte aligned with D and O multiples of 8 (bf16) or 4 (fp32),
- *   at most 4096 (bf16) or 2048 (fp32) features: else FFF_ERR_UNSUPPORTED.
- *   Needs no workspace.  Other arguments, ownership, asynchrony and errors as
+ *   Rows that are 16-byte aligned with D and O multiples of 8 (bf16) or 4 (fp32)
+ *   and at most 4096 (bf16) or 2048 (fp32) features take the vector kernels;
+ *   any other shape an element-wise kernel (correct, slow; option
+ *   "last_block_kernel" reads 1 or 2 after a call).  Needs no workspace.  Other arguments, ownership, asynchrony and errors as
  *   for fff_forward_hard.
  */
 int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, float ln_eps,
@@ -248,6 +249,8 @@ int fff_release_workspace(void);
  *   "last_path"      read it after a call: the path (1, 2, 3 or 4) fff_forward_hard took
  *   "last_walk_top"  read it after a call: the tree levels the last descent or fused launch kept
  *                    in LDS
+ *   "last_block_kernel" read it after fff_forward_block: 1 = a vector kernel ran, 2 = the
+ *                    element-wise one
  *   "last_leaf_path" read it after a staged call: 1 = its leaf stage ran the gather kernel,
  *                    2 = the two tile kernels
  *   "bucket_kernel"  0 = choose by size (default: the token-chunk kernel up to 131072 tokens

@@ -32,6 +32,7 @@ struct Options {
     int64_t bucket_kernel = 0;   // 0 auto, 1 leaf-range kernel, 2 chunk-matrix kernels, 3 token-chunk kernel
     int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
     int64_t last_leaf_path = 0;  // read-only: leaf stage of the last staged call (1 gather kernel, 2 tile kernels)
+    int64_t last_block_kernel = 0; // read-only: 1 = fff_forward_block ran a vector kernel, 2 = the element-wise one
     int64_t token_max_T = 512;   // batches up to this many tokens (6x where no fused launch fits) go one block per token
 } g_opt;
 
@@ -462,13 +463,16 @@ int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, 
     if (leaf_idx && overlaps(leaf_idx, T * 4, out, T * O * es)) return FFF_ERR_ALIAS;
     Problem p{x, nullptr, nullptr, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, leaf_idx,
               T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
-    if (!block_shape_ok(x, out, leaf_w1, leaf_w2, D, O, p.bf16) || !vec_ok(node_w1, D, p.bf16) ||
-        (ln_gamma && (!vec_ok(ln_gamma, D, p.bf16) || !vec_ok(ln_beta, D, p.bf16))) ||
-        !vec_ok(leaf_b2, O, p.bf16))
-        return FFF_ERR_UNSUPPORTED;
+    // rows of whole 16-byte pieces, short enough for a lane group or a wave to hold, take the vector
+    // kernels; everything else the element-wise one
+    const bool vector_rows = block_shape_ok(x, out, leaf_w1, leaf_w2, D, O, p.bf16) &&
+                             (depth == 0 || vec_ok(node_w1, D, p.bf16)) &&
+                             (!ln_gamma || (vec_ok(ln_gamma, D, p.bf16) && vec_ok(ln_beta, D, p.bf16))) &&
+                             vec_ok(leaf_b2, O, p.bf16);
     begin_device_call();
+    g_opt.last_block_kernel = vector_rows ? 1 : 2;
     hipError_t e = launch_forward_block(p, ln_gamma, ln_beta, ln_eps, node_w1, node_b1, node_w2, node_b2,
-                                        node_size, residual != 0, leaf_idx, (hipStream_t)stream);
+                                        node_size, residual != 0, leaf_idx, (hipStream_t)stream, vector_rows);
     return e == hipSuccess ? FFF_OK : set_device_error(e, "block kernel launch");
 }
 
@@ -530,13 +534,15 @@ static int64_t* option_slot(const char* name) {
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
     if (!std::strcmp(name, "last_path")) return &g_opt.last_path;
     if (!std::strcmp(name, "last_leaf_path")) return &g_opt.last_leaf_path;
+    if (!std::strcmp(name, "last_block_kernel")) return &g_opt.last_block_kernel;
     return nullptr;
 }
 
 int fff_set_option(const char* name, int64_t value) {
     int64_t* s = option_slot(name);
     if (!s || value < 0) return FFF_ERR_UNSUPPORTED;
-    if (s == &g_opt.last_path || s == &g_opt.last_leaf_path || s == &g_walk_tuning.last_top)
+    if (s == &g_opt.last_path || s == &g_opt.last_leaf_path || s == &g_walk_tuning.last_top ||
+        s == &g_opt.last_block_kernel)
         return FFF_ERR_UNSUPPORTED;   // read-only
     *s = value;
     return FFF_OK;

@@ -450,6 +450,66 @@ template <bool BF16, bool TWO> hipError_t pick_group(const BlockArgs& a, int nv,
     return run_group<BF16, 8, TWO>(a, blocks, s);
 }
 
+// Any row length and alignment: one wave (one block) per token, element loads, the normalised
+// value of an element recomputed from x, gamma and beta wherever it is used, the leaf's hidden
+// activations through LDS.  Correct for every shape the vector kernels do not take; not fast.
+constexpr int kGenericMaxLeafWidth = 4096;
+
+template <bool BF16>
+__global__ __launch_bounds__(kWave) void block_generic_kernel(const BlockArgs a) {
+    __shared__ float hid[kGenericMaxLeafWidth];
+    const int lane = threadIdx.x;
+    const int64_t D = a.D, O = a.O;
+    const int64_t first_leaf_row = ((int64_t)1 << a.depth) - 1;
+    for (int64_t t = blockIdx.x; t < a.T; t += gridDim.x) {
+        float mean = 0.0f, rstd = 1.0f;
+        if (a.gamma) {
+            float s = 0.0f;
+            for (int64_t k = lane; k < D; k += kWave) s += Elem<BF16>::load(a.x, t * D + k);
+            mean = group_sum<kWave>(s) / (float)D;
+            float q = 0.0f;
+            for (int64_t k = lane; k < D; k += kWave) {
+                const float c = Elem<BF16>::load(a.x, t * D + k) - mean;
+                q = fmaf(c, c, q);
+            }
+            rstd = 1.0f / sqrtf(group_sum<kWave>(q) / (float)D + a.eps);
+        }
+        auto z = [&](int64_t k) {
+            const float v = Elem<BF16>::load(a.x, t * D + k);
+            return a.gamma ? fmaf((v - mean) * rstd, Elem<BF16>::load(a.gamma, k), Elem<BF16>::load(a.beta, k)) : v;
+        };
+        auto dot = [&](const void* w, int64_t row) {
+            float acc = 0.0f;
+            for (int64_t k = lane; k < D; k += kWave) acc = fmaf(z(k), Elem<BF16>::load(w, row * D + k), acc);
+            return group_sum<kWave>(acc);
+        };
+        int64_t node = 0;
+        for (int m = 0; m < a.depth; ++m) {
+            float logit = Elem<BF16>::load(a.node_b2, node);
+            for (int j = 0; j < a.n; ++j) {
+                const int64_t neuron = node * a.n + j;
+                const float h = activate(dot(a.node_w1, neuron) + Elem<BF16>::load(a.node_b1, neuron), a.act);
+                logit = fmaf(Elem<BF16>::load(a.node_w2, neuron), h, logit);
+            }
+            node = 2 * node + (logit >= 0.0f ? 2 : 1);
+        }
+        const int64_t leaf = node - first_leaf_row;
+        if (a.leaf_idx && lane == 0) a.leaf_idx[t] = (int32_t)leaf;
+        __syncthreads();                       // the previous token's readers of hid are done
+        for (int r = 0; r < a.L; ++r) {
+            const float h = activate(dot(a.leaf_w1, leaf * a.L + r) + Elem<BF16>::load(a.leaf_b1, leaf * a.L + r), a.act);
+            if (lane == 0) hid[r] = h;
+        }
+        __syncthreads();
+        for (int64_t o = lane; o < O; o += kWave) {
+            float y = Elem<BF16>::load(a.leaf_b2, leaf * O + o);
+            for (int r = 0; r < a.L; ++r) y = fmaf(hid[r], Elem<BF16>::load(a.leaf_w2, (leaf * a.L + r) * O + o), y);
+            if (a.residual) y += Elem<BF16>::load(a.x, t * D + o);
+            Elem<BF16>::store(a.out, t * O + o, y);
+        }
+    }
+}
+
 template <bool BF16, int NV> hipError_t run(const BlockArgs& a, int64_t blocks, hipStream_t s) {
     block_kernel<BF16, NV><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
     return hipGetLastError();
@@ -478,7 +538,7 @@ bool block_shape_ok(const void* x, const void* out, const void* leaf_w1, const v
 hipError_t launch_forward_block(const Problem& p, const void* gamma, const void* beta, float eps,
                                 const void* node_w1, const void* node_b1, const void* node_w2,
                                 const void* node_b2, int node_size, bool residual, int32_t* leaf_idx,
-                                hipStream_t s) {
+                                hipStream_t s, bool vector_rows) {
     if (p.T == 0) return hipSuccess;
     BlockArgs a;
     a.x = p.x;
@@ -503,6 +563,12 @@ hipError_t launch_forward_block(const Problem& p, const void* gamma, const void*
     a.act = p.act;
     a.residual = residual ? 1 : 0;
     a.eps = eps;
+    if (!vector_rows) {
+        int64_t gblocks = p.T < 256 * 32 ? p.T : 256 * 32;
+        if (p.bf16) block_generic_kernel<true><<<dim3((unsigned)gblocks), dim3(kWave), 0, s>>>(a);
+        else block_generic_kernel<false><<<dim3((unsigned)gblocks), dim3(kWave), 0, s>>>(a);
+        return hipGetLastError();
+    }
     const int per = p.bf16 ? 8 : 4;
     const int64_t pieces = (p.D > p.O ? p.D : p.O) / per;
     const int nv = (int)((pieces + kWave - 1) / kWave);

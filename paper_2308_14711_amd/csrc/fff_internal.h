@@ -112,13 +112,14 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
 
 // Forward_I with nodes of `node_size` hidden neurons on the layer-normalised token (gamma null:
 // no normalisation), plus the token itself when `residual` (fff_block.hip); one launch, a wave per
-// token.  p.node_w / p.node_b are not used.  Needs block_shape_ok.
+// token.  p.node_w / p.node_b are not used.  vector_rows needs block_shape_ok (and 16-byte aligned
+// rows of every other tensor); without it an element-wise kernel takes any shape.
 bool block_shape_ok(const void* x, const void* out, const void* leaf_w1, const void* leaf_w2, int64_t D,
                     int64_t O, bool bf16);
 hipError_t launch_forward_block(const Problem& p, const void* gamma, const void* beta, float eps,
                                 const void* node_w1, const void* node_b1, const void* node_w2,
                                 const void* node_b2, int node_size, bool residual, int32_t* leaf_idx,
-                                hipStream_t s);
+                                hipStream_t s, bool vector_rows = true);
 
 // Row-gather microbenchmark (fff_probe.hip): `blocks` blocks of 512 threads, every 16 lanes read
 // `iters` times `rows_in_flight` (1 or 4) random rows of `pieces` 16-byte pieces from a table of

@@ -137,8 +137,6 @@ def test_forward_block_rejects_bad_arguments_on_the_host(L):
     assert blk(depth=25) == RANGE
     assert blk(O=8) == SHAPE                          # the residual sum needs rows of one width
     assert blk(act=9) == UNSUP
-    assert blk(D=12, O=12) == UNSUP                   # rows must be whole 16-byte vectors
-    assert blk(D=4104, O=4104) == UNSUP               # longer than a wave holds in registers
     assert blk(out=ctypes.c_void_p((1 << 20) + 32)) == ALIAS
 
 

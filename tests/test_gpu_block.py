@@ -32,6 +32,7 @@ CASES = [
     ("group_ragged8",   257,   800,  1000, 3,     2, 3,  W.ACT_RELU,  BF16,  True,  False),
     ("group_max_f32",   200,   512,  384,  3,     6, 7,  W.ACT_GELU,  F32,   True,  False),
     ("group_f32_six",   150,   384,  384,  5,     1, 2,  W.ACT_RELU,  F32,   False, True),
+    ("wide_leaf",       20,    40,   40,   1,     2, 300, W.ACT_RELU, F32,   True,  True),
 ]
 
 
@@ -138,6 +139,27 @@ def test_block_in_place_and_without_an_index_buffer():
     _check(("in_place", 900, 768, 768, 6, 3, 4, W.ACT_GELU, BF16, True, True), in_place=True)
     _check(("in_place_f32", 300, 128, 128, 4, 2, 2, W.ACT_RELU, F32, True, True), in_place=True)
     _check(("no_idx", 900, 768, 768, 6, 3, 4, W.ACT_GELU, BF16, True, True), want_idx=False)
+
+
+GENERIC = [
+    # shapes the vector kernels do not take: the element-wise kernel
+    ("odd_f32",        130,  50,   7,    4, 3, 3,  W.ACT_GELU, F32,  True,  False),
+    ("odd_bf16",       99,   77,   77,   3, 2, 2,  W.ACT_RELU, BF16, True,  True),
+    ("too_long_bf16",  40,   4104, 4104, 2, 2, 1,  W.ACT_GELU, BF16, True,  True),
+    ("too_long_f32",   33,   2052, 16,   2, 1, 5,  W.ACT_RELU, F32,  False, False),
+    ("odd_out_only",   200,  64,   30,   5, 4, 6,  W.ACT_GELU, BF16, True,  False),
+    ("wide_leaf_odd",  20,   42,   42,   1, 2, 300, W.ACT_RELU, F32, True,  True),
+]
+
+
+@pytest.mark.parametrize("case", GENERIC, ids=[c[0] for c in GENERIC])
+def test_block_shapes_for_the_element_wise_kernel(case):
+    import paper_2308_14711_amd as F
+    print("\n[case] block %s T=%d D=%d O=%d depth=%d n=%d L=%d act=%d dtype=%d norm=%s residual=%s seed 5" % case, flush=True)
+    _check(case)
+    assert F.fff_get_option("last_block_kernel") == 2
+    _check(("vector_again", 70, 64, 64, 3, 2, 2, W.ACT_RELU, F32, True, True))
+    assert F.fff_get_option("last_block_kernel") == 1
 
 
 def test_block_two_relu_neurons_route_like_the_linear_node():
