@@ -17,6 +17,8 @@ equal-training-width dense feedforward on the same GPU for the speedup.
 Other modes, each printing one JSON line of its own:
     --sweep depth     small-batch latency against tree depth (the paper's speed experiment)
     --sweep experts   the same with the mixture-of-experts lookup (one engaged expert) beside it
+    --sweep widths    the paper's grid of small networks (training widths 16..128 x leaf sizes 1..8,
+                      batch 2048) beside the dense feedforward network of the same width
     --soft            the soft pass (Forward_T, all leaves) of --config, against the MFMA roofline
     --block           the pre-norm residual layer with nodes of --node-size hidden neurons on the
                       shapes of --config
@@ -189,6 +191,78 @@ def depth_sweep(args, np, torch, W, F, with_moe=False):
         "linear_fit_graph": {"us_per_level": round(float(slope), 3), "us_at_depth_0": round(float(icpt), 2),
                              "max_abs_residual_us": round(float(np.abs(resid).max()), 2)},
         "sweep": rows}))
+
+
+def width_sweep(args, np, torch, W, F):
+    """The paper's small-network grid at its inference batch (section "Explorative evaluation",
+    the table of training widths 16..128 against leaf sizes 1..8; testing batch 2048): MNIST-shaped
+    inputs (784 features, 10 outputs, fp32, ReLU), for every training width w and leaf size l the
+    FFF of depth log2(w / l) timed beside the dense feedforward network of width w (torch addmm +
+    relu + addmm on the same GPU), both replayed from a HIP graph of 20 calls; every FFF cell is
+    checked against the oracle."""
+    import oracle
+    T, D, O = args.sweep_batch if args.sweep_batch != 256 else 2048, 784, 10
+    per_graph = 20
+    reps = max(1, args.steps // per_graph)
+
+    def graph_us(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(per_graph):
+                fn()
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / (reps * per_graph)
+
+    rows = []
+    for width in (16, 32, 64, 128):
+        x32 = torch.randn((T, D), device="cuda")
+        w1 = torch.randn((D, width), device="cuda") / 28.0
+        b1 = torch.zeros((width,), device="cuda")
+        w2 = torch.randn((width, O), device="cuda") / np.sqrt(width)
+        b2 = torch.zeros((O,), device="cuda")
+        ff_us = graph_us(lambda: torch.addmm(b2, torch.relu(torch.addmm(b1, x32, w1)), w2))
+        for L in (8, 4, 2, 1):
+            d = int(np.log2(width // L))
+            w = W.make_layer("width_sweep", T, D, O, d, L, W.ACT_RELU, W.DTYPE_F32, seed=width + L,
+                             x_dist="uniform01", node_b="centred0.1")
+            dev = {k: torch.from_numpy(np.ascontiguousarray(w.device_array(k))).cuda() for k in W.TENSORS}
+            out = torch.empty((T, O), dtype=torch.float32, device="cuda")
+            idx = torch.empty((T,), dtype=torch.int32, device="cuda")
+            F.fff_reserve_workspace(T, d)
+
+            def call():
+                F.fff_forward_hard(dev["x"], dev["node_w"] if d else None, dev["node_b"] if d else None,
+                                   dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"], dev["leaf_b2"], d, L, w.act, out, idx)
+
+            us = graph_us(call)
+            ins = [np.ascontiguousarray(w.device_array(k)) for k in W.TENSORS]
+            ref_out, ref_idx, margin = oracle.forward_hard(*ins, d, L, w.act)
+            got_idx = idx.cpu().numpy()
+            mism = np.nonzero(got_idx != ref_idx)[0]
+            keep = got_idx == ref_idx
+            got = out.cpu().numpy().astype(np.float64)
+            scale = np.maximum(np.abs(ref_out[keep]).max(axis=1), 1e-30)
+            rows.append({"training_width": width, "leaf_size": L, "depth": d, "fff_us_per_call": round(us, 2),
+                         "dense_ff_us_per_call": round(ff_us, 2), "speedup": round(ff_us / us, 2),
+                         "launch_path": int(F.fff_get_option("last_path")),
+                         "leaves_hit": int(np.unique(ref_idx).size),
+                         "idx_mismatch_outside_margin": int((margin[mism] >= 1e-4).sum()),
+                         "max_rel_row_err": float((np.abs(got[keep] - ref_out[keep]).max(axis=1) / scale).max())})
+    print(json.dumps({"metric": "fff_vs_dense_ff_small_networks", "unit": "us per call", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "dtype": "f32",
+                      "data": "synthetic",
+                      "config": {"workload": "width sweep: batch %d, 784 inputs, 10 outputs, fp32, ReLU, training widths "
+                                             "16..128 x leaf sizes 8..1" % T},
+                      "sweep": rows}))
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
@@ -383,7 +457,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
-    ap.add_argument("--sweep", choices=["depth", "experts"], default=None,
+    ap.add_argument("--sweep", choices=["depth", "experts", "widths"], default=None,
                     help="depth: the small-batch latency sweep (time per call against tree depth) instead of a "
                          "workload; experts: the same sweep with the mixture-of-experts lookup (one engaged "
                          "expert) timed beside the tree lookup on the same leaves")
@@ -420,6 +494,10 @@ def main():
     for kv in args.opt:
         k, v = kv.split("=")
         F.fff_set_option(k, int(v))
+
+    if args.sweep == "widths":
+        width_sweep(args, np, torch, W, F)
+        return
 
     if args.sweep in ("depth", "experts"):
         depth_sweep(args, np, torch, W, F, with_moe=args.sweep == "experts")
