@@ -254,9 +254,10 @@ int fff_release_workspace(void);
  *   "last_leaf_path" read it after a staged call: 1 = its leaf stage ran the gather kernel,
  *                    2 = the two tile kernels
  *   "bucket_kernel"  0 = choose by size (default: the token-chunk kernel up to 131072 tokens
- *                    and 4096 leaves; beyond that the chunk-matrix kernels for up to 4096
+ *                    and 4096 leaves; beyond that the segment kernels for up to 4096
  *                    leaves, else the leaf-range kernel up to 2^21 tokens and 2^19 leaves,
- *                    else the chunk-matrix kernels), 1 = the leaf-range kernel when the
+ *                    else the chunk-matrix kernels), 4 = the segment kernels when the sizes
+ *                    allow them, 1 = the leaf-range kernel when the
  *                    sizes allow it, 2 = always the chunk-matrix kernels, 3 = the token-chunk
  *                    kernel when the sizes allow it
  *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages

@@ -29,7 +29,7 @@ struct Options {
     int64_t leaf_path = 0;       // 0 auto (MFMA tiles when the shape allows), 1 gather kernel only
     int64_t bucketing = 1;       // 0: leaf kernel visits tokens in token order
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
-    int64_t bucket_kernel = 0;   // 0 auto, 1 leaf-range kernel, 2 chunk-matrix kernels, 3 token-chunk kernel
+    int64_t bucket_kernel = 0;   // 0 auto, 1 leaf-range kernel, 2 chunk-matrix kernels, 3 token-chunk kernel, 4 segment kernels
     int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
     int64_t last_leaf_path = 0;  // read-only: leaf stage of the last staged call (1 gather kernel, 2 tile kernels)
     int64_t last_block_kernel = 0; // read-only: 1 = fff_forward_block ran a vector kernel, 2 = the element-wise one
@@ -227,9 +227,14 @@ int run_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& w
         return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
     }
     // beyond the token-chunk kernel's sizes: the leaf-range kernel reads leaf_idx once per block of
-    // leaves, which pays for many leaves; for few leaves (up to 4096) and many tokens the chunk-matrix
-    // kernels are faster (806912 tokens over 256 leaves: 102 against 224 us; 201728: 47 against 72 us)
+    // leaves, which pays for many leaves; for few leaves (up to 4096) and many tokens the segment
+    // kernels (count / scan / scatter over segments of 1024 tokens) are faster, and so are the
+    // chunk-matrix kernels (806912 tokens over 256 leaves: 102 against 224 us; 201728: 47 against 72 us)
     const bool few_leaves = g_opt.bucket_kernel == 0 && depth <= 12;
+    if ((few_leaves || g_opt.bucket_kernel == 4) && bucket_segments_ok(T, depth, ws)) {
+        e = launch_bucket_segments(leaf_idx, T, depth, ws, count, offset, perm, slot_leaf, s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
+    }
     if (g_opt.bucket_kernel != 2 && !few_leaves && bucket_onepass_ok(T, depth)) {
         e = launch_bucket_onepass(leaf_idx, T, depth, count, offset, perm, slot_leaf, s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");

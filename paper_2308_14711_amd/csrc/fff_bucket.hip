@@ -150,12 +150,21 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(int32_t* __restrict__
     if (leaf < n_leaves) {
         int32_t* row = M + leaf * n_chunks;
         int32_t carry = 0;
-        for (int64_t c0 = 0; c0 < n_chunks; c0 += kWave) {
-            const int64_t c = c0 + lane;
-            const int32_t v = c < n_chunks ? row[c] : 0;
-            const int32_t inc = wave_incl_scan(v, lane);
-            if (c < n_chunks) row[c] = carry + inc - v;
-            carry += __shfl(inc, kWave - 1, kWave);
+        // four steps of 64 chunks at a time: their loads are requested together
+        for (int64_t c0 = 0; c0 < n_chunks; c0 += 4 * kWave) {
+            int32_t v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t c = c0 + u * kWave + lane;
+                v[u] = c < n_chunks ? row[c] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t c = c0 + u * kWave + lane;
+                const int32_t inc = wave_incl_scan(v[u], lane);
+                if (c < n_chunks) row[c] = carry + inc - v[u];
+                carry += __shfl(inc, kWave - 1, kWave);
+            }
         }
         if (lane == 0) __hip_atomic_store(count + leaf, carry, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -508,6 +517,114 @@ hipError_t launch_bucket_hist(const int32_t* leaf_idx, int64_t T, int depth, int
         bucket_hist_kernel<false><<<dim3((unsigned)blocks), dim3(1024), sizeof(unsigned long long) * (size_t)NL, s>>>(
             leaf_idx, T, NL, chunk, vec, count, offset, perm, slot_leaf);
     return hipGetLastError();
+}
+
+// ---- many tokens over few leaves (up to 4096): segments of 1024 tokens, a wave each ----------
+//
+//   count    a wave histograms its segment in LDS and writes M[leaf][segment] for every leaf (so M
+//            needs no clearing)
+//   scan     bucket_scan_kernel, as for the chunk-matrix kernels
+//   scatter  a wave walks its segment again in the same order, 64 tokens at a time: a token's
+//            position is the running start of its leaf (LDS, initialised to offset[leaf] +
+//            M[leaf][segment]) plus the number of lower lanes of the batch with the same leaf (from
+//            one ballot per bit of the leaf index); the last lane of every leaf in the batch stores
+//            the new running start.  One wave per
+//            block, so a batch's reads of the running starts precede its writes by program order.
+constexpr int kSegTokens = 1024;
+constexpr int kSegMaxLeaves = 4096;
+
+__global__ __launch_bounds__(kWave) void seg_count_kernel(const int32_t* __restrict__ leaf_idx, int64_t T,
+                                                          int n_leaves, int64_t n_segs, int32_t* __restrict__ M) {
+    __shared__ int32_t hist[kSegMaxLeaves];
+    const int lane = threadIdx.x;
+    const int64_t seg = blockIdx.x;
+    for (int j = lane; j < n_leaves; j += kWave) hist[j] = 0;
+    __syncthreads();
+    const int64_t t0 = seg * kSegTokens;
+    int32_t mine[kSegTokens / kWave];          // all requested before the first is used
+#pragma unroll
+    for (int k = 0; k < kSegTokens / kWave; ++k) {
+        const int64_t t = t0 + (int64_t)k * kWave + lane;
+        mine[k] = t < T ? leaf_idx[t] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < kSegTokens / kWave; ++k)
+        if ((uint32_t)mine[k] < (uint32_t)n_leaves) atomicAdd(&hist[mine[k]], 1);   // a caller's bad index is skipped, not followed
+    __syncthreads();
+    for (int j = lane; j < n_leaves; j += kWave) M[(int64_t)j * n_segs + seg] = hist[j];
+}
+
+__global__ __launch_bounds__(kWave) void seg_scatter_kernel(const int32_t* __restrict__ leaf_idx, int64_t T,
+                                                            int n_leaves, int n_bits, int64_t n_segs,
+                                                            const int32_t* __restrict__ M,
+                                                            const int32_t* __restrict__ offset,
+                                                            int32_t* __restrict__ perm,
+                                                            int32_t* __restrict__ slot_leaf) {
+    __shared__ int32_t start[kSegMaxLeaves];
+    const int lane = threadIdx.x;
+    const int64_t seg = blockIdx.x;
+    for (int j = lane; j < n_leaves; j += kWave) start[j] = offset[j] + M[(int64_t)j * n_segs + seg];
+    __syncthreads();
+    const int64_t t0 = seg * kSegTokens;
+    // the segment's leaf ids are requested at once: the batches below depend on each other through
+    // the running starts, and a wave alone on its SIMD has nothing else to hide a load behind
+    int32_t mine[kSegTokens / kWave];
+#pragma unroll
+    for (int k = 0; k < kSegTokens / kWave; ++k) {
+        const int64_t t = t0 + (int64_t)k * kWave + lane;
+        mine[k] = t < T ? leaf_idx[t] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < kSegTokens / kWave; ++k) {
+        const int64_t t = t0 + (int64_t)k * kWave + lane;
+        const int32_t leaf = mine[k];
+        const bool valid = (uint32_t)leaf < (uint32_t)n_leaves;
+        // the lanes of the batch that hold my leaf: one ballot per bit of the index, each lane keeps
+        // the lanes that agree with it on that bit
+        uint64_t same = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 12; ++b) {                          // kSegMaxLeaves = 2^12
+            if (b < n_bits) {
+                const bool bit = (leaf >> b) & 1;
+                const uint64_t m = __ballot(bit);
+                same &= bit ? m : ~m;
+            }
+        }
+        if (valid) {
+            const int below = __popcll(same & lanes_below(lane));
+            const bool last = lane == kWave - 1 || (same >> (lane + 1)) == 0;
+            const int32_t pos = start[leaf] + below;
+            perm[pos] = (int32_t)t;
+            if (slot_leaf) slot_leaf[pos] = leaf;
+            if (last) start[leaf] = pos + 1;
+        }
+    }
+}
+
+bool bucket_segments_ok(int64_t T, int depth, const Workspace& ws) {
+    const int64_t NL = (int64_t)1 << depth;
+    const int64_t n_segs = (T + kSegTokens - 1) / kSegTokens;
+    return T > 0 && NL <= kSegMaxLeaves && n_segs <= ws.n_chunks && n_segs < ((int64_t)1 << 31);
+}
+
+hipError_t launch_bucket_segments(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,
+                                  int32_t* count, int32_t* offset, int32_t* perm, int32_t* slot_leaf,
+                                  hipStream_t s) {
+    const int64_t NL = (int64_t)1 << depth;
+    const int64_t n_segs = (T + kSegTokens - 1) / kSegTokens;
+    hipError_t e;
+    seg_count_kernel<<<dim3((unsigned)n_segs), dim3(kWave), 0, s>>>(leaf_idx, T, (int)NL, n_segs, ws.chunk_cnt);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    bucket_scan_kernel<<<dim3((unsigned)((NL + 15) / 16)), dim3(1024), 0, s>>>(
+        ws.chunk_cnt, NL, n_segs, kTileRows, count ? count : ws.count, offset ? offset : ws.offset, ws.tile_off,
+        ws.ctrl);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (perm) {
+        seg_scatter_kernel<<<dim3((unsigned)n_segs), dim3(kWave), 0, s>>>(leaf_idx, T, (int)NL, depth, n_segs, ws.chunk_cnt,
+                                                                         offset ? offset : ws.offset, perm, slot_leaf);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,

@@ -76,6 +76,13 @@ bool bucket_hist_ok(int64_t T, int depth);
 hipError_t launch_bucket_hist(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, int32_t* offset,
                               int32_t* perm, int32_t* slot_leaf, hipStream_t s);
 
+// K2 for many tokens over few leaves (up to 4096): segments of 1024 tokens, three launches (count, scan,
+// scatter); the matrix region of the workspace must hold a column per segment (bucket_segments_ok).
+bool bucket_segments_ok(int64_t T, int depth, const Workspace& ws);
+hipError_t launch_bucket_segments(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws,
+                                  int32_t* count, int32_t* offset, int32_t* perm, int32_t* slot_leaf,
+                                  hipStream_t s);
+
 // K3 + K4: leaf networks and output rows.
 //   order == nullptr: slot i is token i.  Otherwise slot i is token order[i].
 hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order,

@@ -210,7 +210,7 @@ def test_runs_on_a_side_stream():
                                           (8, 50432, "u"), (12, 131072, "zipf"), (12, 131071, "u"), (2, 63, "u"),
                                           (9, 16385, "zipf"), (3, 65535, "one"), (3, 65536, "one"),
                                           (8, 806912, "u"), (12, 131073, "zipf")])
-@pytest.mark.parametrize("kernel", [0, 1, 2, 3])
+@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4])
 def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
     import torch
     import paper_2308_14711_amd as F
