@@ -153,3 +153,24 @@ def test_probe_gather_rejects_bad_arguments_on_the_host(L):
     assert probe(k=3) == UNSUP
     assert probe(blocks=0) == RANGE
     assert probe(iters=0) == RANGE
+
+
+def test_header_is_plain_c99_and_links_from_c(tmp_path):
+    """The boundary is a C ABI: a C99 translation unit includes include/fff.h with -pedantic, links
+    against the library and calls it (host-side checks only: no GPU is touched)."""
+    import subprocess
+    import paper_2308_14711_amd as F
+    src = tmp_path / "client.c"
+    src.write_text(
+        '#include "fff.h"\n#include <stdio.h>\n'
+        'int main(void) {\n'
+        '    printf("%d|%s|", fff_version(), fff_status_string(FFF_ERR_ALIAS));\n'
+        '    printf("%d|", fff_forward_hard(0, 0, 0, 0, 0, 0, 0, 3, 2, 0, 0, 0, 0, 4, 16, 8, FFF_BF16));\n'
+        '    printf("%d\\n", (int)(fff_workspace_bytes(1000, 4) > 0));\n'
+        '    return 0;\n}\n')
+    exe = tmp_path / "client"
+    libdir = os.path.dirname(F.library_path())
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe), "-L", libdir, "-lfff_hip", "-Wl,-rpath," + libdir])
+    out = subprocess.check_output([str(exe)], text=True).strip().split("|")
+    assert int(out[0]) == F.fff_version() and out[1] == "out overlaps x" and out[2] == "1" and out[3] == "1"
