@@ -11,8 +11,8 @@
 // holds 4 x 2 accumulator tiles of v_mfma_f32_16x16x32_bf16.  The logits never reach memory: a
 // wave reduces its 32 experts per token with DPP row steps, the waves meet in LDS, and the block
 // writes one (value, index) candidate per token; a second small kernel picks the best candidate
-// per token over the expert blocks.  Blocks that share a token tile are adjacent in the grid, so
-// the tile stays in L2 while the gating matrix streams from HBM once.
+// per token over the expert blocks.  The token tiles of one expert block run back to back on one
+// XCD, so the gating matrix streams from HBM once while the (small) token rows stay cached.
 #include "fff_device.h"
 #include "fff_internal.h"
 #include "fff_mfma_tile.h"
@@ -31,6 +31,7 @@ struct GateArgs {
     int32_t* cand_idx;           // [T][n_eblocks]
     int64_t T, G;
     int D, n_eblocks;
+    int64_t n_ttiles;
 };
 
 // (v, i) <- the better of (v, i) and (v2, i2): larger value, then lower index
@@ -56,8 +57,12 @@ __global__ __launch_bounds__(256) void moe_gate_kernel(const GateArgs a) {
     __shared__ int32_t part_i[4][kGateTokens];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int j = lane & 15, kg = lane >> 4;
-    const int eb = (int)(blockIdx.x % a.n_eblocks);
-    const int64_t t0 = (int64_t)(blockIdx.x / a.n_eblocks) * kGateTokens;
+    // the token tiles of one expert block run back to back on one XCD (whose L2 then serves the
+    // expert block's rows to all of them): logical block = expert block * token tiles + token tile
+    const int64_t lb = xcd_contiguous_block();
+    if (lb >= (int64_t)a.n_eblocks * a.n_ttiles) return;      // padding of the grid to a multiple of 8
+    const int eb = (int)(lb / a.n_ttiles);
+    const int64_t t0 = (lb % a.n_ttiles) * kGateTokens;
     const int64_t e0 = (int64_t)eb * kGateExperts;
     const int D = a.D;
 
@@ -157,7 +162,8 @@ hipError_t launch_moe_gate(const void* x, const void* gate_w, const void* gate_b
     a.T = T;
     a.G = n_experts;
     a.D = (int)D;
-    const int64_t blocks = (T + kGateTokens - 1) / kGateTokens * a.n_eblocks;
+    a.n_ttiles = (T + kGateTokens - 1) / kGateTokens;
+    const int64_t blocks = (a.n_ttiles * a.n_eblocks + kXcds - 1) / kXcds * kXcds;
     moe_gate_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
