@@ -45,7 +45,7 @@ MEASURED_TRAFFIC = {
     ("C3", "staged", "leaf_hidden"): 82.7e6,
     ("C3", "staged", "leaf_output"): 85.9e6,
     ("C5", "fused", "walk_fused"): 1645.3e6,   # profiles/large_skewed_fff_fused_C5.md
-    ("C3", "block_n4", "block_group_kernel"): 860.5e6,   # profiles/vit_block_layer_wide_nodes_C3.md
+    ("C3", "block_n4", "block_group_kernel"): 818.9e6,   # profiles/vit_block_layer_wide_nodes_C3.md
 }
 
 

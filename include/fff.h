@@ -251,6 +251,11 @@ int fff_release_workspace(void);
  *                    in LDS
  *   "last_block_kernel" read it after fff_forward_block: 1 = a vector kernel ran, 2 = the
  *                    element-wise one
+ *   "block_top"      fff_forward_block, rows of up to 128 pieces, 32768 tokens and more: the
+ *                    hidden-neuron rows of the top node levels are kept in LDS by persistent
+ *                    blocks; k + 1 = at most k such levels, 0 = as many as fit (default).
+ *                    The results do not depend on it, bit for bit.
+ *   "last_block_top" read it after fff_forward_block: the levels its launch kept in LDS
  *   "last_leaf_path" read it after a staged call: 1 = its leaf stage ran the gather kernel,
  *                    2 = the two tile kernels
  *   "bucket_kernel"  0 = choose by size (default: the token-chunk kernel up to 131072 tokens

@@ -540,6 +540,8 @@ static int64_t* option_slot(const char* name) {
     if (!std::strcmp(name, "last_path")) return &g_opt.last_path;
     if (!std::strcmp(name, "last_leaf_path")) return &g_opt.last_leaf_path;
     if (!std::strcmp(name, "last_block_kernel")) return &g_opt.last_block_kernel;
+    if (!std::strcmp(name, "block_top")) return &g_block_tuning.top;
+    if (!std::strcmp(name, "last_block_top")) return &g_block_tuning.last_top;
     return nullptr;
 }
 
@@ -547,7 +549,7 @@ int fff_set_option(const char* name, int64_t value) {
     int64_t* s = option_slot(name);
     if (!s || value < 0) return FFF_ERR_UNSUPPORTED;
     if (s == &g_opt.last_path || s == &g_opt.last_leaf_path || s == &g_walk_tuning.last_top ||
-        s == &g_opt.last_block_kernel)
+        s == &g_opt.last_block_kernel || s == &g_block_tuning.last_top)
         return FFF_ERR_UNSUPPORTED;   // read-only
     *s = value;
     return FFF_OK;

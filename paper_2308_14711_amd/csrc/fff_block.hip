@@ -18,6 +18,7 @@
 #include "fff_internal.h"
 
 namespace fff {
+BlockTuning g_block_tuning;
 namespace {
 
 struct BlockArgs {
@@ -36,6 +37,7 @@ struct BlockArgs {
     int32_t* leaf_idx;     // may be null
     int64_t T;
     int D, O, depth, n, L, act, residual;
+    int top;               // node levels whose rows the lane-group kernel keeps in LDS
     float eps;
 };
 
@@ -254,9 +256,10 @@ __global__ __launch_bounds__(256) void block_group_kernel(const BlockArgs a) {
     typedef Piece<BF16> P;
     constexpr int E = P::kElems;
     constexpr int kLpt = 16;                            // lanes per token
-    constexpr int kGroups = 256 / kLpt;                 // tokens a block holds at a time
     constexpr int kRows = NV >= 6 ? 2 : 4;              // weight rows requested together per token
     static_assert(BF16 || !TWO, "fp32 rows are kept as they are");
+    constexpr int kGroups = 256 / kLpt;                 // tokens a block holds at a time
+    extern __shared__ uint4 top_rows[];                 // node_w1 rows of the levels above a.top
     const int sub = threadIdx.x & (kLpt - 1);
     const int quad = threadIdx.x & 3;
     const int grp_in_block = threadIdx.x / kLpt;
@@ -273,6 +276,16 @@ __global__ __launch_bounds__(256) void block_group_kernel(const BlockArgs a) {
         vd[i] = okd[i] ? v : pd - 1;
         vo[i] = oko[i] ? v : po - 1;
     }
+
+    // The hidden-neuron rows of the top levels are the first rows of node_w1 (heap order): one
+    // copy per block, then every token of the block reads them at LDS latency.
+    if (a.top > 0) {
+        const int staged = a.n * ((1 << a.top) - 1) * pd;
+        for (int i = threadIdx.x; i < staged; i += 256) top_rows[i] = ((const uint4*)a.node_w1)[i];
+        __syncthreads();
+    }
+    const auto lds_row = [&](int64_t row, int i) { return top_rows[(int)row * pd + vd[i]]; };
+    const auto mem_row = [&](int64_t row, int i) { return ((const uint4*)a.node_w1)[row * pd + vd[i]]; };
 
     for (int64_t t = (int64_t)blockIdx.x * kGroups + grp_in_block; t < a.T; t += (int64_t)gridDim.x * kGroups) {
         const uint4* xrow = (const uint4*)a.x + t * pd;
@@ -333,15 +346,15 @@ __global__ __launch_bounds__(256) void block_group_kernel(const BlockArgs a) {
 
         int64_t node = 0;
         // nodes of one hidden neuron (the usual case) go a row at a time
-        for (int m = 0; m < (a.n != 1 ? 0 : a.depth); ++m) {
+        const auto narrow_level = [&](const auto& load_row) {
             uint4 w[NV];
 #pragma unroll
-            for (int i = 0; i < NV; ++i) w[i] = ((const uint4*)a.node_w1)[node * pd + vd[i]];
+            for (int i = 0; i < NV; ++i) w[i] = load_row(node, i);
             const float pre = group_sum<kLpt>(dotz(w)) + Elem<BF16>::load(a.node_b1, node);
             const float logit = fmaf(Elem<BF16>::load(a.node_w2, node), activate(pre, a.act), Elem<BF16>::load(a.node_b2, node));
             node = 2 * node + (logit >= 0.0f ? 2 : 1);
-        }
-        for (int m = 0; m < (a.n == 1 ? 0 : a.depth); ++m) {
+        };
+        const auto wide_level = [&](const auto& load_row) {
             float logit = Elem<BF16>::load(a.node_b2, node);
             for (int j0 = 0; j0 < a.n; j0 += kRows) {
                 // the rows of up to kRows hidden neurons are requested together; past the node's last
@@ -353,7 +366,7 @@ __global__ __launch_bounds__(256) void block_group_kernel(const BlockArgs a) {
                 for (int j = 0; j < kRows; ++j) {
                     const int64_t row = node * a.n + j0 + (j < cnt ? j : cnt - 1);
 #pragma unroll
-                    for (int i = 0; i < NV; ++i) w[j][i] = ((const uint4*)a.node_w1)[row * pd + vd[i]];
+                    for (int i = 0; i < NV; ++i) w[j][i] = load_row(row, i);
                 }
                 float sj[kRows];
 #pragma unroll
@@ -372,6 +385,13 @@ __global__ __launch_bounds__(256) void block_group_kernel(const BlockArgs a) {
             }
             // the 16 lanes of a token hold the same bits, so they take the same child
             node = 2 * node + (logit >= 0.0f ? 2 : 1);
+        };
+        if (a.n == 1) {
+            for (int m = 0; m < a.top; ++m) narrow_level(lds_row);
+            for (int m = a.top; m < a.depth; ++m) narrow_level(mem_row);
+        } else {
+            for (int m = 0; m < a.top; ++m) wide_level(lds_row);
+            for (int m = a.top; m < a.depth; ++m) wide_level(mem_row);
         }
         const int64_t leaf = node - first_leaf_row;
         if (a.leaf_idx && sub == 0) a.leaf_idx[t] = (int32_t)leaf;
@@ -438,16 +458,53 @@ __global__ __launch_bounds__(256) void block_group_kernel(const BlockArgs a) {
     }
 }
 
-template <bool BF16, int NV, bool TWO> hipError_t run_group(const BlockArgs& a, int64_t blocks, hipStream_t s) {
-    block_group_kernel<BF16, NV, TWO><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
+// Launch shape of the lane-group kernel: blocks of 256 threads, 16 tokens at a time.  Small
+// batches: a block per 16 tokens, no staging.  From 32768 tokens on: two persistent blocks per
+// compute unit, each keeping the hidden-neuron rows of as many top levels as fit its half of the
+// LDS (blocks of 512 threads with all of it were measured too: slower on every shape tried).
+template <bool BF16, int NV, bool TWO> hipError_t run_group(BlockArgs a, hipStream_t s) {
+    const DeviceInfo di = device_info();
+    int64_t blocks = (a.T + 15) / 16;
+    const int64_t cap = 256 * 16;
+    const int64_t row_bytes = (int64_t)a.D * (BF16 ? 2 : 4);
+    size_t lds_limit = di.lds_per_block;
+    if (lds_limit > 144 * 1024) lds_limit = 144 * 1024;
+    const size_t lds_cap = lds_limit / 2;
+    int top = 0;
+    if (a.T >= 32768) {
+        while (top < a.depth && top < 12 &&
+               (size_t)(a.n * (((int64_t)1 << (top + 1)) - 1) * row_bytes) <= lds_cap)
+            ++top;
+    }
+    if (g_block_tuning.top > 0 && g_block_tuning.top - 1 < top) top = (int)g_block_tuning.top - 1;
+    g_block_tuning.last_top = top;
+    a.top = top;
+    const size_t lds_bytes = (size_t)(a.n * (((int64_t)1 << top) - 1) * row_bytes);
+    if (top > 0) {
+        const int64_t resident = (int64_t)di.cus * 2;
+        if (blocks > resident) blocks = resident;
+    } else if (blocks > cap) {
+        blocks = cap;
+    }
+    auto kern = block_group_kernel<BF16, NV, TWO>;
+    // raise this instantiation's dynamic LDS limit once per device (the limit only ever grows)
+    static size_t lds_allowed_on[64];
+    size_t& lds_allowed = lds_allowed_on[di.dev];
+    if (lds_bytes > 48 * 1024 && lds_bytes > lds_allowed) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_limit);
+        if (e != hipSuccess) return e;
+        lds_allowed = lds_limit;
+    }
+    kern<<<dim3((unsigned)blocks), dim3(256), lds_bytes, s>>>(a);
     return hipGetLastError();
 }
 
-template <bool BF16, bool TWO> hipError_t pick_group(const BlockArgs& a, int nv, int64_t blocks, hipStream_t s) {
-    if (nv <= 2) return run_group<BF16, 2, TWO>(a, blocks, s);
-    if (nv <= 4) return run_group<BF16, 4, TWO>(a, blocks, s);
-    if (nv <= 6) return run_group<BF16, 6, TWO>(a, blocks, s);
-    return run_group<BF16, 8, TWO>(a, blocks, s);
+template <bool BF16, bool TWO> hipError_t pick_group(const BlockArgs& a, int nv, hipStream_t s) {
+    if (nv <= 2) return run_group<BF16, 2, TWO>(a, s);
+    if (nv <= 4) return run_group<BF16, 4, TWO>(a, s);
+    if (nv <= 6) return run_group<BF16, 6, TWO>(a, s);
+    return run_group<BF16, 8, TWO>(a, s);
 }
 
 // Any row length and alignment: one wave (one block) per token, element loads, the normalised
@@ -562,7 +619,9 @@ hipError_t launch_forward_block(const Problem& p, const void* gamma, const void*
     a.L = p.L;
     a.act = p.act;
     a.residual = residual ? 1 : 0;
+    a.top = 0;
     a.eps = eps;
+    g_block_tuning.last_top = 0;
     if (!vector_rows) {
         int64_t gblocks = p.T < 256 * 32 ? p.T : 256 * 32;
         if (p.bf16) block_generic_kernel<true><<<dim3((unsigned)gblocks), dim3(kWave), 0, s>>>(a);
@@ -578,12 +637,10 @@ hipError_t launch_forward_block(const Problem& p, const void* gamma, const void*
     const int64_t cap = 256 * 16;
     if (blocks > cap) blocks = cap;
     if (pieces <= kGroupMaxPieces) {
-        // sixteen lanes a token, sixteen tokens a block
-        int64_t gblocks = (p.T + 15) / 16;
-        if (gblocks > cap) gblocks = cap;
+        // sixteen lanes a token
         const int gnv = (int)((pieces + 15) / 16);
-        if (!p.bf16) return pick_group<false, false>(a, gnv, gblocks, s);
-        return gamma ? pick_group<true, true>(a, gnv, gblocks, s) : pick_group<true, false>(a, gnv, gblocks, s);
+        if (!p.bf16) return pick_group<false, false>(a, gnv, s);
+        return gamma ? pick_group<true, true>(a, gnv, s) : pick_group<true, false>(a, gnv, s);
     }
     return p.bf16 ? pick<true>(a, nv, blocks, s) : pick<false>(a, nv, blocks, s);
 }

@@ -48,6 +48,14 @@ hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 // Descent + leaf network + output row in one launch; needs fused_shape_ok(p).
 hipError_t launch_walk_fused(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 // Experiment switches of the walk kernel (0 = the built-in choice).
+// Compute units, the dynamic LDS a block may ask for, and the index of the current device (cached).
+struct DeviceInfo {
+    int cus = 0;
+    size_t lds_per_block = 0;
+    int dev = 0;
+};
+DeviceInfo device_info();
+
 struct WalkTuning {
     int64_t tpg = 0;     // tokens per lane group
     int64_t block = 0;   // threads per block
@@ -121,6 +129,11 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
 // no normalisation), plus the token itself when `residual` (fff_block.hip); one launch, a wave per
 // token.  p.node_w / p.node_b are not used.  vector_rows needs block_shape_ok (and 16-byte aligned
 // rows of every other tensor); without it an element-wise kernel takes any shape.
+struct BlockTuning {
+    int64_t top = 0;      // k + 1 forces at most k LDS-staged node levels
+    int64_t last_top = 0; // read-only: node levels the last fff_forward_block launch kept in LDS
+};
+extern BlockTuning g_block_tuning;
 bool block_shape_ok(const void* x, const void* out, const void* leaf_w1, const void* leaf_w2, int64_t D,
                     int64_t O, bool bf16);
 hipError_t launch_forward_block(const Problem& p, const void* gamma, const void* beta, float eps,

@@ -293,14 +293,6 @@ bool vec_ok(const void* p, int64_t row_elems, bool bf16) {
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && row_elems % per == 0;
 }
 
-namespace {
-
-struct DeviceInfo {
-    int cus = 0;
-    size_t lds_per_block = 0;
-    int dev = 0;
-};
-
 DeviceInfo device_info() {
     static DeviceInfo info[64];
     int dev = 0;
@@ -319,7 +311,6 @@ DeviceInfo device_info() {
     return info[dev];
 }
 
-}  // namespace
 WalkTuning g_walk_tuning;
 namespace {
 

@@ -141,6 +141,49 @@ def test_block_in_place_and_without_an_index_buffer():
     _check(("no_idx", 900, 768, 768, 6, 3, 4, W.ACT_GELU, BF16, True, True), want_idx=False)
 
 
+STAGED = [
+    # from 32768 tokens on the lane-group kernel keeps the top node levels' rows in LDS (last column:
+    # how many levels)
+    # name,              T,     D,    O,    depth, n, L, act,         dtype, norm,  residual, top
+    ("staged_vit",       40000, 768,  768,  8,     4, 8, W.ACT_GELU,  BF16,  True,  True,  3),
+    ("staged_one",       33000, 768,  768,  9,     1, 1, W.ACT_RELU,  BF16,  False, True,  5),
+    ("staged_f32",       32768, 200,  40,   6,     3, 5, W.ACT_GELU,  F32,   True,  False, 4),
+    ("staged_whole",     35003, 64,   64,   4,     2, 2, W.ACT_RELU,  BF16,  True,  True,  4),
+    ("staged_widest",    32800, 1000, 1000, 5,     2, 3, W.ACT_GELU,  BF16,  True,  False, 4),
+]
+
+
+@pytest.mark.parametrize("case", STAGED, ids=[c[0] for c in STAGED])
+def test_block_with_top_levels_in_lds(case):
+    import torch
+    import paper_2308_14711_amd as F
+    print("\n[case] block %s T=%d D=%d O=%d depth=%d n=%d L=%d act=%d dtype=%d norm=%s residual=%s seed 5, %d levels in LDS" % case, flush=True)
+    top = case[-1]
+    _check(case[:-1])
+    assert F.fff_get_option("last_block_kernel") == 1
+    assert F.fff_get_option("last_block_top") == top
+    # the same launch with fewer levels, and with every level read from memory, gives the same bits
+    name, T, D, O, depth, n, L, act, dtype, norm, residual = case[:-1]
+    x, ln, nodes, leaves = _inputs(name, T, D, O, depth, n, L, act, dtype, norm, 5)
+    d = [_upload(x)] + [None if a is None else _upload(a) for a in ln]
+    d_w = [_upload(a) for a in nodes] + [_upload(a) for a in leaves]
+    bits = torch.int16 if dtype == BF16 else torch.int32
+    outs = []
+    try:
+        for top_option, expect in ((0, top), (2, 1), (1, 0)):
+            F.fff_set_option("block_top", top_option)
+            out = torch.empty((T, O), dtype=d[0].dtype, device="cuda")
+            idx = torch.empty((T,), dtype=torch.int32, device="cuda")
+            F.fff_forward_block(d[0], d[1], d[2], 1e-5, *d_w, depth, n, L, act, residual, out, idx)
+            torch.cuda.synchronize()
+            assert F.fff_get_option("last_block_top") == expect
+            outs.append((out, idx))
+    finally:
+        F.fff_set_option("block_top", 0)
+    for out, idx in outs[1:]:
+        assert torch.equal(outs[0][1], idx) and torch.equal(outs[0][0].view(bits), out.view(bits))
+
+
 GENERIC = [
     # shapes the vector kernels do not take: the element-wise kernel
     ("odd_f32",        130,  50,   7,    4, 3, 3,  W.ACT_GELU, F32,  True,  False),
