@@ -224,8 +224,10 @@ int fff_release_workspace(void);
  * Tuning and test switches (process-wide; not thread-safe against running calls).
  *   "leaf_path"      staged path only: 0 = the MFMA tile kernels when the shape allows them
  *                    (bf16, 3 <= leaf_width <= 32, D % 8 == 0, O % 8 == 0, 16-byte aligned
- *                    rows), else the gather kernel (default); 1 = always the gather kernel;
- *                    2 = the tile kernels also for leaf_width 1 and 2
+ *                    rows) and a leaf sees at least 8 tokens on average or is wider than 8
+ *                    neurons, else the gather kernel (default); 1 = always the gather kernel;
+ *                    2 = the tile kernels whenever the shape allows them, also for
+ *                    leaf_width 1 and 2
  *   "path"           0 = choose by shape and batch size (default), 1 = one fused launch
  *                    (walk, leaf network and output row per token, tokens streamed through
  *                    persistent blocks; leaf_width <= 8), 2 = staged (descent, bucketing,
@@ -235,9 +237,9 @@ int fff_release_workspace(void);
  *                    16-byte vectors); a path the shape does not allow falls back to one it
  *                    does.  The default takes 4 for batches of up to "token_max_T" tokens
  *                    (6 times that where leaf_width > 8 rules out the fused launch), then
- *                    staged when a leaf sees >= 32 tokens on average, T > 8192 and the leaves
+ *                    staged when a leaf sees >= 3 tokens on average, T > 8192 and the leaves
  *                    are wide (leaf_width >= 8, or >= 4 with more than 5 MB of leaf weights
- *                    in total), else fused
+ *                    in total, or 3 with more than 16 MB), else fused
  *   "token_max_T"    see "path" (default 512)
  *   "walk_tpg", "walk_block", "walk_top", "walk_bpc", "walk_prefetch"
  *                    experiment switches of the fused/descent kernel (tokens per lane
@@ -257,7 +259,10 @@ int fff_release_workspace(void);
  *                    The results do not depend on it, bit for bit.
  *   "last_block_top" read it after fff_forward_block: the levels its launch kept in LDS
  *   "last_leaf_path" read it after a staged call: 1 = its leaf stage ran the gather kernel,
- *                    2 = the two tile kernels
+ *                    2 = the two tile kernels, 3 = both, each on its share of the tiles
+ *   "leaf_split"     staged leaf stage on the tile kernels: 1..16 = a tile (16 consecutive
+ *                    slots of the bucketed order) with at least this many runs of equal leaf
+ *                    goes to the gather kernel instead; 0 (default) or above 16 = no split
  *   "bucket_kernel"  0 = choose by size (default: the token-chunk kernel up to 131072 tokens
  *                    and 4096 leaves; beyond that the segment kernels for up to 4096
  *                    leaves, else the leaf-range kernel up to 2^21 tokens and 2^19 leaves,

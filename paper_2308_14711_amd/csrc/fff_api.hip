@@ -26,12 +26,13 @@ std::mutex g_mu;
 
 struct Options {
     int64_t path = 0;            // 0 auto, 1 fused walk, 2 staged, 3 generic one-wave-per-token
-    int64_t leaf_path = 0;       // 0 auto (MFMA tiles when the shape allows), 1 gather kernel only
+    int64_t leaf_path = 0;       // 0 auto, 1 gather kernel only, 2 MFMA tiles whenever the shape allows
     int64_t bucketing = 1;       // 0: leaf kernel visits tokens in token order
     int64_t stage_timing = 0;    // 1: bracket the stages of fff_forward_hard with events
     int64_t bucket_kernel = 0;   // 0 auto, 1 leaf-range kernel, 2 chunk-matrix kernels, 3 token-chunk kernel, 4 segment kernels
     int64_t last_path = 0;       // read-only: the path the last fff_forward_hard call took
-    int64_t last_leaf_path = 0;  // read-only: leaf stage of the last staged call (1 gather kernel, 2 tile kernels)
+    int64_t last_leaf_path = 0;  // read-only: leaf stage of the last staged call (1 gather kernel, 2 tile kernels, 3 both)
+    int64_t leaf_split = 0;      // 1..16: tiles of 16 slots with that many runs of equal leaf go to the gather kernel
     int64_t last_block_kernel = 0; // read-only: 1 = fff_forward_block ran a vector kernel, 2 = the element-wise one
     int64_t token_max_T = 512;   // batches up to this many tokens (6x where no fused launch fits) go one block per token
 } g_opt;
@@ -208,14 +209,19 @@ int choose_path(const Problem& p) {
     if (!fused_ok && !staged_ok) return token_ok ? kPathToken : kPathGeneric;
     if (!staged_ok) return kPathFused;
     if (!fused_ok) return kPathStaged;
-    // grouping pays once a leaf is visited by enough tokens to share its rows and is either wide
-    // (8 neurons) or, from 4 neurons on, the leaf weights together outgrow the 4 MB L2 of one XCD,
-    // which the fused launch relies on for its per-token row fetches (measured on 768-wide rows:
-    // depth 8 ties at 6 neurons, depth 10 at 4, depth 4 only at 8)
-    const int64_t tokens_per_leaf = p.T >> p.depth;
+    // grouping pays once a leaf is either wide (8 neurons) or, from 4 neurons on, the leaf weights
+    // together outgrow the 4 MB L2 of one XCD, which the fused launch relies on for its per-token
+    // row fetches (measured on 768-wide rows: depth 8 ties at 6 neurons, depth 10 at 4, depth 4 only
+    // at 8) -- and a leaf is visited by a few tokens on average: in bucket order the tokens of a leaf
+    // find its rows in cache, so the staged path stays ahead down to 3 tokens a leaf (50432 tokens,
+    // 768-wide rows, 8 neurons, depth 13 and 14: 151 and 218 us against 224 and 260 fused; 16384
+    // tokens, 4096-wide rows, 4 neurons, depth 12: 233 against 285); below that (the skewed workload:
+    // half a token a leaf) the single launch wins again
     const int64_t leaf_bytes = ((int64_t)1 << p.depth) * (p.L * (p.D + p.O) + p.O) * (p.bf16 ? 2 : 4);
-    const bool wide = p.L >= 8 || (p.L >= 4 && leaf_bytes >= (int64_t)5 << 20);
-    return (wide && tokens_per_leaf >= 32 && p.T > 8192) ? kPathStaged : kPathFused;
+    const bool wide = p.L >= 8 || (p.L >= 4 && leaf_bytes >= (int64_t)5 << 20) ||
+                      (p.L == 3 && leaf_bytes >= (int64_t)16 << 20);   // 3 neurons, depth 11: 89 against 100 us
+    const bool visited = p.depth < 40 && p.T >= ((int64_t)3 << p.depth);
+    return (wide && visited && p.T > 8192) ? kPathStaged : kPathFused;
 }
 
 // K2 with whichever kernel set takes the sizes; outputs may be null (then workspace arrays are used).
@@ -261,12 +267,25 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
     const int rc = run_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, ws.slot_leaf, s);
     if (rc != FFF_OK) return rc;
     if (timed) stage_mark(s);
-    // the MFMA tile path pays once a leaf has a few neurons; for 1-2 the VALU gather kernel is leaner
-    const bool tiles = g_opt.leaf_path != 1 && tiles_shape_ok(p) && (p.L >= 3 || g_opt.leaf_path == 2);
-    g_opt.last_leaf_path = tiles ? 2 : 1;
-    if (tiles)
-        e = launch_leaf_tiles(p, ws.slot_leaf, ws.perm, ws.hidden, s, timed ? stage_mark : nullptr);
-    else {
+    // the MFMA tile path pays once a leaf has a few neurons (for 1-2 the VALU gather kernel is leaner)
+    // and a tile of 16 slots holds few different leaves: from 8 tokens a leaf on average (measured
+    // on 768-wide rows, 50432 tokens, 8 neurons: 12 tokens a leaf 118 us tiles against 128 gather,
+    // 6 tokens a leaf 168 against 151; leaves of more than 8 neurons always, the gather kernel
+    // needs twice the time there)
+    const bool filled = p.L > 8 || (p.depth < 40 && p.T >= ((int64_t)8 << p.depth));
+    const bool tiles = g_opt.leaf_path != 1 && tiles_shape_ok(p) &&
+                       (g_opt.leaf_path == 2 || (p.L >= 3 && filled));
+    // On request ("leaf_split"), tiles whose 16 slots hold that many different leaves or more are
+    // left to the gather kernel, one lane group per token, and the tile kernels keep the tiles of
+    // well-filled buckets.  Not the default: on every shape measured one of the two kernels alone
+    // was at least as fast as the pair.
+    const int split = tiles && gather_takes_split(p) && g_opt.leaf_split >= 1 && g_opt.leaf_split <= 16
+                          ? (int)g_opt.leaf_split : 0;
+    g_opt.last_leaf_path = tiles ? (split ? 3 : 2) : 1;
+    if (tiles) {
+        e = launch_leaf_tiles(p, ws.slot_leaf, ws.perm, ws.hidden, s, timed ? stage_mark : nullptr, split);
+        if (e == hipSuccess && split) e = launch_leaf_gather(p, leaf_idx, ws.perm, s, ws.slot_leaf, split);
+    } else {
         e = launch_leaf_gather(p, leaf_idx, ws.perm, s);
         if (timed) stage_mark(s);
     }
@@ -526,6 +545,7 @@ int fff_release_workspace(void) {
 static int64_t* option_slot(const char* name) {
     if (!name) return nullptr;
     if (!std::strcmp(name, "leaf_path")) return &g_opt.leaf_path;
+    if (!std::strcmp(name, "leaf_split")) return &g_opt.leaf_split;
     if (!std::strcmp(name, "path")) return &g_opt.path;
     if (!std::strcmp(name, "token_max_T")) return &g_opt.token_max_T;
     if (!std::strcmp(name, "walk_tpg")) return &g_walk_tuning.tpg;

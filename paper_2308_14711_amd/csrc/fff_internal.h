@@ -93,13 +93,18 @@ hipError_t launch_bucket_segments(const int32_t* leaf_idx, int64_t T, int depth,
 
 // K3 + K4: leaf networks and output rows.
 //   order == nullptr: slot i is token i.  Otherwise slot i is token order[i].
+//   split > 0 (needs order, the leaf of every slot, and gather_takes_split(p)): only the tiles of 16
+//   consecutive slots with at least `split` runs of equal leaf are handled, the rest is left to
+//   launch_leaf_tiles with the same value.
+bool gather_takes_split(const Problem& p);
 hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order,
-                              hipStream_t s);
+                              hipStream_t s, const int32_t* slot_leaf = nullptr, int split = 0);
 // MFMA tile path over tokens grouped by leaf (perm, and the leaf of every slot); needs tiles_shape_ok(p).
 // Two launches (hidden activations, output rows); `between`, if given, is called between them.
 bool tiles_shape_ok(const Problem& p);
+//   split > 0: tiles with at least `split` runs of equal leaf are skipped (launch_leaf_gather's).
 hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const int32_t* perm, void* hidden,
-                             hipStream_t s, void (*between)(hipStream_t) = nullptr);
+                             hipStream_t s, void (*between)(hipStream_t) = nullptr, int split = 0);
 
 // Whole forward pass in one launch, one block per token: the small-batch path, built for the
 // latency of the dependent loads rather than for throughput; needs token_shape_ok(p).

@@ -19,14 +19,27 @@ __global__ __launch_bounds__(256) void leaf_gather_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ w1, const void* __restrict__ b1,
     const void* __restrict__ w2, const void* __restrict__ b2, const int32_t* __restrict__ leaf_idx,
     const int32_t* __restrict__ order, int L, int act, int64_t T, int nvec, int64_t O, int out_vec,
-    void* __restrict__ out) {
+    void* __restrict__ out, const int32_t* __restrict__ slot_leaf, int split) {
     constexpr int kGroups = 256 / LPT;
     constexpr int VE = Elem<BF16>::kPerVec;
+    static_assert(16 % kGroups == 0, "the slots of a block lie in one tile of 16");
     __shared__ float hs[kGroups][kMaxLeafWidthGather];
     const int sub = threadIdx.x % LPT;
     const int g = threadIdx.x / LPT;
     // in bucket order consecutive slots share a leaf: keep them on one XCD
-    const int64_t slot = (order ? xcd_contiguous_block() : (int64_t)blockIdx.x) * kGroups + g;
+    const int64_t first_slot = (order ? xcd_contiguous_block() : (int64_t)blockIdx.x) * kGroups;
+    if (split > 0) {
+        // Shared with the tile kernels: only tiles (16 consecutive slots) with at least `split`
+        // runs of equal leaf are this kernel's; the whole block leaves otherwise.  Every wave
+        // counts the runs of the block's tile for itself.
+        const int lane = threadIdx.x & 63;
+        const int64_t ts = first_slot / 16 * 16 + (lane & 15);
+        const int32_t lf = ts < T ? slot_leaf[ts] : -1;
+        const int32_t prev = __shfl_up(lf, 1, 16);
+        const uint32_t changes = (uint32_t)__ballot(lane > 0 && lane < 16 && lf >= 0 && lf != prev);
+        if (__popc(changes) + 1 < split) return;
+    }
+    const int64_t slot = first_slot + g;
     const bool live = slot < T;
     const int64_t t = live ? (order ? (int64_t)order[slot] : slot) : 0;
     const int64_t leaf = leaf_idx[t];
@@ -160,14 +173,15 @@ __global__ __launch_bounds__(256) void fused_generic_kernel(
 }
 
 template <bool BF16, int LPT, int NV>
-static hipError_t run_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order, hipStream_t s) {
+static hipError_t run_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order, hipStream_t s,
+                             const int32_t* slot_leaf, int split) {
     constexpr int kGroups = 256 / LPT;
     const int nvec = (int)(p.D / Elem<BF16>::kPerVec);
     const int out_vec = vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
     const int64_t blocks = ((p.T + kGroups - 1) / kGroups + kXcds - 1) / kXcds * kXcds;
     leaf_gather_kernel<BF16, LPT, NV><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(
         (const uint4*)p.x, (const uint4*)p.leaf_w1, p.leaf_b1, p.leaf_w2, p.leaf_b2, leaf_idx, order,
-        p.L, p.act, p.T, nvec, p.O, out_vec, p.out);
+        p.L, p.act, p.T, nvec, p.O, out_vec, p.out, slot_leaf, split);
     return hipGetLastError();
 }
 
@@ -183,23 +197,35 @@ static hipError_t run_generic(const Problem& p, const int32_t* leaf_in, const in
 }
 
 template <bool BF16>
-static hipError_t dispatch_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order, hipStream_t s) {
+static hipError_t dispatch_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order, hipStream_t s,
+                                  const int32_t* slot_leaf, int split) {
     const int64_t nvec = p.D / Elem<BF16>::kPerVec;
     const bool fast = vec_ok(p.x, p.D, BF16) && vec_ok(p.leaf_w1, p.D, BF16) && p.L <= kMaxLeafWidthGather;
-    if (fast && nvec <= 16) return run_gather<BF16, 16, 1>(p, leaf_idx, order, s);
-    if (fast && nvec <= 32) return run_gather<BF16, 16, 2>(p, leaf_idx, order, s);
-    if (fast && nvec <= 64) return run_gather<BF16, 16, 4>(p, leaf_idx, order, s);
-    if (fast && nvec <= 96) return run_gather<BF16, 16, 6>(p, leaf_idx, order, s);
-    if (fast && nvec <= 128) return run_gather<BF16, 16, 8>(p, leaf_idx, order, s);
-    if (fast && nvec <= 256) return run_gather<BF16, 64, 4>(p, leaf_idx, order, s);
-    if (fast && nvec <= 512) return run_gather<BF16, 64, 8>(p, leaf_idx, order, s);
-    if (fast && nvec <= 1024) return run_gather<BF16, 64, 16>(p, leaf_idx, order, s);
+    if (fast && nvec <= 16) return run_gather<BF16, 16, 1>(p, leaf_idx, order, s, slot_leaf, split);
+    if (fast && nvec <= 32) return run_gather<BF16, 16, 2>(p, leaf_idx, order, s, slot_leaf, split);
+    if (fast && nvec <= 64) return run_gather<BF16, 16, 4>(p, leaf_idx, order, s, slot_leaf, split);
+    if (fast && nvec <= 96) return run_gather<BF16, 16, 6>(p, leaf_idx, order, s, slot_leaf, split);
+    if (fast && nvec <= 128) return run_gather<BF16, 16, 8>(p, leaf_idx, order, s, slot_leaf, split);
+    if (fast && nvec <= 256) return run_gather<BF16, 64, 4>(p, leaf_idx, order, s, slot_leaf, split);
+    if (fast && nvec <= 512) return run_gather<BF16, 64, 8>(p, leaf_idx, order, s, slot_leaf, split);
+    if (fast && nvec <= 1024) return run_gather<BF16, 64, 16>(p, leaf_idx, order, s, slot_leaf, split);
+    if (split > 0) return hipErrorInvalidValue;   // callers ask gather_takes_split() first
     return run_generic<BF16>(p, leaf_idx, order, nullptr, s);
 }
 
-hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order, hipStream_t s) {
+// the shapes whose gather launch can leave tiles to the tile kernels (the lane-group kernels)
+bool gather_takes_split(const Problem& p) {
+    const int per = p.bf16 ? 8 : 4;
+    return vec_ok(p.x, p.D, p.bf16) && vec_ok(p.leaf_w1, p.D, p.bf16) && p.L <= kMaxLeafWidthGather &&
+           p.D / per <= 1024;
+}
+
+hipError_t launch_leaf_gather(const Problem& p, const int32_t* leaf_idx, const int32_t* order, hipStream_t s,
+                              const int32_t* slot_leaf, int split) {
     if (p.T == 0) return hipSuccess;
-    return p.bf16 ? dispatch_gather<true>(p, leaf_idx, order, s) : dispatch_gather<false>(p, leaf_idx, order, s);
+    if (split > 0 && (!order || !slot_leaf)) return hipErrorInvalidValue;
+    return p.bf16 ? dispatch_gather<true>(p, leaf_idx, order, s, slot_leaf, split)
+                  : dispatch_gather<false>(p, leaf_idx, order, s, slot_leaf, split);
 }
 
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s) {

@@ -50,6 +50,7 @@ struct TilesArgs {
     int64_t T, n_tiles;
     int D, O, L, act;
     int units_per_tile;      // output kernel: waves per tile (each takes kRangesPerWave ranges)
+    int split;               // > 0: tiles with at least this many runs belong to the gather kernel
 };
 
 constexpr int kChunk = 8;            // K steps of the first contraction fetched per lane per group (4 pairs)
@@ -111,6 +112,7 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
     const int P = NB == 1 ? 16 / L : 1;      // runs per pass
     const int n_pairs = (D + 63) / 64;       // pairs of K steps (64 elements of a row each)
     const TileColumn c = tile_column(a, tile, j);
+    if (a.split > 0 && c.n_runs >= a.split) return;
     // A row j of block b = (run rr_i of the pass, neuron n_i + 16 b)
     const int rr_i = NB == 1 ? j / L : 0, n_i = NB == 1 ? j % L : j;
     uint4* my_stage = stage[wave];
@@ -262,6 +264,7 @@ __global__ __launch_bounds__(256) void leaf_output_kernel(const TilesArgs a) {
     const int O = a.O, L = a.L;
     const int P = WIDE ? 1 : 16 / L;
     const TileColumn c = tile_column(a, tile, j);
+    if (a.split > 0 && c.n_runs >= a.split) return;
 
     // token rows this lane stores: rows 4 kg + q of the tile
     uint16_t* orow[4];
@@ -396,9 +399,10 @@ bool tiles_shape_ok(const Problem& p) {
 
 // hidden: workspace of T * L bf16 values
 hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const int32_t* perm, void* hidden,
-                             hipStream_t s, void (*between)(hipStream_t)) {
+                             hipStream_t s, void (*between)(hipStream_t), int split) {
     if (p.T == 0) return hipSuccess;
     TilesArgs a;
+    a.split = split;
     a.x = (const uint16_t*)p.x;
     a.w1 = (const uint16_t*)p.leaf_w1;
     a.b1 = (const uint16_t*)p.leaf_b1;

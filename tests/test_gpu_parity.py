@@ -106,21 +106,27 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("path", [0, 1, 2, 4], ids=["auto", "fused", "staged", "token"])
+# (path, leaf_path): the staged path picks its leaf kernels by bucket size, so the tile kernels get
+# a run of their own on every shape they take
+@pytest.mark.parametrize("path", [(0, 0), (1, 0), (2, 0), (2, 2), (4, 0)],
+                         ids=["auto", "fused", "staged", "staged_tiles", "token"])
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
 def test_small_and_edge_shapes(case, path):
     import paper_2308_14711_amd as F
     name, T, D, O, depth, L, act, dtype = case
+    path, leaf_path = path
     print("\n[case] %s T=%d D=%d O=%d depth=%d L=%d dtype=%d seed 5 path=%d" % (name, T, D, O, depth, L, dtype, path),
           flush=True)
     w = W.make_layer(name, T, D, O, depth, L, act, dtype, seed=5,
                      node_b="zipf" if name.startswith("skew") else "uniform")
     F.fff_set_option("path", path)
+    F.fff_set_option("leaf_path", leaf_path)
     try:
         out, idx = run_forward(w)
         took = F.fff_get_option("last_path")
     finally:
         F.fff_set_option("path", 0)
+        F.fff_set_option("leaf_path", 0)
     per = 8 if dtype == W.DTYPE_BF16 else 4
     if D % per == 0 and D // per <= 512 and (path == 4 or (path == 0 and T <= 512)):
         assert took == 4, "the one-block-per-token launch takes this shape, but path %d ran" % took
@@ -281,6 +287,43 @@ def test_alternative_paths_agree_with_the_oracle(opt):
     _log("paths %s" % (opt,), check_against_oracle(w, out, idx))
 
 
+SPLIT_CASES = [
+    # name,          T,    D,    O,    depth, L,  node_b
+    ("skewed",       6000, 256,  128,  10,    4,  "zipf"),      # popular leaves and a long tail of single tokens
+    ("skewed_wide",  3000, 2048, 2048, 9,     8,  "zipf"),      # a wave per token in the gather kernel
+    ("thin",         900,  128,  64,   8,     3,  "uniform"),   # 3.5 tokens a leaf, leaf width not a divisor of 16
+    ("skewed_l20",   2500, 512,  256,  9,     20, "zipf"),      # leaves of 17..32 neurons
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=[c[0] for c in SPLIT_CASES])
+def test_leaf_stage_split_between_tile_and_gather_kernels(case):
+    """On request the staged leaf stage sends tiles (16 consecutive slots of the bucketed order) with
+    many different leaves to the gather kernel and keeps the others on the tile kernels.  Every
+    threshold, from "all tiles to the gather kernel" to "none", must give the oracle's rows, and
+    every token's row is written by exactly one of the kernels (the output starts as NaN)."""
+    import paper_2308_14711_amd as F
+    name, T, D, O, depth, L, node_b = case
+    print("\n[case] split %s T=%d D=%d O=%d depth=%d L=%d bf16 seed 12 node_b=%s" % case, flush=True)
+    w = W.make_layer(name, T, D, O, depth, L, W.ACT_GELU, W.DTYPE_BF16, seed=12, node_b=node_b)
+    F.fff_set_option("path", 2)
+    try:
+        out, idx = run_forward(w)
+        # few tokens a leaf: the gather kernel alone, except for leaves of more than 8 neurons
+        assert F.fff_get_option("last_leaf_path") == (2 if L > 8 else 1)
+        _log("split %s auto" % name, check_against_oracle(w, out, idx))
+        F.fff_set_option("leaf_path", 2)
+        for split in (1, 2, 5, 8, 13, 16, 17, 0):
+            F.fff_set_option("leaf_split", split)
+            out, idx = run_forward(w)
+            assert F.fff_get_option("last_leaf_path") == (3 if 1 <= split <= 16 else 2)
+            _log("split %s %d" % (name, split), check_against_oracle(w, out, idx))
+    finally:
+        F.fff_set_option("path", 0)
+        F.fff_set_option("leaf_path", 0)
+        F.fff_set_option("leaf_split", 0)
+
+
 @pytest.mark.parametrize("path", [1, 2, 4], ids=["fused", "staged", "token"])
 def test_capture_in_a_hip_graph_and_replay(path):
     """The call only enqueues kernels on the given stream (no allocation once the workspace is
@@ -339,22 +382,25 @@ def _random_cases(n, seed):
 RANDOM_CASES = _random_cases(36, seed=2024)
 
 
-@pytest.mark.parametrize("path", [0, 2], ids=["auto", "staged"])
+@pytest.mark.parametrize("path", [(0, 0), (2, 0), (2, 2)], ids=["auto", "staged", "staged_tiles"])
 @pytest.mark.parametrize("case", RANDOM_CASES, ids=["%s_T%d_D%d_O%d_d%d_L%d_%s" % (c[0], c[1], c[2], c[3], c[4], c[5],
                                                                                     "bf16" if c[7] else "f32")
                                                     for c in RANDOM_CASES])
 def test_random_shapes(case, path):
     import paper_2308_14711_amd as F
     name, T, D, O, depth, L, act, dtype = case
+    path, leaf_path = path
     print("\n[case] %s T=%d D=%d O=%d depth=%d L=%d act=%d dtype=%d seed 77 path=%d" % (name, T, D, O, depth, L, act, dtype, path),
           flush=True)
     w = W.make_layer(name, T, D, O, depth, L, act, dtype, seed=77)
     F.fff_set_option("path", path)
+    F.fff_set_option("leaf_path", leaf_path)
     try:
         out, idx = run_forward(w)
         took = F.fff_get_option("last_path")
     finally:
         F.fff_set_option("path", 0)
+        F.fff_set_option("leaf_path", 0)
     _log("%s path=%d took=%d" % (name, path, took), check_against_oracle(w, out, idx))
 
 
