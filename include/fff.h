@@ -225,7 +225,8 @@ int fff_release_workspace(void);
  *   "leaf_path"      staged path only: 0 = the MFMA tile kernels when the shape allows them
  *                    (bf16, 3 <= leaf_width <= 32, D % 8 == 0, O % 8 == 0, 16-byte aligned
  *                    rows) and a leaf sees at least 8 tokens on average or is wider than 8
- *                    neurons, else the gather kernel (default); 1 = always the gather kernel;
+ *                    neurons (32 tokens on average for batches of up to 8192 tokens), else
+ *                    the gather kernel (default); 1 = always the gather kernel;
  *                    2 = the tile kernels whenever the shape allows them, also for
  *                    leaf_width 1 and 2
  *   "path"           0 = choose by shape and batch size (default), 1 = one fused launch
@@ -236,11 +237,13 @@ int fff_release_workspace(void);
  *                    leaf's neurons split over the block's waves; rows of at most 512
  *                    16-byte vectors); a path the shape does not allow falls back to one it
  *                    does.  The default takes 4 for batches of up to "token_max_T" tokens
- *                    (6 times that where leaf_width > 8 rules out the fused launch), then
- *                    staged when a leaf sees >= 3 tokens on average, T > 8192 and the leaves
- *                    are wide (leaf_width >= 8, or >= 4 with more than 5 MB of leaf weights
- *                    in total, or 3 with more than 16 MB), else fused
- *   "token_max_T"    see "path" (default 512)
+ *                    (twice that where leaf_width > 8 rules out the fused launch), then
+ *                    staged when the leaf rows a token meets are many bytes (24 KB, or 12 KB
+ *                    with more than 5 MB of leaf weights in total, or 8 KB with more than
+ *                    16 MB) and, beyond 8192 tokens, a leaf sees >= 3 tokens on average
+ *                    (up to 8192 tokens: the tile kernels take the shape, or the leaf weights
+ *                    are a megabyte), else fused
+ *   "token_max_T"    see "path" (default 1536)
  *   "walk_tpg", "walk_block", "walk_top", "walk_bpc", "walk_prefetch"
  *                    experiment switches of the fused/descent kernel (tokens per lane
  *                    group, threads per block, k + 1 = at most k LDS-staged levels,
