@@ -237,13 +237,12 @@ int fff_release_workspace(void);
  *                    leaf's neurons split over the block's waves; rows of at most 512
  *                    16-byte vectors); a path the shape does not allow falls back to one it
  *                    does.  The default takes 4 for batches of up to "token_max_T" tokens
- *                    (twice that where leaf_width > 8 rules out the fused launch), then
- *                    staged when the leaf rows a token meets are many bytes (24 KB, or 12 KB
- *                    with more than 5 MB of leaf weights in total, or 8 KB with more than
- *                    16 MB) and, beyond 8192 tokens, a leaf sees >= 3 tokens on average
- *                    (up to 8192 tokens: the tile kernels take the shape, or the leaf weights
- *                    are a megabyte), else fused
- *   "token_max_T"    see "path" (default 1536)
+ *                    (6 times that where leaf_width > 8 rules out the fused launch), then
+ *                    staged when there are more than 8192 tokens, the leaf rows a token meets
+ *                    are many bytes (24 KB, or 12 KB with more than 8 MB of leaf weights in
+ *                    total, or 8 KB with more than 16 MB) and a leaf sees >= 3 tokens on
+ *                    average, else fused
+ *   "token_max_T"    see "path" (default 512)
  *   "walk_tpg", "walk_block", "walk_top", "walk_bpc", "walk_prefetch"
  *                    experiment switches of the fused/descent kernel (tokens per lane
  *                    group, threads per block, k + 1 = at most k LDS-staged levels,

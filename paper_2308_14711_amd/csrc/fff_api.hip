@@ -34,7 +34,7 @@ struct Options {
     int64_t last_leaf_path = 0;  // read-only: leaf stage of the last staged call (1 gather kernel, 2 tile kernels, 3 both)
     int64_t leaf_split = 0;      // 1..16: tiles of 16 slots with that many runs of equal leaf go to the gather kernel
     int64_t last_block_kernel = 0; // read-only: 1 = fff_forward_block ran a vector kernel, 2 = the element-wise one
-    int64_t token_max_T = 1536;  // batches up to this many tokens (2x where no fused launch fits) go one block per token
+    int64_t token_max_T = 512;   // batches up to this many tokens (6x where no fused launch fits) go one block per token
 } g_opt;
 
 // Events recorded around the stages of fff_forward_hard while "stage_timing" is on:
@@ -201,17 +201,17 @@ int choose_path(const Problem& p) {
     if (g_opt.path == kPathStaged && staged_ok) return kPathStaged;
     if (g_opt.path == kPathGeneric) return kPathGeneric;
     // a small batch cannot fill the chip with streaming work: one block per token, built for latency
-    // (measured crossovers on 768-wide rows: 1024 tokens take 12-17 us here against 18-50 us for
-    // the other launches, 2048 tokens 22-32 us against 19-31; leaves too wide for the fused launch
-    // leave only the staged path, which overtakes between 2048 and 4096 tokens)
+    // (measured crossovers on 768-wide rows: the fused launch, with its smallest tiles, takes 9-12 us
+    // from 256 to 2048 tokens, this one 9 us up to 512 tokens and 13-16 at 1024; leaves too wide for
+    // the fused launch leave only the staged path, which overtakes between 2048 and 4096 tokens)
     if (g_opt.path == kPathAuto && token_ok &&
-        p.T <= (fused_ok ? g_opt.token_max_T : 2 * g_opt.token_max_T))
+        p.T <= (fused_ok ? g_opt.token_max_T : 6 * g_opt.token_max_T))
         return kPathToken;
     if (!fused_ok && !staged_ok) return token_ok ? kPathToken : kPathGeneric;
     if (!staged_ok) return kPathFused;
     if (!fused_ok) return kPathStaged;
     // Grouping pays once the leaf rows a token meets are many bytes -- 24 KB (8 neurons on 768-wide
-    // bf16 rows), or 12 KB (4 neurons) where the leaf weights together outgrow the 4 MB L2 of one XCD,
+    // bf16 rows), or 12 KB (4 neurons) where the leaf weights together (8 MB) outgrow the 4 MB L2 of one XCD,
     // which the fused launch relies on for its per-token row fetches, or 8 KB (3 neurons) from 16 MB
     // on (measured on 768-wide rows: depth 8 ties at 6 neurons, depth 10 at 4, depth 4 only at 8;
     // 128-wide rows stay on the fused launch at 8 neurons, 256-wide ones leave it at depth 12) --
@@ -219,20 +219,16 @@ int choose_path(const Problem& p) {
     // its rows in cache, so the staged path stays ahead down to 3 tokens a leaf (50432 tokens,
     // 768-wide rows, 8 neurons, depth 13 and 14: 151 and 218 us against 224 and 260 fused; 16384
     // tokens, 4096-wide rows, 4 neurons, depth 12: 233 against 285); below that (the skewed workload:
-    // half a token a leaf) the single launch wins again.  Up to 8192 tokens the fused launch has too
-    // few blocks in flight for wide leaves whatever the occupancy (2048-8192 tokens, 8 neurons:
-    // 27-40 us staged against 38-55) ...
+    // half a token a leaf) the single launch wins again.  Up to 8192 tokens the fused launch, cut
+    // into tiles of 32 tokens, is ahead for every leaf it takes (2048-8192 tokens, 8 neurons, depth
+    // 9: 17-22 us against 25-31 staged; 16384 tokens: 42 against 34).
     const int64_t es = p.bf16 ? 2 : 4;
     const int64_t token_leaf_bytes = (p.L * (p.D + p.O) + p.O) * es;
     const int64_t leaf_bytes = token_leaf_bytes << p.depth;
     const bool wide = token_leaf_bytes >= 24 * 1024 ||
-                      (token_leaf_bytes >= 12 * 1024 && leaf_bytes >= (int64_t)5 << 20) ||
+                      (token_leaf_bytes >= 12 * 1024 && leaf_bytes >= (int64_t)8 << 20) ||
                       (token_leaf_bytes >= 8 * 1024 && leaf_bytes >= (int64_t)16 << 20);
-    // (... where the tile kernels take the shape or the leaf weights are a megabyte: the paper's small
-    // fp32 networks, 784 inputs, 10 outputs, 8 neurons a leaf, batch 2048, take 15-17 us fused against
-    // 18-19 staged)
-    const bool visited = p.T <= 8192 ? (leaf_bytes >= (int64_t)1 << 20 || tiles_shape_ok(p))
-                                     : (p.depth < 40 && p.T >= ((int64_t)3 << p.depth));
+    const bool visited = p.T > 8192 && p.depth < 40 && p.T >= ((int64_t)3 << p.depth);
     return (wide && visited) ? kPathStaged : kPathFused;
 }
 
@@ -310,7 +306,7 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
 
 // The leaf networks at given leaves: small batches go one block per token, larger ones are bucketed.
 int run_leaf_any(const Problem& p, const int32_t* leaf_idx, hipStream_t s) {
-    if (g_opt.path != kPathStaged && token_shape_ok(p) && p.T <= 2 * g_opt.token_max_T) {
+    if (g_opt.path != kPathStaged && token_shape_ok(p) && p.T <= 6 * g_opt.token_max_T) {
         hipError_t e = launch_token_block(p, nullptr, s, leaf_idx);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "token-block kernel launch");
     }
@@ -443,7 +439,7 @@ int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b, 
     if (e != hipSuccess) return set_device_error(e, "gating kernel launch");
     stage_mark(s);
     // the experts are leaves: small batches one block per token, larger ones bucketed
-    if (g_opt.path != kPathStaged && token_shape_ok(p) && T <= 2 * g_opt.token_max_T) {
+    if (g_opt.path != kPathStaged && token_shape_ok(p) && T <= 6 * g_opt.token_max_T) {
         g_opt.last_path = kPathToken;
         e = launch_token_block(p, nullptr, s, ei);
         for (int k = 0; k < 3; ++k) stage_mark(s);

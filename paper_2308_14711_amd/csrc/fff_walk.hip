@@ -382,9 +382,19 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     const int64_t nvec = p.D / Elem<BF16>::kPerVec;
     // (lanes per token, 16-byte vectors per lane, tokens per group, block size): blocks of 1024
     // threads leave 128 VGPRs per lane, blocks of 512 leave 256 for the long-row variants
-    if (nvec <= 16) return run_walk<BF16, 16, 1, 4, 1024, FUSED>(p, leaf_idx, s);
-    if (nvec <= 32) return run_walk<BF16, 16, 2, 2, 1024, FUSED>(p, leaf_idx, s);
-    if (nvec <= 64) return run_walk<BF16, 16, 4, 2, 1024, FUSED>(p, leaf_idx, s);
+    // A block's tile is (threads / lanes per token) x (tokens per group) tokens; a batch of up to
+    // 32 tokens per compute unit is cut into tiles of 32, so that it still spreads over the chip.
+    // (Rows of up to 64 vectors have no tile in between and keep the small one up to two tiles
+    // per compute unit.)
+    const bool untuned = g_walk_tuning.tpg == 0 && g_walk_tuning.block == 0;
+    const int64_t cus = device_info().cus;
+    const bool small_batch = untuned && p.T <= 32 * cus, smallish_batch = untuned && p.T <= 64 * cus;
+    if (nvec <= 16) return smallish_batch ? run_walk<BF16, 16, 1, 1, 512, FUSED>(p, leaf_idx, s)
+                                          : run_walk<BF16, 16, 1, 4, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 32) return smallish_batch ? run_walk<BF16, 16, 2, 1, 512, FUSED>(p, leaf_idx, s)
+                                          : run_walk<BF16, 16, 2, 2, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 64) return smallish_batch ? run_walk<BF16, 16, 4, 1, 512, FUSED>(p, leaf_idx, s)
+                                          : run_walk<BF16, 16, 4, 2, 1024, FUSED>(p, leaf_idx, s);
     if (nvec <= 96) {
         const int64_t tpg = g_walk_tuning.tpg, blk = g_walk_tuning.block;
         if (tpg == 1 && blk == 512) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
@@ -396,7 +406,15 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
                            vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
         if (exact && g_walk_tuning.prefetch)
             return run_walk_t<BF16, 16, 6, 2, 512, FUSED, true, true>(p, leaf_idx, s);
-        if (FUSED && tpg == 0 && blk == 0) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
+        if (tpg == 0 && blk == 0) {
+            // at most one tile per compute unit before tiles get larger: 32 tokens a block up
+            // to 8192 tokens, 64 up to 16384, then 128 (fused launch, depth 11, one neuron a leaf:
+            // 2048 tokens 9.5 us against 23.4 with tiles of 128, 8192 tokens 14.8 against 30.3,
+            // 16384 tokens 24.3 against 32.7, 24576 tokens 37.1 with tiles of 64 against 35.7).
+            if (p.T <= 32 * cus) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
+            if (p.T <= 64 * cus) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
+            if (FUSED) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
+        }
         if (tpg == 1) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
         if (tpg == 2 && blk == 512) return run_walk<BF16, 16, 6, 2, 512, FUSED>(p, leaf_idx, s);
         if (tpg == 4 && blk == 512) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
@@ -404,7 +422,8 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
         if (tpg == 4 && blk == 256) return run_walk<BF16, 16, 6, 4, 256, FUSED>(p, leaf_idx, s);
         return run_walk<BF16, 16, 6, 2, 1024, FUSED>(p, leaf_idx, s);
     }
-    if (nvec <= 128) return run_walk<BF16, 16, 8, 2, 512, FUSED>(p, leaf_idx, s);
+    if (nvec <= 128) return small_batch ? run_walk<BF16, 16, 8, 1, 512, FUSED>(p, leaf_idx, s)
+                                        : run_walk<BF16, 16, 8, 2, 512, FUSED>(p, leaf_idx, s);
     if (nvec <= 256) return run_walk<BF16, 64, 4, 2, 1024, FUSED>(p, leaf_idx, s);
     if (nvec <= 512) {
         const int64_t tpg = g_walk_tuning.tpg, blk = g_walk_tuning.block;

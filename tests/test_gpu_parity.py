@@ -291,6 +291,42 @@ def test_alternative_paths_agree_with_the_oracle(opt):
     _log("paths %s" % (opt,), check_against_oracle(w, out, idx))
 
 
+TILE_SIZES = [
+    # the walk kernels cut a batch into tiles of 32, 64, 128 or 256 tokens by batch size and row width:
+    # batches on both sides of the switches, for every row-width class
+    # name,            T,     D,    O,   depth, L, dtype
+    ("w64_small",      3000,  64,   64,  5,     2, W.DTYPE_BF16),
+    ("w64_large",      20011, 64,   32,  6,     3, W.DTYPE_BF16),
+    ("w128_large",     17000, 128,  128, 7,     1, W.DTYPE_BF16),
+    ("w256_mid",       12000, 256,  64,  8,     4, W.DTYPE_BF16),
+    ("w256_large",     16500, 256,  256, 5,     2, W.DTYPE_BF16),
+    ("w512_large",     16500, 512,  128, 6,     2, W.DTYPE_BF16),
+    ("w768_mid",       12001, 768,  768, 9,     1, W.DTYPE_BF16),
+    ("w768_ragged",    9000,  760,  768, 7,     3, W.DTYPE_BF16),
+    ("w1024_small",    5000,  1024, 256, 6,     2, W.DTYPE_BF16),
+    ("w1024_large",    9000,  1024, 1024, 6,    2, W.DTYPE_BF16),
+    ("f32_w64_large",  17000, 64,   16,  6,     2, W.DTYPE_F32),
+    ("f32_w256_small", 4000,  256,  64,  7,     3, W.DTYPE_F32),
+]
+
+
+@pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
+@pytest.mark.parametrize("case", TILE_SIZES, ids=[c[0] for c in TILE_SIZES])
+def test_tile_sizes_of_the_walk_kernels(case, path):
+    import paper_2308_14711_amd as F
+    name, T, D, O, depth, L, dtype = case
+    print("\n[case] tiles %s T=%d D=%d O=%d depth=%d L=%d dtype=%d seed 21 path=%d" % (name, T, D, O, depth, L, dtype, path),
+          flush=True)
+    w = W.make_layer(name, T, D, O, depth, L, W.ACT_GELU, dtype, seed=21)
+    F.fff_set_option("path", path)
+    try:
+        out, idx = run_forward(w)
+        assert F.fff_get_option("last_path") == path
+    finally:
+        F.fff_set_option("path", 0)
+    _log("tiles %s path=%d" % (name, path), check_against_oracle(w, out, idx))
+
+
 SPLIT_CASES = [
     # name,          T,    D,    O,    depth, L,  node_b
     ("skewed",       6000, 256,  128,  10,    4,  "zipf"),      # popular leaves and a long tail of single tokens
