@@ -413,7 +413,21 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
             // 16384 tokens 24.3 against 32.7, 24576 tokens 37.1 with tiles of 64 against 35.7).
             if (p.T <= 32 * cus) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
             if (p.T <= 64 * cus) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
-            if (FUSED) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
+            if (FUSED) {
+                // Beyond that a block walks through several tiles and the launch lasts as long as
+                // the block with the most tokens: up to 256 tokens per compute unit a smaller tile
+                // is taken where it shortens that block's share by 15 % (18000-24576 tokens: tiles
+                // of 96, 27-35 us against 33-37; 40000 tokens: tiles of 32, 54 us against 66).
+                const auto share = [&](int64_t tile) { return ((p.T + tile - 1) / tile + cus - 1) / cus * tile; };
+                int64_t tile = 128;
+                if (p.T <= 256 * cus)
+                    for (const int64_t cand : {(int64_t)96, (int64_t)64, (int64_t)32})
+                        if (share(cand) * 115 <= share(tile) * 100) tile = cand;
+                if (tile == 96) return run_walk<BF16, 16, 6, 3, 512, FUSED>(p, leaf_idx, s);
+                if (tile == 64) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
+                if (tile == 32) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
+                return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
+            }
         }
         if (tpg == 1) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
         if (tpg == 2 && blk == 512) return run_walk<BF16, 16, 6, 2, 512, FUSED>(p, leaf_idx, s);

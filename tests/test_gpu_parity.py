@@ -303,6 +303,8 @@ TILE_SIZES = [
     ("w512_large",     16500, 512,  128, 6,     2, W.DTYPE_BF16),
     ("w768_mid",       12001, 768,  768, 9,     1, W.DTYPE_BF16),
     ("w768_ragged",    9000,  760,  768, 7,     3, W.DTYPE_BF16),
+    ("w768_tiles_96",  20000, 768,  768, 8,     2, W.DTYPE_BF16),
+    ("w768_rounds",    40000, 768,  256, 7,     1, W.DTYPE_BF16),
     ("w1024_small",    5000,  1024, 256, 6,     2, W.DTYPE_BF16),
     ("w1024_large",    9000,  1024, 1024, 6,    2, W.DTYPE_BF16),
     ("f32_w64_large",  17000, 64,   16,  6,     2, W.DTYPE_F32),
