@@ -14,8 +14,9 @@
 //     every token keeps hitting) are staged in LDS once per block; deeper rows,
 //     which few tokens share, are fetched from L2/HBM.
 //   - Partial dot products are reduced inside the group with DPP row rotations.
-//   - Blocks are persistent: a block strides over token tiles, so the LDS
-//     staging is paid once per block, not once per tile.
+//   - Blocks are persistent: a block owns a contiguous share of the tokens and
+//     takes it in equal rounds of at most one tile, so the LDS staging is paid
+//     once per block and every block has the same number of tokens per round.
 #include "fff_device.h"
 #include "fff_internal.h"
 
@@ -71,6 +72,8 @@ struct WalkArgs {
     void* out;
     int32_t* leaf_idx;   // may be null when FUSED
     int64_t T, O;
+    int64_t share;       // tokens per block (the last block may get fewer)
+    int chunk;           // tokens per round, at most one tile
     int depth, top, nvec, L, act, out_vec;
 };
 
@@ -79,7 +82,6 @@ struct WalkArgs {
 template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT, bool PREFETCH>
 __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
     extern __shared__ uint4 lds[];                 // [(2^top - 1) * nvec] rows, then (2^top - 1) biases
-    constexpr int kGroups = kWalkBlock / LPT;
     constexpr int VE = Elem<BF16>::kPerVec;
     const int nvec = a.nvec;
     const int n_top = (1 << a.top) - 1;
@@ -91,15 +93,17 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
 
     const int sub = threadIdx.x % LPT;
     const int g = threadIdx.x / LPT;
-    const int64_t tile = (int64_t)kGroups * TPG;
     const int n_nodes = (1 << a.depth) - 1;
 
-    // token rows of a tile: row of token base + g TPG + k goes to xr[k] (clamped past the end)
+    // this block's tokens, taken a.chunk at a time: slot g TPG + k of a round holds token
+    // base + g TPG + k while that is inside the round and the share (else the last token, unused)
+    const int64_t lo = (int64_t)blockIdx.x * a.share;
+    const int64_t hi = lo + a.share < a.T ? lo + a.share : a.T;
     auto fetch_rows = [&](int64_t base, uint4 (&xr)[TPG][NV]) {
 #pragma unroll
         for (int k = 0; k < TPG; ++k) {
             const int64_t tt = base + (int64_t)g * TPG + k;
-            const uint4* xrow = a.x + (tt < a.T ? tt : a.T - 1) * nvec;
+            const uint4* xrow = a.x + ((g * TPG + k < a.chunk && tt < hi) ? tt : a.T - 1) * nvec;
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 const int v = sub + i * LPT;
@@ -107,24 +111,24 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
             }
         }
     };
-    const int64_t stride = (int64_t)gridDim.x * tile;
+    const int64_t stride = a.chunk;
     uint4 xv[TPG][NV];
-    if (PREFETCH) fetch_rows((int64_t)blockIdx.x * tile, xv);
+    if (PREFETCH) fetch_rows(lo, xv);
 
-    for (int64_t base = (int64_t)blockIdx.x * tile; base < a.T; base += stride) {
+    for (int64_t base = lo; base < hi; base += stride) {
         int64_t t[TPG];
         bool live[TPG];
 #pragma unroll
         for (int k = 0; k < TPG; ++k) {
             const int64_t tt = base + (int64_t)g * TPG + k;
-            live[k] = tt < a.T;
+            live[k] = g * TPG + k < a.chunk && tt < hi;
             t[k] = live[k] ? tt : a.T - 1;
         }
         // PREFETCH: the rows of this tile were requested one iteration ago; request the next
         // tile's now, so that they travel while this tile walks the tree
         uint4 xn[TPG][NV];
         if (PREFETCH) {
-            if (base + stride < a.T) fetch_rows(base + stride, xn);
+            if (base + stride < hi) fetch_rows(base + stride, xn);
         } else {
             fetch_rows(base, xv);
         }
@@ -319,10 +323,18 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     constexpr int kGroups = kWalkBlock / LPT;
     const DeviceInfo di = device_info();
     const int64_t tile = (int64_t)kGroups * TPG;
-    int64_t blocks = (p.T + tile - 1) / tile;
+    // a block is worth starting for 32 tokens (or a tile, if that is smaller)
+    const int64_t min_share = tile < 32 ? tile : 32;
+    int64_t blocks = (p.T + min_share - 1) / min_share;
     const int64_t cap = (int64_t)di.cus * (g_walk_tuning.bpc > 0 ? g_walk_tuning.bpc : 1);
     if (blocks > cap) blocks = cap;
+    // equal contiguous shares, each taken in equal rounds of at most one tile (a multiple of the
+    // tokens a lane group carries)
     const int64_t tokens_per_block = (p.T + blocks - 1) / blocks;
+    blocks = (p.T + tokens_per_block - 1) / tokens_per_block;
+    const int64_t rounds = (tokens_per_block + tile - 1) / tile;
+    int64_t chunk = ((tokens_per_block + rounds - 1) / rounds + TPG - 1) / TPG * TPG;
+    if (chunk > tile) chunk = tile;
     // stage the top levels while a block handles at least two tokens per staged row and they fit
     const int64_t row_bytes = p.D * (BF16 ? 2 : 4);
     size_t lds_cap = di.lds_per_block;
@@ -357,6 +369,8 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     a.leaf_idx = leaf_idx;
     a.T = p.T;
     a.O = p.O;
+    a.share = tokens_per_block;
+    a.chunk = (int)chunk;
     a.depth = p.depth;
     a.top = top;
     g_walk_tuning.last_top = top;
@@ -414,17 +428,19 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
             if (p.T <= 32 * cus) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
             if (p.T <= 64 * cus) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
             if (FUSED) {
-                // Beyond that a block walks through several tiles and the launch lasts as long as
-                // the block with the most tokens: up to 256 tokens per compute unit a smaller tile
-                // is taken where it shortens that block's share by 15 % (18000-24576 tokens: tiles
-                // of 96, 27-35 us against 33-37; 40000 tokens: tiles of 32, 54 us against 66).
-                const auto share = [&](int64_t tile) { return ((p.T + tile - 1) / tile + cus - 1) / cus * tile; };
+                // Beyond that a block takes its share in several rounds, and a round costs about
+                // the same whether its tile is full or not: up to 512 tokens per compute unit a
+                // smaller tile is taken where rounds x tile comes out 15 % shorter (18000-24576
+                // tokens: tiles of 96, 27-35 us against 33-37; 40000 tokens: tiles of 32, 54 us
+                // against 62-66; 80000 tokens: tiles of 64, 88-98 us against 99-102).
+                const int64_t share = (p.T + cus - 1) / cus;
+                const auto busy = [&](int64_t tile) { return (share + tile - 1) / tile * tile; };
                 int64_t tile = 128;
-                if (p.T <= 256 * cus)
+                if (p.T <= 512 * cus)
                     for (const int64_t cand : {(int64_t)96, (int64_t)64, (int64_t)32})
-                        if (share(cand) * 115 <= share(tile) * 100) tile = cand;
+                        if (busy(cand) * 115 <= busy(tile) * 100) tile = cand;
                 if (tile == 96) return run_walk<BF16, 16, 6, 3, 512, FUSED>(p, leaf_idx, s);
-                if (tile == 64) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
+                if (tile == 64) return run_walk<BF16, 16, 6, 2, 512, FUSED>(p, leaf_idx, s);
                 if (tile == 32) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
                 return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
             }
