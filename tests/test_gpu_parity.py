@@ -329,6 +329,42 @@ def test_tile_sizes_of_the_walk_kernels(case, path):
     _log("tiles %s path=%d" % (name, path), check_against_oracle(w, out, idx))
 
 
+WALK_SWITCHES = [
+    # the experiment switches of the walk kernels select other instantiations: (options, D)
+    ({"walk_tpg": 1, "walk_block": 512}, 768), ({"walk_tpg": 1, "walk_block": 1024}, 768),
+    ({"walk_tpg": 2, "walk_block": 512}, 768), ({"walk_tpg": 2, "walk_block": 1024}, 768),
+    ({"walk_tpg": 3, "walk_block": 512}, 768), ({"walk_tpg": 4, "walk_block": 512}, 768),
+    ({"walk_tpg": 4, "walk_block": 256}, 768), ({"walk_prefetch": 1}, 768),
+    ({"walk_top": 1}, 768), ({"walk_top": 3}, 768), ({"walk_bpc": 2}, 768), ({"walk_bpc": 3, "walk_top": 4}, 768),
+    ({"walk_tpg": 1, "walk_block": 1024}, 4096), ({"walk_tpg": 3, "walk_block": 512}, 4096),
+    ({"walk_tpg": 4, "walk_block": 256}, 4096), ({"walk_tpg": 6, "walk_block": 256}, 4096),
+]
+
+
+@pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
+@pytest.mark.parametrize("switches", WALK_SWITCHES, ids=["_".join("%s%d" % (k[5:], v) for k, v in o.items()) + "_w%d" % d
+                                                         for o, d in WALK_SWITCHES])
+def test_walk_kernel_switches(switches, path):
+    """Every instantiation the switches reach, on a batch of several rounds with a ragged end."""
+    import paper_2308_14711_amd as F
+    opts, D = switches
+    T = 40007 if D == 768 else 5003
+    print("\n[case] walk switches %s T=%d D=%d depth=9 L=1 bf16 seed 31 path=%d" % (opts, T, D, path), flush=True)
+    w = W.make_layer("switches", T, D, D, 9, 1, W.ACT_GELU, W.DTYPE_BF16, seed=31, keep_f32=False)
+    F.fff_set_option("path", path)
+    for k, v in opts.items():
+        F.fff_set_option(k, v)
+    try:
+        out, idx = run_forward(w)
+        if "walk_top" in opts:
+            assert F.fff_get_option("last_walk_top") <= opts["walk_top"] - 1
+    finally:
+        F.fff_set_option("path", 0)
+        for k in opts:
+            F.fff_set_option(k, 0)
+    _log("switches %s path=%d" % (opts, path), check_against_oracle(w, out, idx))
+
+
 SPLIT_CASES = [
     # name,          T,    D,    O,    depth, L,  node_b
     ("skewed",       6000, 256,  128,  10,    4,  "zipf"),      # popular leaves and a long tail of single tokens
