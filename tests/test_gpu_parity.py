@@ -365,6 +365,22 @@ def test_walk_kernel_switches(switches, path):
     _log("switches %s path=%d" % (opts, path), check_against_oracle(w, out, idx))
 
 
+def test_token_block_threshold_option():
+    """token_max_T moves the batch size up to which the one-block-per-token launch is taken."""
+    import paper_2308_14711_amd as F
+    print("\n[case] token_max_T T=700 D=256 depth=6 L=2 bf16 seed 8", flush=True)
+    w = W.make_layer("threshold", 700, 256, 64, 6, 2, W.ACT_RELU, W.DTYPE_BF16, seed=8)
+    old = F.fff_get_option("token_max_T")
+    try:
+        for limit, expect in ((0, 1), (699, 1), (700, 4), (old, 1 if old < 700 else 4)):
+            F.fff_set_option("token_max_T", limit)
+            out, idx = run_forward(w)
+            assert F.fff_get_option("last_path") == expect, "token_max_T=%d took path %d" % (limit, F.fff_get_option("last_path"))
+            _log("threshold %d" % limit, check_against_oracle(w, out, idx))
+    finally:
+        F.fff_set_option("token_max_T", old)
+
+
 SPLIT_CASES = [
     # name,          T,    D,    O,    depth, L,  node_b
     ("skewed",       6000, 256,  128,  10,    4,  "zipf"),      # popular leaves and a long tail of single tokens
