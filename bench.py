@@ -11,8 +11,11 @@ Beside the headline tokens/s the line carries: the roofline position of the
 dominant kernel (algorithmic bytes per launch / its average duration measured
 with HIP events recorded on the call's stream inside the library), the same
 for every stage and for the whole path, the spread of the timing, the CPU
-oracle timed on this host (all cores, and one core), and an
-equal-training-width dense feedforward on the same GPU for the speedup.
+oracle timed on this host (all cores, and one core), an equal-training-width
+dense feedforward on the same GPU for the speedup, the ceiling a plain
+streaming copy reaches on this device ("copy_ceiling") with every fraction also
+stated against it, and under "others" the remaining two of the three
+bandwidth-bound workloads (C3, C4, C5) timed and checked the same way.
 
 Other modes, each printing one JSON line of its own:
     --sweep depth     small-batch latency against tree depth (the paper's speed experiment)
@@ -35,18 +38,102 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 
-# HBM-side bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs summarised in profiles/ (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0, the factors a plain device
-# copy of known size reads there).  Keyed by (workload, launch path, kernel); None where not measured.
-MEASURED_TRAFFIC = {
-    ("C4", "fused", "walk_fused"): 494.0e6,    # profiles/bert_base_fff_fused_C4.md
-    ("C3", "staged", "descent"): 80.9e6,       # profiles/vit_block_fff_staged_C3.md
-    ("C3", "staged", "bucketing"): 3.8e6,
-    ("C3", "staged", "leaf_hidden"): 82.7e6,
-    ("C3", "staged", "leaf_output"): 85.9e6,
-    ("C5", "fused", "walk_fused"): 1645.3e6,   # profiles/large_skewed_fff_fused_C5.md
-    ("C3", "block_n4", "block_group_kernel"): 818.9e6,   # profiles/vit_block_layer_wide_nodes_C3.md
-}
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+
+
+def measured_traffic(workload, kernel_launch):
+    """HBM-side bytes per launch from profiles/hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    runs (scaled by what the same counters read for a plain copy of known size), one row per
+    workload and kernel, each with the launch it was measured on as the library describes it
+    (fff_last_launch: kernel names with their tile parameters).  None unless the launch that has
+    just been timed is that very one -- a figure measured on another kernel says nothing here."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 6 and cells[0] == workload and cells[1].strip("`") == kernel_launch:
+            try:
+                return {"bytes": float(cells[4]) * 1e6, "fetch_bytes": float(cells[2]) * 1e6,
+                        "write_bytes": float(cells[3]) * 1e6, "source": cells[5].strip("`")}
+            except ValueError:
+                return None
+    return None
+
+
+_probe_lib = None
+
+
+def probes():
+    """The bench-only probe library (row gather, streaming copy); no part of the product ABI."""
+    global _probe_lib
+    if _probe_lib is None:
+        import ctypes
+        from paper_2308_14711_amd import build
+        P = ctypes.CDLL(build.PROBE_LIB)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        P.fffb_gather.argtypes = [vp, i64, i64, i32, i64, i32, i32, vp, vp]
+        P.fffb_copy.argtypes = [vp, vp, i64, i64, vp]
+        _probe_lib = P
+    return _probe_lib
+
+
+def probe_gather(torch, table, row_bytes, rows_in_flight, blocks, iters, dependent, sink):
+    """Launch the row-gather probe on torch's current stream; returns the bytes the launch reads."""
+    rows = table.numel() * table.element_size() // row_bytes
+    rc = probes().fffb_gather(table.data_ptr(), rows, row_bytes, rows_in_flight, blocks, iters, int(bool(dependent)),
+                              sink.data_ptr(), torch.cuda.current_stream().cuda_stream or None)
+    if rc != 0:
+        raise RuntimeError("fffb_gather failed (%d)" % rc)
+    return blocks * 32 * iters * rows_in_flight * row_bytes
+
+
+def copy_ceiling(torch, mbytes=512, reps=10):
+    """What a kernel that only moves rows reaches on this device: a plain streaming copy of
+    `mbytes` MB (beyond the 256 MB last-level cache), bytes read plus bytes written over time."""
+    n = mbytes << 20
+    src = torch.zeros((n,), dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    stream = torch.cuda.current_stream().cuda_stream or None
+    best = {}
+    for blocks in (1024, 2048, 4096, 8192):
+        for _ in range(2):
+            rc = probes().fffb_copy(dst.data_ptr(), src.data_ptr(), n, blocks, stream)
+            if rc != 0:
+                raise RuntimeError("fffb_copy failed (%d)" % rc)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            probes().fffb_copy(dst.data_ptr(), src.data_ptr(), n, blocks, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        best[blocks] = 2.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    for _ in range(2):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    runtime_copy = 2.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    blocks = max(best, key=best.get)
+    del src, dst
+    return {"GBps": round(best[blocks], 1), "blocks_of_512": blocks, "MB": mbytes,
+            "runtime_copy_GBps": round(runtime_copy, 1),
+            "counts": "bytes read + bytes written"}
+
+
+_ceiling = None
+
+
+def copy_ceiling_once(torch):
+    global _ceiling
+    if _ceiling is None:
+        _ceiling = copy_ceiling(torch)
+    return _ceiling
 
 
 def algorithmic_bytes(w, ref_idx):
@@ -265,9 +352,6 @@ def width_sweep(args, np, torch, W, F):
                       "sweep": rows}))
 
 
-MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
-
-
 def soft_bench(args, np, torch, W, F):
     """Forward_T of the chosen workload: every token against every leaf.  One step = one call of
     fff_forward_soft (node scores, mixture weights, weighted hidden activations, output rows, per-node
@@ -362,6 +446,7 @@ def block_bench(args, np, torch, W, F):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     kernel_ms = e0.elapsed_time(e1) / args.steps
+    launch = F.fff_last_launch()
     es = 2 if w.dtype == W.DTYPE_BF16 else 4
     # rows of up to 128 16-byte pieces take the 16-lanes-per-token kernel, longer ones a wave per token
     kernel = "block_group_kernel" if max(w.D, w.O) * es <= 128 * 16 else "block_kernel"
@@ -400,7 +485,8 @@ def block_bench(args, np, torch, W, F):
                    "seed": 0, "buffer_sets": sets},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None if (args.opt or args.tokens) else MEASURED_TRAFFIC.get((w.name, "block_n%d" % n, kernel)),
+                     "traffic": (measured_traffic(w.name, launch) or {}).get("bytes") if not args.tokens else None,
+                     "kernel_launch": launch,
                      "kernel": kernel,
                      "kernel_ms": round(kernel_ms, 5), "algorithmic_bytes": alg,
                      "weight_row_bytes_per_token": row_bytes},
@@ -412,7 +498,7 @@ def block_bench(args, np, torch, W, F):
 
 
 def gather_probe(args, np, torch, F):
-    """The row-gather microbenchmark behind the roofline discussion (fff_probe_gather): random rows of
+    """The row-gather microbenchmark behind the roofline discussion (probe library, fffb_gather): random rows of
     --probe-row-bytes out of zero-filled tables from well inside one XCD's L2 to beyond the last-level
     cache, as a dependent chain with four rows in flight per 16 lanes.  One JSON line."""
     rb = args.probe_row_bytes
@@ -427,12 +513,12 @@ def gather_probe(args, np, torch, F):
         res = {}
         for dep in (0, 1):
             for _ in range(2):
-                nbytes = F.fff_probe_gather(table, rb, 4, blocks, iters, dep, sink)
+                nbytes = probe_gather(torch, table, rb, 4, blocks, iters, dep, sink)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(5):
-                F.fff_probe_gather(table, rb, 4, blocks, iters, dep, sink)
+                probe_gather(torch, table, rb, 4, blocks, iters, dep, sink)
             e1.record()
             torch.cuda.synchronize()
             res["dependent" if dep else "independent"] = round(nbytes * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 2)
@@ -457,6 +543,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
+    ap.add_argument("--no-others", dest="others", action="store_false",
+                    help="time only --config (default: the other two of C3, C4, C5 are timed after it and "
+                         "reported under \"others\")")
     ap.add_argument("--sweep", choices=["depth", "experts", "widths"], default=None,
                     help="depth: the small-batch latency sweep (time per call against tree depth) instead of a "
                          "workload; experts: the same sweep with the mixture-of-experts lookup (one engaged "
@@ -515,7 +604,31 @@ def main():
         block_bench(args, np, torch, W, F)
         return
 
-    w = W.config(args.config, keep_f32=False, T=args.tokens or None)
+    line = hard_bench(args.config, args, np, torch, W, F, headline=True)
+    if args.others and not (args.tokens or args.opt):
+        # the other two bandwidth-bound workloads, timed the same way (fewer extras): the default run
+        # then covers all three configurations the bandwidth target is stated for
+        line["others"] = {}
+        for name in ("C3", "C4", "C5"):
+            if name == args.config:
+                continue
+            o = hard_bench(name, args, np, torch, W, F, headline=False)
+            line["others"][name] = {"ms_per_step": o["ms_per_step"], "tokens_per_s": o["value"],
+                                    "launch_path": o["config"]["launch_path"], "kernels": o["config"]["kernels"],
+                                    "alg_bytes": o["path"]["alg_bytes"], "path_frac": o["path"]["frac"],
+                                    "path_frac_of_copy_ceiling": o["path"].get("frac_of_copy_ceiling"),
+                                    "stages": o["stages"], "parity": o["parity"],
+                                    "workload": o["config"]["workload"]}
+    print(json.dumps(line))
+
+
+def hard_bench(name, args, np, torch, W, F, headline=True):
+    """Time fff_forward_hard on workload `name` and return the JSON line as a dict.  headline=False
+    leaves out the CPU baseline legs, the dense comparator and the gather probe (the parity check and
+    the per-stage durations stay)."""
+    no_cpu = args.no_cpu_baseline or not headline
+    no_dense = args.no_dense or not headline
+    w = W.config(name, keep_f32=False, T=args.tokens or None)
     tdt = torch.bfloat16 if w.dtype == W.DTYPE_BF16 else torch.float32
 
     def up(a):
@@ -553,21 +666,22 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = w.T * args.steps / (t1 - t0)
+    kernels = F.fff_last_launch()     # what the timed calls launched, as the library names it
 
     # routing of the oracle: which nodes and leaves are touched (host side, for the byte model)
     import oracle
     ins = [np.ascontiguousarray(w.device_array(k)) for k in W.TENSORS]
     ref_out, ref_idx, margin = oracle.forward_hard(*ins, w.depth, w.leaf_width, w.act,
-                                                   want_out=not args.no_cpu_baseline)
+                                                   want_out=True)
     cpu_passes, cpu_s = 0, 0.0
-    if not args.no_cpu_baseline:       # the oracle as it stands, whole batch, repeated for about 10 s
+    if not no_cpu:       # the oracle as it stands, whole batch, repeated for about 10 s
         t2 = time.perf_counter()
         while cpu_passes < 1 or (time.perf_counter() - t2 < 10.0 and cpu_passes < 400):
             oracle.forward_hard(*ins, w.depth, w.leaf_width, w.act)
             cpu_passes += 1
         cpu_s = time.perf_counter() - t2
     cpu_single = None
-    if not args.no_cpu_baseline:       # and on one core, on a prefix of the batch (about a second)
+    if not no_cpu:       # and on one core, on a prefix of the batch (about a second)
         n1 = min(w.T, 8192)
         ins1 = [np.ascontiguousarray(ins[0][:n1])] + ins[1:]
         all_threads = oracle.num_threads()
@@ -613,25 +727,35 @@ def main():
             names = (("descent", d_ms), ("bucketing", b_ms), ("leaf_hidden", l_ms), ("leaf_output", l2_ms))
         else:
             names = (("descent", d_ms), ("bucketing", b_ms), ("leaf", l_ms))
-        for name, ms in names:
+        for stage, ms in names:
             avg = ms / max(calls, 1)
-            gbs = alg[name] / (avg * 1e-3) / 1e9 if avg > 0 else 0.0
-            stages[name] = {"avg_ms": round(avg, 5), "alg_bytes": alg[name], "GBps": round(gbs, 1),
-                            "frac": round(gbs / HBM_PEAK_GBS, 4)}
+            gbs = alg[stage] / (avg * 1e-3) / 1e9 if avg > 0 else 0.0
+            stages[stage] = {"avg_ms": round(avg, 5), "alg_bytes": alg[stage], "GBps": round(gbs, 1),
+                             "frac": round(gbs / HBM_PEAK_GBS, 4)}
     dom = max(stages, key=lambda k: stages[k]["avg_ms"]) if stages else None
     roofline = None
     if dom:
-        launch = path_names.get(F.fff_get_option("last_path"), "?")
-        traffic = None if (args.opt or args.tokens) else MEASURED_TRAFFIC.get((w.name, launch, dom))
-        roofline = {"bound": "hbm", "kernel": dom, "achieved": stages[dom]["GBps"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": stages[dom]["frac"], "traffic": traffic}
+        # the dominant kernel as the library names it: the stage's position in the call's launches
+        names_in_order = [k.strip() for k in kernels.split(" + ")]
+        dom_kernel = kernels if len(stages) == 1 else None
+        if dom_kernel is None:
+            pos = {"descent": 0, "leaf_output": -1, "leaf_hidden": -2, "leaf": -1}.get(dom)
+            dom_kernel = names_in_order[pos] if pos is not None and names_in_order else dom
+        measured = None if args.tokens else measured_traffic(w.name, dom_kernel)
+        ceiling = copy_ceiling_once(torch)
+        roofline = {"bound": "hbm", "kernel": dom, "kernel_launch": dom_kernel, "achieved": stages[dom]["GBps"],
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": stages[dom]["frac"],
+                    "traffic": measured["bytes"] if measured else None,
+                    "traffic_source": measured["source"] if measured else None,
+                    "copy_ceiling_GBps": ceiling["GBps"],
+                    "frac_of_copy_ceiling": round(stages[dom]["GBps"] / ceiling["GBps"], 4)}
     path_gbs = alg["path"] / (ms_per_step * 1e-3) / 1e9
 
     # the fused launch fetches weight rows per token; how fast such rows can come at all depends on
     # whether the weight table fits an L2: measure random row fetches over tables of the next smaller
-    # and next larger power-of-two row count (fff_probe_gather) and report the time the launch's
+    # and next larger power-of-two row count (the probe library's fffb_gather) and report the time the launch's
     # gathered rows alone would take at those rates
-    if roofline and dom == "walk_fused" and w.O == w.D:
+    if headline and roofline and dom == "walk_fused" and w.O == w.D:
         es = 2 if w.dtype == W.DTYPE_BF16 else 4
         rb = w.D * es
         if rb % 16 == 0:
@@ -645,12 +769,12 @@ def main():
             for rows in (lo, 2 * lo):
                 table = torch.zeros((rows * rb,), dtype=torch.uint8, device="cuda")
                 for _ in range(2):
-                    nbytes = F.fff_probe_gather(table, rb, 4, 512, 16, True, sink)
+                    nbytes = probe_gather(torch, table, rb, 4, 512, 16, True, sink)
                 torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 for _ in range(5):
-                    F.fff_probe_gather(table, rb, 4, 512, 16, True, sink)
+                    probe_gather(torch, table, rb, 4, 512, 16, True, sink)
                 e1.record()
                 torch.cuda.synchronize()
                 rate = nbytes * 5 / (e0.elapsed_time(e1) * 1e-3)
@@ -674,14 +798,14 @@ def main():
         parity["max_rel_row_err"] = float((np.abs(got[keep] - ref_out[keep]).max(axis=1) / scale).max())
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not no_cpu:
         cpu = {"value": round(w.T * cpu_passes / cpu_s, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle",
                "sample": "all %d tokens of %s, %d passes, fp64, OpenMP over tokens" % (w.T, w.name, cpu_passes),
                "seconds": round(cpu_s, 3)}
 
     dense = None
-    if not args.no_dense and (1 << w.depth) * w.leaf_width <= 8192:
+    if not no_dense and (1 << w.depth) * w.leaf_width <= 8192:
         H = (1 << w.depth) * w.leaf_width          # equal training width
         W1 = dev["leaf_w1"].reshape(H, w.D)
         B1 = dev["leaf_b1"].reshape(H)
@@ -713,10 +837,12 @@ def main():
         "config": {"workload": "%s: %s" % (w.name, w.note), "T": w.T, "D": w.D, "O": w.O, "depth": w.depth,
                    "leaf_width": w.leaf_width, "act": "gelu" if w.act else "relu", "buffer_sets": nsets,
                    "seed": 0, "options": args.opt,
-                   "launch_path": path_names.get(F.fff_get_option("last_path"), "?")},
+                   "launch_path": path_names.get(F.fff_get_option("last_path"), "?"), "kernels": kernels},
         "roofline": roofline,
         "path": {"alg_bytes": alg["path"], "GBps": round(path_gbs, 1), "frac": round(path_gbs / HBM_PEAK_GBS, 4),
+                 "frac_of_copy_ceiling": round(path_gbs / copy_ceiling_once(torch)["GBps"], 4),
                  "u_node": alg["u_node"], "u_leaf": alg["u_leaf"]},
+        "copy_ceiling": copy_ceiling_once(torch),
         "stages": stages,
         "timing_stats": timing_stats,
         "cpu_baseline": cpu,
@@ -724,7 +850,9 @@ def main():
         "dense_ff": dense,
         "parity": parity,
     }
-    print(json.dumps(line))
+    del dev, xs, outs, idx
+    torch.cuda.empty_cache()
+    return line
 
 
 if __name__ == "__main__":

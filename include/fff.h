@@ -24,18 +24,26 @@
  *     the d decisions read as a binary number, root decision first.
  *   - Leaf k computes h = act(W1[k] x + b1[k]), y = W2[k]^T h + b2[k], with
  *     W1 [l, D] and W2 [l, O]: per neuron its D input weights, then its O
- *     output weights (the paper's "one set of neurons that has both input and
- *     output weights").
+ *     output weights (Definition, Section "Algorithm": a leaf is a <D, l, O>
+ *     feedforward network, one set of l neurons).
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only
- *     enqueue work on it and return; they never synchronise the device.
+ *     enqueue work on it and return; with one exception (next item) they
+ *     never allocate, free or synchronise the device.
  *   - Every call returns an fff_status.  Arguments are checked on the host
  *     before any HIP call is made: a bad argument returns its error code and
  *     enqueues nothing.  Nothing throws or aborts.
- *   - The library keeps one workspace per device (bucket tables, work lists).
- *     It is grown with hipMalloc when a call needs more than is there (never
- *     shrunk), so calls on one device must not overlap in time, and a caller
- *     that cannot tolerate an allocation mid-stream calls
- *     fff_reserve_workspace first.
+ *   - Workspace (bucket tables, work lists, intermediates; the size for given
+ *     arguments is what the fff_workspace_bytes* functions return).  Each
+ *     device has one, used by every call on that device, so calls on one
+ *     device must not overlap in time.  Either the caller provides it
+ *     (fff_set_workspace): then no call allocates, frees, clears with a
+ *     memset or synchronises, and a call that needs more than the caller gave
+ *     returns FFF_ERR_WORKSPACE before it enqueues anything.  Or the library
+ *     owns it: a call that needs more than is there frees the old block,
+ *     allocates a larger one and clears its control words -- the exception to
+ *     the rule above: hipFree waits for the device.  It cannot happen during
+ *     stream capture (such a call returns FFF_ERR_WORKSPACE instead), and not
+ *     at all after fff_reserve_workspace* with sizes at least as large.
  */
 #ifndef FFF_H
 #define FFF_H
@@ -54,7 +62,8 @@ typedef enum {
     FFF_ERR_DTYPE = 3,       /* unknown dtype */
     FFF_ERR_RANGE = 4,       /* depth / leaf_width / T out of range */
     FFF_ERR_UNSUPPORTED = 5, /* unknown activation or option */
-    FFF_ERR_WORKSPACE = 6,   /* workspace could not be allocated */
+    FFF_ERR_WORKSPACE = 6,   /* workspace too small (caller-provided, or growth needed during
+                                stream capture), misaligned, or could not be allocated */
     FFF_ERR_DEVICE = 7,      /* a HIP call failed (see fff_last_device_error) */
     FFF_ERR_ALIAS = 8        /* out overlaps x */
 } fff_status;
@@ -140,9 +149,8 @@ int fff_leaf_forward(const void* x, const void* leaf_w1, const void* leaf_b1,
  *   the leaves' layout (leaf_w1 [2^log2_experts, leaf_width, D], ...);
  *   expert_idx [T] int32 may be NULL; dtype must be FFF_BF16 with D % 8 == 0 and
  *   16-byte aligned rows (else FFF_ERR_UNSUPPORTED); other arguments, ownership,
- *   asynchrony and errors as for fff_forward_hard.  The gating needs
- *   2 * T * ceil(2^log2_experts / 128) more words of workspace than
- *   fff_workspace_bytes reports; the first call with larger sizes allocates them.
+ *   asynchrony and errors as for fff_forward_hard.  Workspace:
+ *   fff_workspace_bytes_moe(T, log2_experts).
  */
 int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b,
                          const void* leaf_w1, const void* leaf_b1, const void* leaf_w2,
@@ -165,9 +173,9 @@ int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b,
  *            (paragraph "Hardening")
  *   dtype must be FFF_BF16 with D % 8 == 0 and 16-byte aligned rows (else
  *   FFF_ERR_UNSUPPORTED); other arguments, ownership, asynchrony and errors as
- *   for fff_forward_hard.  Needs about
- *   4 T (2^(depth+1)) + 2 (T + O) 2^depth (leaf_width + 1) bytes of workspace,
- *   allocated by the first call with larger sizes (FFF_ERR_WORKSPACE if that fails).
+ *   for fff_forward_hard.  Workspace:
+ *   fff_workspace_bytes_soft(T, O, depth, leaf_width), about
+ *   4 T (2^(depth+1)) + 2 (T + O) 2^depth (leaf_width + 1) bytes.
  */
 int fff_forward_soft(const void* x, const void* node_w, const void* node_b,
                      const void* leaf_w1, const void* leaf_b1, const void* leaf_w2,
@@ -210,88 +218,77 @@ int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, 
                       int leaf_width, int act, int residual, void* out, int32_t* leaf_idx,
                       void* stream, int64_t T, int64_t D, int64_t O, int dtype);
 
-/* Bytes of workspace a call with these sizes uses on the current device. */
+/*
+ * Workspace sizes, in bytes (0 for arguments out of range).  Sizes follow from
+ * the Definition's counts alone: T tokens, 2^depth leaves (experts), leaves of
+ * leaf_width neurons, O outputs.
+ *   fff_workspace_bytes       fff_forward_hard, fff_descend, fff_bucket, fff_leaf_forward
+ *   fff_workspace_bytes_moe   fff_moe_top1_forward (the above plus the gating candidates)
+ *   fff_workspace_bytes_soft  fff_forward_soft (the dense intermediates)
+ * fff_forward_block uses none.
+ */
 size_t fff_workspace_bytes(int64_t T, int depth);
+size_t fff_workspace_bytes_moe(int64_t T, int log2_experts);
+size_t fff_workspace_bytes_soft(int64_t T, int64_t O, int depth, int leaf_width);
 
-/* Make sure the current device's workspace holds at least fff_workspace_bytes(T, depth)
- * (allocates now, so that later calls with sizes up to these do not). */
+/*
+ * fff_set_workspace: from now on every call on the current device works in the
+ * caller's memory: `dev_ptr` (device memory, 256-byte aligned, `bytes` long),
+ * which stays the caller's and must outlive the work that uses it.  The first
+ * 256 bytes are cleared by a small kernel enqueued on `stream`; later calls
+ * must be ordered after it (same stream, or an event).  While set, no call
+ * allocates, frees, memsets or synchronises: one that needs more than `bytes`
+ * returns FFF_ERR_WORKSPACE and enqueues nothing, so calls can be captured in
+ * a HIP graph with no preparation other than this one.  dev_ptr == NULL
+ * returns the device to the library-owned workspace (what it held is kept).
+ * Errors: FFF_ERR_WORKSPACE (misaligned, or shorter than 256 bytes),
+ * FFF_ERR_DEVICE.
+ */
+int fff_set_workspace(void* dev_ptr, size_t bytes, void* stream);
+
+/* Library-owned workspace: make sure the current device's holds at least
+ * fff_workspace_bytes(T, depth), or `bytes` (allocates now, so that later calls with
+ * sizes up to these do not).  FFF_ERR_WORKSPACE while a caller's workspace is set. */
 int fff_reserve_workspace(int64_t T, int depth);
+int fff_reserve_workspace_bytes(size_t bytes);
 
-/* Free the workspaces of all devices (call with no work in flight). */
+/* Free the library-owned workspaces of all devices (call with no work in flight). */
 int fff_release_workspace(void);
 
 /*
- * Tuning and test switches (process-wide; not thread-safe against running calls).
- *   "leaf_path"      staged path only: 0 = the MFMA tile kernels when the shape allows them
- *                    (bf16, 3 <= leaf_width <= 32, D % 8 == 0, O % 8 == 0, 16-byte aligned
- *                    rows) and a leaf sees at least 8 tokens on average or is wider than 8
- *                    neurons (32 tokens on average for batches of up to 8192 tokens), else
- *                    the gather kernel (default); 1 = always the gather kernel;
- *                    2 = the tile kernels whenever the shape allows them, also for
- *                    leaf_width 1 and 2
+ * Options (process-wide; not thread-safe against running calls).
  *   "path"           0 = choose by shape and batch size (default), 1 = one fused launch
- *                    (walk, leaf network and output row per token, tokens streamed through
- *                    persistent blocks; leaf_width <= 8), 2 = staged (descent, bucketing,
- *                    leaf kernels), 3 = the element-wise fallback kernel, 4 = one block per
- *                    token (small batches: several tree levels per memory round trip, the
- *                    leaf's neurons split over the block's waves; rows of at most 512
- *                    16-byte vectors); a path the shape does not allow falls back to one it
- *                    does.  The default takes 4 for batches of up to "token_max_T" tokens
- *                    (6 times that where leaf_width > 8 rules out the fused launch), then
- *                    staged when there are more than 8192 tokens, the leaf rows a token meets
- *                    are many bytes (24 KB, or 12 KB with more than 8 MB of leaf weights in
- *                    total, or 8 KB with more than 16 MB) and a leaf sees >= 3 tokens on
- *                    average, else fused
- *   "token_max_T"    see "path" (default 512)
- *   "walk_tpg", "walk_block", "walk_top", "walk_bpc", "walk_prefetch"
- *                    experiment switches of the fused/descent kernel (tokens per lane
- *                    group, threads per block, k + 1 = at most k LDS-staged levels,
- *                    persistent blocks per compute unit, next-tile prefetch); 0 = built-in
- *                    choice, combinations the kernel is not built for are ignored
+ *                    (walk, leaf network and output row per token; leaf_width <= 8),
+ *                    2 = staged (descent, bucketing, leaf kernels), 3 = the element-wise
+ *                    fallback kernel, 4 = one block per token (small batches); a path the
+ *                    shape does not allow falls back to one it does
+ *   "leaf_path"      staged path only: 0 = choose by shape and bucket size (default),
+ *                    1 = always the gather kernel, 2 = the MFMA tile kernels whenever the
+ *                    shape allows them (bf16, leaf_width <= 32, D % 8 == 0, O % 8 == 0,
+ *                    16-byte aligned rows)
  *   "bucketing"      1 (default) = the leaf kernel visits tokens grouped by leaf,
  *                    0 = in token order (no bucketing stage)
- *   "last_path"      read it after a call: the path (1, 2, 3 or 4) fff_forward_hard took
- *   "last_walk_top"  read it after a call: the tree levels the last descent or fused launch kept
- *                    in LDS
- *   "last_block_kernel" read it after fff_forward_block: 1 = a vector kernel ran, 2 = the
- *                    element-wise one
- *   "block_top"      fff_forward_block, rows of up to 128 pieces, 32768 tokens and more: the
- *                    hidden-neuron rows of the top node levels are kept in LDS by persistent
- *                    blocks; k + 1 = at most k such levels, 0 = as many as fit (default).
- *                    The results do not depend on it, bit for bit.
- *   "last_block_top" read it after fff_forward_block: the levels its launch kept in LDS
- *   "last_leaf_path" read it after a staged call: 1 = its leaf stage ran the gather kernel,
- *                    2 = the two tile kernels, 3 = both, each on its share of the tiles
- *   "leaf_split"     staged leaf stage on the tile kernels: 1..16 = a tile (16 consecutive
- *                    slots of the bucketed order) with at least this many runs of equal leaf
- *                    goes to the gather kernel instead; 0 (default) or above 16 = no split
- *   "bucket_kernel"  0 = choose by size (default: the token-chunk kernel up to 131072 tokens
- *                    and 4096 leaves; beyond that the segment kernels for up to 4096
- *                    leaves, else the leaf-range kernel up to 2^21 tokens and 2^19 leaves,
- *                    else the chunk-matrix kernels), 4 = the segment kernels when the sizes
- *                    allow them, 1 = the leaf-range kernel when the
- *                    sizes allow it, 2 = always the chunk-matrix kernels, 3 = the token-chunk
- *                    kernel when the sizes allow it
  *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages
  *                    (read them with fff_stage_times); 0 (default) = off
+ * Read-only, describing the last call: "last_path" (1..4 as above), "last_leaf_path"
+ * (1 = gather kernel, 2 = the two tile kernels, 3 = both, each on its share of the tiles),
+ * "last_walk_top" (tree levels the descent or fused launch kept in LDS),
+ * "last_block_kernel" (fff_forward_block: 1 = a vector kernel, 2 = the element-wise one),
+ * "last_block_top" (node levels fff_forward_block kept in LDS).
  * Unknown names or negative values return FFF_ERR_UNSUPPORTED.
  */
 int fff_set_option(const char* name, int64_t value);
 int fff_get_option(const char* name, int64_t* value);
 
 /*
- * fff_probe_gather: a measuring stick for the roofline discussion, not a step of
- * the method.  Launches `blocks` blocks of 512 threads; every 16 lanes read,
- * `iters` times, `rows_in_flight` (1 or 4) rows of `row_bytes` bytes picked at
- * random from `table` (device, table_rows rows, a power of two, 16-byte aligned,
- * row_bytes a multiple of 16; fill it with zeros) -- the access pattern of a
- * tree walk, one row per token and level.  `dependent` non-zero makes each row
- * index wait for the data of the previous one.  The caller times the launch;
- * bytes moved = blocks * 32 * iters * rows_in_flight * row_bytes.  `sink`: 4
- * bytes of device memory (never written for a table of zeros).
+ * Experiment switches of the kernels, for tests and profiles: tile shapes, LDS
+ * levels, kernel selection thresholds.  Results never depend on them beyond
+ * rounding order; names and meanings are listed where they are read
+ * (csrc/fff_api.hip, `debug_slot`) and are not a stable interface.  value < 0
+ * reads: the current value is returned through *current (may be NULL when
+ * setting).  FFF_ERR_UNSUPPORTED for an unknown name.
  */
-int fff_probe_gather(const void* table, int64_t table_rows, int64_t row_bytes, int rows_in_flight,
-                     int64_t blocks, int iters, int dependent, void* sink, void* stream);
+int fff_debug_option(const char* name, int64_t value, int64_t* current);
 
 /*
  * Waits for, sums and clears the stage events recorded since the last call:
@@ -309,6 +306,12 @@ const char* fff_status_string(int status);
 
 /* Text of the last HIP error seen on this thread's calls ("" if none). */
 const char* fff_last_device_error(void);
+
+/* The kernels the last forward call of this process launched, in order, joined by " + ", each
+ * with the tile parameters that select its instantiation, e.g.
+ * "walk_kernel<bf16,16,6,4,512,fused,tight> top=6".  For logs and for matching a measurement
+ * with the kernel it was taken on; valid until the next call. */
+const char* fff_last_launch(void);
 
 /* Library version as major * 10000 + minor * 100 + patch. */
 int fff_version(void);

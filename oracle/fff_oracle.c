@@ -91,6 +91,14 @@ static double activation(double v, int act) {
     return 0.5 * v * (1.0 + erf(v / sqrt(2.0)));   /* v * Phi(v) */
 }
 
+/* Several tokens may fail to get scratch memory at once: the shared status is written atomically. */
+static void flag_out_of_memory(int *err) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+    *err = 2;
+}
+
 static int args_ok(int depth, int leaf_width, int act, int64_t T, int64_t D, int64_t O, int dtype) {
     return depth >= 0 && depth <= 24 && leaf_width >= 1 && T >= 0 && D >= 1 && O >= 1 &&
            (act == ORACLE_ACT_RELU || act == ORACLE_ACT_GELU) && dtype >= 0 && dtype <= 2;
@@ -145,7 +153,7 @@ int fff_oracle_forward_hard(const void *x, const void *node_w, const void *node_
 #endif
     for (int64_t t = 0; t < T; ++t) {
         double *h = (double *)malloc(sizeof(double) * (size_t)leaf_width);
-        if (!h) { err = 2; continue; }
+        if (!h) { flag_out_of_memory(&err); continue; }
         int64_t n = 0;                 /* position within the current level */
         double mg = INFINITY;
         for (int m = 0; m < depth; ++m) {
@@ -178,7 +186,7 @@ int fff_oracle_leaf_forward(const void *x, const void *leaf_w1, const void *leaf
 #endif
     for (int64_t t = 0; t < T; ++t) {
         double *h = (double *)malloc(sizeof(double) * (size_t)leaf_width);
-        if (!h) { err = 2; continue; }
+        if (!h) { flag_out_of_memory(&err); continue; }
         leaf_eval(x, t * D, leaf_w1, leaf_b1, leaf_w2, leaf_b2, leaf_idx[t], leaf_width, act, D, O, dtype, h, out + t * O);
         free(h);
     }
@@ -308,7 +316,7 @@ int fff_oracle_moe_top1(const void *x, const void *gate_w, const void *gate_b, c
 #endif
     for (int64_t t = 0; t < T; ++t) {
         double *h = (double *)malloc(sizeof(double) * (size_t)leaf_width);
-        if (!h) { err = 2; continue; }
+        if (!h) { flag_out_of_memory(&err); continue; }
         double best = -INFINITY, second = -INFINITY, best_scale = 0.0, second_scale = 0.0;
         int64_t arg = 0;
         for (int64_t e = 0; e < n_experts; ++e) {
@@ -427,7 +435,7 @@ int fff_oracle_forward_block(const void *x, const void *ln_gamma, const void *ln
     for (int64_t t = 0; t < T; ++t) {
         double *z = (double *)malloc(sizeof(double) * (size_t)D);
         double *h = (double *)malloc(sizeof(double) * (size_t)leaf_width);
-        if (!z || !h) { err = 2; free(z); free(h); continue; }
+        if (!z || !h) { flag_out_of_memory(&err); free(z); free(h); continue; }
         if (norm) layer_norm(x, t * D, ln_gamma, ln_beta, ln_eps, D, dtype, z);
         else for (int64_t j = 0; j < D; ++j) z[j] = ld(x, t * D + j, dtype);
         int64_t n = 0;

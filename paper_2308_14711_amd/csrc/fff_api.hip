@@ -3,6 +3,8 @@
 // (Algorithm 1): descent -> bucketing -> leaf networks with fused output rows.
 #include <hip/hip_runtime.h>
 
+#include <cstdarg>
+#include <cstdio>
 #include <cstring>
 #include <mutex>
 #include <string>
@@ -15,10 +17,15 @@ namespace fff {
 namespace {
 
 thread_local std::string g_last_error;
+std::string g_last_launch;   // kernels of the last forward call (process-wide, like the "last_*" options)
 
+// One workspace per device: the library's own block (grown on demand), or the caller's
+// (fff_set_workspace), which takes precedence while it is set.
 struct DeviceWs {
-    void* base = nullptr;
+    void* base = nullptr;        // library-owned
     size_t bytes = 0;
+    void* user_base = nullptr;   // caller-provided
+    size_t user_bytes = 0;
 };
 constexpr int kMaxDevices = 64;
 DeviceWs g_ws[kMaxDevices];
@@ -36,6 +43,9 @@ struct Options {
     int64_t last_block_kernel = 0; // read-only: 1 = fff_forward_block ran a vector kernel, 2 = the element-wise one
     int64_t token_max_T = 512;   // batches up to this many tokens (6x where no fused launch fits) go one block per token
 } g_opt;
+
+// the vector L1 of a compute unit (not reported by the runtime)
+constexpr int64_t kVectorL1Bytes = 32 * 1024;
 
 // Events recorded around the stages of fff_forward_hard while "stage_timing" is on:
 // five per call (start, after descent, after bucketing, after the leaf stage's first kernel, after
@@ -97,6 +107,7 @@ Layout layout_for(int64_t T, int depth, int64_t extra_words = 0) {
 // launch checks below report this call's errors only.
 void begin_device_call() {
     g_last_error.clear();
+    g_last_launch.clear();
     (void)hipGetLastError();
 }
 
@@ -105,54 +116,90 @@ int set_device_error(hipError_t e, const char* what) {
     return FFF_ERR_DEVICE;
 }
 
-// Grows the current device's workspace if needed and carves it for (T, depth).
-int get_workspace(int64_t T, int depth, Workspace* ws, Layout* lay, int64_t extra_words = 0) {
-    *lay = layout_for(T, depth, extra_words);
-    const size_t need = (size_t)lay->total * sizeof(int32_t);
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+int current_device(int* dev) {
+    hipError_t e = hipGetDevice(dev);
     if (e != hipSuccess) return set_device_error(e, "hipGetDevice");
-    if (dev < 0 || dev >= kMaxDevices) {
+    if (*dev < 0 || *dev >= kMaxDevices) {
         g_last_error = "device ordinal out of range";
         return FFF_ERR_DEVICE;
     }
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceWs& d = g_ws[dev];
-    if (d.bytes < need) {
-        if (d.base) {
-            e = hipFree(d.base);   // waits for work that may still use it
-            d.base = nullptr;
-            d.bytes = 0;
-            if (e != hipSuccess) return set_device_error(e, "hipFree(workspace)");
-        }
-        void* p = nullptr;
-        e = hipMalloc(&p, need);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            g_last_error = std::string("hipMalloc(workspace): ") + hipGetErrorString(e);
+    return FFF_OK;
+}
+
+// Makes the current device's library-owned block at least `need` bytes (g_mu held).  Growing frees
+// the old block (which waits for the device) and cannot be done while `s` is being captured.
+int grow_owned(DeviceWs& d, size_t need, hipStream_t s, bool check_capture) {
+    if (d.bytes >= need) return FFF_OK;
+    if (check_capture) {
+        hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &st) != hipSuccess) (void)hipGetLastError();
+        if (st != hipStreamCaptureStatusNone) {
+            g_last_error = "workspace must grow to " + std::to_string(need) +
+                           " bytes, which cannot happen during stream capture: reserve or set it first";
             return FFF_ERR_WORKSPACE;
         }
-        e = hipMemset(p, 0, kCtrlWords * sizeof(int32_t));   // ticket counters start at zero
-        if (e != hipSuccess) {
-            (void)hipFree(p);
-            return set_device_error(e, "hipMemset(workspace)");
-        }
-        d.base = p;
-        d.bytes = need;
     }
-    int32_t* b = (int32_t*)d.base;
-    ws->ctrl = b + lay->o_ctrl;
-    ws->leaf_idx = b + lay->o_leaf;
-    ws->rank = b + lay->o_rank;
-    ws->slot_leaf = b + lay->o_sleaf;
-    ws->perm = b + lay->o_perm;
-    ws->count = b + lay->o_count;
-    ws->offset = b + lay->o_offset;
-    ws->tile_off = b + lay->o_tileoff;
-    ws->chunk_cnt = b + lay->o_matrix;
-    ws->hidden = b + lay->o_hidden;
-    ws->extra = b + lay->o_extra;
-    ws->n_chunks = lay->n_chunks;
+    hipError_t e;
+    if (d.base) {
+        e = hipFree(d.base);   // waits for work that may still use it
+        d.base = nullptr;
+        d.bytes = 0;
+        if (e != hipSuccess) return set_device_error(e, "hipFree(workspace)");
+    }
+    void* p = nullptr;
+    e = hipMalloc(&p, need);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        g_last_error = std::string("hipMalloc(workspace): ") + hipGetErrorString(e);
+        return FFF_ERR_WORKSPACE;
+    }
+    e = hipMemset(p, 0, kCtrlWords * sizeof(int32_t));   // ticket counters start at zero
+    if (e != hipSuccess) {
+        (void)hipFree(p);
+        return set_device_error(e, "hipMemset(workspace)");
+    }
+    d.base = p;
+    d.bytes = need;
+    return FFF_OK;
+}
+
+void carve(void* base, const Layout& lay, Workspace* ws) {
+    int32_t* b = (int32_t*)base;
+    ws->ctrl = b + lay.o_ctrl;
+    ws->leaf_idx = b + lay.o_leaf;
+    ws->rank = b + lay.o_rank;
+    ws->slot_leaf = b + lay.o_sleaf;
+    ws->perm = b + lay.o_perm;
+    ws->count = b + lay.o_count;
+    ws->offset = b + lay.o_offset;
+    ws->tile_off = b + lay.o_tileoff;
+    ws->chunk_cnt = b + lay.o_matrix;
+    ws->hidden = b + lay.o_hidden;
+    ws->extra = b + lay.o_extra;
+    ws->n_chunks = lay.n_chunks;
+}
+
+// The current device's workspace carved for (T, depth): the caller's if one is set (too small is
+// an error, nothing is allocated), else the library's own, grown if needed.
+int get_workspace(int64_t T, int depth, Workspace* ws, Layout* lay, hipStream_t s, int64_t extra_words = 0) {
+    *lay = layout_for(T, depth, extra_words);
+    const size_t need = (size_t)lay->total * sizeof(int32_t);
+    int dev = 0;
+    int rc = current_device(&dev);
+    if (rc != FFF_OK) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceWs& d = g_ws[dev];
+    if (d.user_base) {
+        if (d.user_bytes < need) {
+            g_last_error = "the caller's workspace holds " + std::to_string(d.user_bytes) + " bytes, this call needs " +
+                           std::to_string(need);
+            return FFF_ERR_WORKSPACE;
+        }
+        carve(d.user_base, *lay, ws);
+        return FFF_OK;
+    }
+    if ((rc = grow_owned(d, need, s, true)) != FFF_OK) return rc;
+    carve(d.base, *lay, ws);
     return FFF_OK;
 }
 
@@ -222,13 +269,17 @@ int choose_path(const Problem& p) {
     // half a token a leaf) the single launch wins again.  Up to 8192 tokens the fused launch, cut
     // into tiles of 32 tokens, is ahead for every leaf it takes (2048-8192 tokens, 8 neurons, depth
     // 9: 17-22 us against 25-31 staged; 16384 tokens: 42 against 34).
+    // In the device's own units: a token's leaf rows against the vector L1 of a compute unit
+    // (3/4, 3/8, 1/4 of its 32 KB), all leaf weights against the L2 of one XCD (2x, 4x its 4 MB),
+    // the batch against 32 tokens per compute unit.
+    const DeviceInfo di = device_info();
     const int64_t es = p.bf16 ? 2 : 4;
     const int64_t token_leaf_bytes = (p.L * (p.D + p.O) + p.O) * es;
     const int64_t leaf_bytes = token_leaf_bytes << p.depth;
-    const bool wide = token_leaf_bytes >= 24 * 1024 ||
-                      (token_leaf_bytes >= 12 * 1024 && leaf_bytes >= (int64_t)8 << 20) ||
-                      (token_leaf_bytes >= 8 * 1024 && leaf_bytes >= (int64_t)16 << 20);
-    const bool visited = p.T > 8192 && p.depth < 40 && p.T >= ((int64_t)3 << p.depth);
+    const bool wide = token_leaf_bytes * 4 >= 3 * kVectorL1Bytes ||
+                      (token_leaf_bytes * 8 >= 3 * kVectorL1Bytes && leaf_bytes >= 2 * di.l2_bytes) ||
+                      (token_leaf_bytes * 4 >= kVectorL1Bytes && leaf_bytes >= 4 * di.l2_bytes);
+    const bool visited = p.T > 32 * (int64_t)di.cus && p.depth < 40 && p.T >= ((int64_t)3 << p.depth);
     return (wide && visited) ? kPathStaged : kPathFused;
 }
 
@@ -282,7 +333,7 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
     // needs twice the time there); up to 8192 tokens only from 32 tokens a leaf (4096 tokens, 8
     // neurons, 8 tokens a leaf: 40 us against 32)
     const int64_t per_leaf = p.depth < 40 ? p.T >> p.depth : 0;
-    const bool filled = (p.T > 8192 && (p.L > 8 || per_leaf >= 8)) || per_leaf >= 32;
+    const bool filled = (p.T > 32 * (int64_t)device_info().cus && (p.L > 8 || per_leaf >= 8)) || per_leaf >= 32;
     const bool tiles = g_opt.leaf_path != 1 && tiles_shape_ok(p) &&
                        (g_opt.leaf_path == 2 || (p.L >= 3 && filled));
     // On request ("leaf_split"), tiles whose 16 slots hold that many different leaves or more are
@@ -312,12 +363,85 @@ int run_leaf_any(const Problem& p, const int32_t* leaf_idx, hipStream_t s) {
     }
     Workspace ws;
     Layout lay;
-    const int rc = get_workspace(p.T, p.depth, &ws, &lay);
+    const int rc = get_workspace(p.T, p.depth, &ws, &lay, s);
     if (rc != FFF_OK) return rc;
     return run_leaf_stage(p, leaf_idx, ws, s);   // falls back per shape inside
 }
 
+// Host-side argument checks of fff_forward_hard (no HIP call).  FFF_OK with *empty set: nothing to do.
+int check_forward_hard(const void* x, const void* node_w, const void* node_b, const void* leaf_w1,
+                       const void* leaf_b1, const void* leaf_w2, const void* leaf_b2, int depth, int leaf_width,
+                       int act, const void* out, int64_t T, int64_t D, int64_t O, int dtype, bool* empty) {
+    *empty = false;
+    int rc = check_common(depth, T, D, dtype);
+    if (rc == FFF_OK) rc = check_leaf(depth, leaf_width, act, T, D, O);
+    if (rc != FFF_OK) return rc;
+    if (T == 0) {
+        *empty = true;
+        return FFF_OK;
+    }
+    if (!x || !leaf_w1 || !leaf_b1 || !leaf_w2 || !leaf_b2 || !out) return FFF_ERR_NULL;
+    if (depth > 0 && (!node_w || !node_b)) return FFF_ERR_NULL;
+    const int64_t es = dtype == FFF_BF16 ? 2 : 4;
+    if (overlaps(x, T * D * es, out, T * O * es)) return FFF_ERR_ALIAS;
+    return FFF_OK;
+}
+
+// The launches of Forward_I.  fixed_scratch == nullptr: the staged path works in the device's
+// workspace and the stages are bracketed by events when "stage_timing" is on.  Otherwise that block
+// of device memory (large enough for layout_for(T, depth): the caller has checked) is carved
+// instead, its control words are cleared by a kernel first, and no event is created.
+int run_forward_hard(const Problem& p, int32_t* leaf_idx, hipStream_t s, void* fixed_scratch) {
+    const bool marks = fixed_scratch == nullptr;
+    const int path = choose_path(p);
+    g_opt.last_path = path;
+    if (path == kPathGeneric) {
+        hipError_t e = launch_fused_generic(p, leaf_idx, s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "generic kernel launch");
+    }
+    if (path == kPathToken) {
+        if (marks) stage_mark(s);
+        hipError_t e = launch_token_block(p, leaf_idx, s);
+        for (int k = 0; marks && k < 4; ++k) stage_mark(s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "token-block kernel launch");
+    }
+    if (path == kPathFused) {
+        if (marks) stage_mark(s);
+        hipError_t e = launch_walk_fused(p, leaf_idx, s);
+        for (int k = 0; marks && k < 4; ++k) stage_mark(s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "fused walk kernel launch");
+    }
+    Workspace ws;
+    Layout lay;
+    hipError_t e;
+    if (fixed_scratch) {
+        lay = layout_for(p.T, p.depth);
+        carve(fixed_scratch, lay, &ws);
+        if ((e = launch_zero(ws.ctrl, kCtrlWords, s)) != hipSuccess) return set_device_error(e, "zero kernel launch");
+    } else {
+        const int rc = get_workspace(p.T, p.depth, &ws, &lay, s);
+        if (rc != FFF_OK) return rc;
+    }
+    int32_t* li = leaf_idx ? leaf_idx : ws.leaf_idx;
+    if (marks) stage_mark(s);
+    e = launch_descend(p, li, s);
+    if (e != hipSuccess) return set_device_error(e, "descent kernel launch");
+    if (marks) stage_mark(s);
+    return run_leaf_stage(p, li, ws, s, marks);
+}
+
 }  // namespace
+
+void note_launch(const char* fmt, ...) {
+    char buf[256];
+    va_list ap;
+    va_start(ap, fmt);
+    std::vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (!g_last_launch.empty()) g_last_launch += " + ";
+    g_last_launch += buf;
+}
+
 }  // namespace fff
 
 using namespace fff;
@@ -328,47 +452,14 @@ int fff_forward_hard(const void* x, const void* node_w, const void* node_b, cons
                      const void* leaf_b1, const void* leaf_w2, const void* leaf_b2, int depth,
                      int leaf_width, int act, void* out, int32_t* leaf_idx, void* stream, int64_t T,
                      int64_t D, int64_t O, int dtype) {
-    int rc = check_common(depth, T, D, dtype);
-    if (rc == FFF_OK) rc = check_leaf(depth, leaf_width, act, T, D, O);
-    if (rc != FFF_OK) return rc;
-    if (T == 0) return FFF_OK;
-    if (!x || !leaf_w1 || !leaf_b1 || !leaf_w2 || !leaf_b2 || !out) return FFF_ERR_NULL;
-    if (depth > 0 && (!node_w || !node_b)) return FFF_ERR_NULL;
-    const int64_t es = dtype == FFF_BF16 ? 2 : 4;
-    if (overlaps(x, T * D * es, out, T * O * es)) return FFF_ERR_ALIAS;
-
+    bool empty = false;
+    const int rc = check_forward_hard(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, leaf_width, act,
+                                      out, T, D, O, dtype, &empty);
+    if (rc != FFF_OK || empty) return rc;
     Problem p{x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, leaf_idx,
               T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
-    hipStream_t s = (hipStream_t)stream;
     begin_device_call();
-
-    const int path = choose_path(p);
-    g_opt.last_path = path;
-    if (path == kPathGeneric) {
-        hipError_t e = launch_fused_generic(p, leaf_idx, s);
-        return e == hipSuccess ? FFF_OK : set_device_error(e, "generic kernel launch");
-    }
-    if (path == kPathToken) {
-        stage_mark(s);
-        hipError_t e = launch_token_block(p, leaf_idx, s);
-        for (int k = 0; k < 4; ++k) stage_mark(s);
-        return e == hipSuccess ? FFF_OK : set_device_error(e, "token-block kernel launch");
-    }
-    if (path == kPathFused) {
-        stage_mark(s);
-        hipError_t e = launch_walk_fused(p, leaf_idx, s);
-        for (int k = 0; k < 4; ++k) stage_mark(s);
-        return e == hipSuccess ? FFF_OK : set_device_error(e, "fused walk kernel launch");
-    }
-    Workspace ws;
-    Layout lay;
-    if ((rc = get_workspace(T, depth, &ws, &lay)) != FFF_OK) return rc;
-    int32_t* li = leaf_idx ? leaf_idx : ws.leaf_idx;
-    stage_mark(s);
-    hipError_t e = launch_descend(p, li, s);
-    if (e != hipSuccess) return set_device_error(e, "descent kernel launch");
-    stage_mark(s);
-    return run_leaf_stage(p, li, ws, s, true);
+    return run_forward_hard(p, leaf_idx, (hipStream_t)stream, nullptr);
 }
 
 int fff_descend(const void* x, const void* node_w, const void* node_b, int depth, int32_t* leaf_idx,
@@ -392,7 +483,7 @@ int fff_bucket(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, in
     begin_device_call();
     Workspace ws;
     Layout lay;
-    int rc = get_workspace(T, depth, &ws, &lay);
+    int rc = get_workspace(T, depth, &ws, &lay, (hipStream_t)stream);
     if (rc != FFF_OK) return rc;
     return run_bucket(leaf_idx, T, depth, ws, count, offset, perm, nullptr, (hipStream_t)stream);
 }
@@ -432,7 +523,7 @@ int fff_moe_top1_forward(const void* x, const void* gate_w, const void* gate_b, 
     hipStream_t s = (hipStream_t)stream;
     Workspace ws;
     Layout lay;
-    if ((rc = get_workspace(T, log2_experts, &ws, &lay, 2 * T * moe_gate_blocks(G))) != FFF_OK) return rc;
+    if ((rc = get_workspace(T, log2_experts, &ws, &lay, s, 2 * T * moe_gate_blocks(G))) != FFF_OK) return rc;
     int32_t* ei = expert_idx ? expert_idx : ws.leaf_idx;
     stage_mark(s);
     hipError_t e = launch_moe_gate(x, gate_w, gate_b, T, D, G, ws.extra, ei, s);
@@ -470,7 +561,7 @@ int fff_forward_soft(const void* x, const void* node_w, const void* node_b, cons
     begin_device_call();
     Workspace ws;
     Layout lay;
-    if ((rc = get_workspace(0, 0, &ws, &lay, words)) != FFF_OK) return rc;
+    if ((rc = get_workspace(0, 0, &ws, &lay, (hipStream_t)stream, words)) != FFF_OK) return rc;
     hipError_t e = launch_forward_soft(p, ws.extra, mix, entropy, (hipStream_t)stream);
     return e == hipSuccess ? FFF_OK : set_device_error(e, "soft forward kernel launch");
 }
@@ -510,31 +601,61 @@ int fff_forward_block(const void* x, const void* ln_gamma, const void* ln_beta, 
     return e == hipSuccess ? FFF_OK : set_device_error(e, "block kernel launch");
 }
 
-int fff_probe_gather(const void* table, int64_t table_rows, int64_t row_bytes, int rows_in_flight,
-                     int64_t blocks, int iters, int dependent, void* sink, void* stream) {
-    if (!table || !sink) return FFF_ERR_NULL;
-    if (table_rows < 1 || (table_rows & (table_rows - 1)) != 0 || table_rows > ((int64_t)1 << 30)) return FFF_ERR_RANGE;
-    if (row_bytes < 16 || row_bytes % 16 != 0 || row_bytes > ((int64_t)1 << 20)) return FFF_ERR_SHAPE;
-    if (blocks < 1 || blocks > ((int64_t)1 << 20) || iters < 1 || iters > (1 << 24)) return FFF_ERR_RANGE;
-    if (rows_in_flight != 1 && rows_in_flight != 4) return FFF_ERR_UNSUPPORTED;
-    if ((reinterpret_cast<uintptr_t>(table) & 15u) != 0) return FFF_ERR_UNSUPPORTED;
-    begin_device_call();
-    hipError_t e = launch_gather_probe(table, table_rows, (int)(row_bytes / 16), rows_in_flight, blocks, iters,
-                                       dependent != 0, (uint32_t*)sink, (hipStream_t)stream);
-    return e == hipSuccess ? FFF_OK : set_device_error(e, "gather probe launch");
-}
-
 size_t fff_workspace_bytes(int64_t T, int depth) {
     if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH) return 0;
     return (size_t)layout_for(T, depth).total * sizeof(int32_t);
 }
 
+size_t fff_workspace_bytes_moe(int64_t T, int log2_experts) {
+    if (T < 0 || T > kMaxTokens || log2_experts < 0 || log2_experts > FFF_MAX_DEPTH) return 0;
+    const int64_t G = (int64_t)1 << log2_experts;
+    return (size_t)layout_for(T, log2_experts, 2 * T * moe_gate_blocks(G)).total * sizeof(int32_t);
+}
+
+size_t fff_workspace_bytes_soft(int64_t T, int64_t O, int depth, int leaf_width) {
+    if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH || O < 1 || O > kMaxElems ||
+        leaf_width < 1 || leaf_width > kMaxLeafWidth)
+        return 0;
+    Problem p{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+              T, 8, O, depth, leaf_width, 0, true};
+    const int64_t words = soft_scratch_words(p);
+    if (words > kMaxElems / 4) return 0;
+    return (size_t)layout_for(0, 0, words).total * sizeof(int32_t);
+}
+
+int fff_set_workspace(void* dev_ptr, size_t bytes, void* stream) {
+    if (dev_ptr && ((reinterpret_cast<uintptr_t>(dev_ptr) & 255u) != 0 || bytes < kCtrlWords * sizeof(int32_t)))
+        return FFF_ERR_WORKSPACE;
+    begin_device_call();
+    int dev = 0;
+    int rc = current_device(&dev);
+    if (rc != FFF_OK) return rc;
+    if (dev_ptr) {   // ticket counters start at zero (a fill kernel: a memset node does not belong in a graph)
+        hipError_t e = launch_zero((int32_t*)dev_ptr, kCtrlWords, (hipStream_t)stream);
+        if (e != hipSuccess) return set_device_error(e, "zero kernel launch");
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_ws[dev].user_base = dev_ptr;
+    g_ws[dev].user_bytes = dev_ptr ? bytes : 0;
+    return FFF_OK;
+}
+
+int fff_reserve_workspace_bytes(size_t bytes) {
+    begin_device_call();
+    int dev = 0;
+    int rc = current_device(&dev);
+    if (rc != FFF_OK) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (g_ws[dev].user_base) {
+        g_last_error = "a caller-provided workspace is set on this device";
+        return FFF_ERR_WORKSPACE;
+    }
+    return grow_owned(g_ws[dev], bytes, nullptr, false);
+}
+
 int fff_reserve_workspace(int64_t T, int depth) {
     if (T < 0 || T > kMaxTokens || depth < 0 || depth > FFF_MAX_DEPTH) return FFF_ERR_RANGE;
-    begin_device_call();
-    Workspace ws;
-    Layout lay;
-    return get_workspace(T, depth, &ws, &lay);
+    return fff_reserve_workspace_bytes(fff_workspace_bytes(T, depth));
 }
 
 int fff_release_workspace(void) {
@@ -554,24 +675,45 @@ int fff_release_workspace(void) {
 
 static int64_t* option_slot(const char* name) {
     if (!name) return nullptr;
-    if (!std::strcmp(name, "leaf_path")) return &g_opt.leaf_path;
-    if (!std::strcmp(name, "leaf_split")) return &g_opt.leaf_split;
     if (!std::strcmp(name, "path")) return &g_opt.path;
+    if (!std::strcmp(name, "leaf_path")) return &g_opt.leaf_path;
+    if (!std::strcmp(name, "bucketing")) return &g_opt.bucketing;
+    if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
+    if (!std::strcmp(name, "last_path")) return &g_opt.last_path;
+    if (!std::strcmp(name, "last_leaf_path")) return &g_opt.last_leaf_path;
+    if (!std::strcmp(name, "last_walk_top")) return &g_walk_tuning.last_top;
+    if (!std::strcmp(name, "last_block_kernel")) return &g_opt.last_block_kernel;
+    if (!std::strcmp(name, "last_block_top")) return &g_block_tuning.last_top;
+    return nullptr;
+}
+
+// Experiment switches (fff_debug_option); 0 = the built-in choice everywhere.
+//   "token_max_T"    batches of up to this many tokens take the one-block-per-token launch (6 times
+//                    that where leaf_width > 8 rules out the fused launch); default 512
+//   "walk_tpg", "walk_block", "walk_top", "walk_bpc", "walk_prefetch"
+//                    descent / fused kernel: tokens per lane group, threads per block, k + 1 = at most
+//                    k LDS-staged levels, persistent blocks per compute unit, next-tile prefetch;
+//                    combinations the kernel is not built for are ignored
+//   "block_top"      fff_forward_block, persistent launch: k + 1 = at most k node levels in LDS
+//   "leaf_split"     staged leaf stage on the tile kernels: 1..16 = a tile (16 consecutive slots of the
+//                    bucketed order) with at least this many runs of equal leaf goes to the gather
+//                    kernel instead; 0 or above 16 = no split
+//   "bucket_kernel"  0 = choose by size (the token-chunk kernel up to 131072 tokens and 4096 leaves;
+//                    beyond that the segment kernels for up to 4096 leaves, else the leaf-range kernel
+//                    up to 2^21 tokens and 2^19 leaves, else the chunk-matrix kernels), 1 = the
+//                    leaf-range kernel, 2 = the chunk-matrix kernels, 3 = the token-chunk kernel,
+//                    4 = the segment kernels, each when the sizes allow it
+static int64_t* debug_slot(const char* name) {
+    if (!name) return nullptr;
     if (!std::strcmp(name, "token_max_T")) return &g_opt.token_max_T;
     if (!std::strcmp(name, "walk_tpg")) return &g_walk_tuning.tpg;
     if (!std::strcmp(name, "walk_block")) return &g_walk_tuning.block;
     if (!std::strcmp(name, "walk_top")) return &g_walk_tuning.top;
     if (!std::strcmp(name, "walk_bpc")) return &g_walk_tuning.bpc;
     if (!std::strcmp(name, "walk_prefetch")) return &g_walk_tuning.prefetch;
-    if (!std::strcmp(name, "last_walk_top")) return &g_walk_tuning.last_top;
-    if (!std::strcmp(name, "bucketing")) return &g_opt.bucketing;
-    if (!std::strcmp(name, "stage_timing")) return &g_opt.stage_timing;
-    if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
-    if (!std::strcmp(name, "last_path")) return &g_opt.last_path;
-    if (!std::strcmp(name, "last_leaf_path")) return &g_opt.last_leaf_path;
-    if (!std::strcmp(name, "last_block_kernel")) return &g_opt.last_block_kernel;
     if (!std::strcmp(name, "block_top")) return &g_block_tuning.top;
-    if (!std::strcmp(name, "last_block_top")) return &g_block_tuning.last_top;
+    if (!std::strcmp(name, "leaf_split")) return &g_opt.leaf_split;
+    if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
     return nullptr;
 }
 
@@ -590,6 +732,14 @@ int fff_get_option(const char* name, int64_t* value) {
     if (!s) return FFF_ERR_UNSUPPORTED;
     if (!value) return FFF_ERR_NULL;
     *value = *s;
+    return FFF_OK;
+}
+
+int fff_debug_option(const char* name, int64_t value, int64_t* current) {
+    int64_t* s = debug_slot(name);
+    if (!s) return FFF_ERR_UNSUPPORTED;
+    if (value >= 0) *s = value;
+    if (current) *current = *s;
     return FFF_OK;
 }
 
@@ -624,7 +774,7 @@ const char* fff_status_string(int status) {
         case FFF_ERR_DTYPE: return "unknown dtype";
         case FFF_ERR_RANGE: return "depth, leaf_width or T out of range";
         case FFF_ERR_UNSUPPORTED: return "unknown activation or option";
-        case FFF_ERR_WORKSPACE: return "workspace allocation failed";
+        case FFF_ERR_WORKSPACE: return "workspace too small, misaligned or not allocatable";
         case FFF_ERR_DEVICE: return "a HIP call failed";
         case FFF_ERR_ALIAS: return "out overlaps x";
         default: return "unknown status";
@@ -633,6 +783,8 @@ const char* fff_status_string(int status) {
 
 const char* fff_last_device_error(void) { return g_last_error.c_str(); }
 
-int fff_version(void) { return 200; }
+const char* fff_last_launch(void) { return g_last_launch.c_str(); }
+
+int fff_version(void) { return 300; }
 
 }  // extern "C"

@@ -496,6 +496,7 @@ template <bool BF16, int NV, bool TWO> hipError_t run_group(BlockArgs a, hipStre
         if (e != hipSuccess) return e;
         lds_allowed = lds_limit;
     }
+    note_launch("block_group_kernel<%s,%d,%s> n=%d top=%d", BF16 ? "bf16" : "f32", NV, TWO ? "hi+lo" : "plain", a.n, top);
     kern<<<dim3((unsigned)blocks), dim3(256), lds_bytes, s>>>(a);
     return hipGetLastError();
 }
@@ -568,6 +569,7 @@ __global__ __launch_bounds__(kWave) void block_generic_kernel(const BlockArgs a)
 }
 
 template <bool BF16, int NV> hipError_t run(const BlockArgs& a, int64_t blocks, hipStream_t s) {
+    note_launch("block_kernel<%s,%d> n=%d", BF16 ? "bf16" : "f32", NV, a.n);
     block_kernel<BF16, NV><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
     return hipGetLastError();
 }
@@ -624,6 +626,7 @@ hipError_t launch_forward_block(const Problem& p, const void* gamma, const void*
     g_block_tuning.last_top = 0;
     if (!vector_rows) {
         int64_t gblocks = p.T < 256 * 32 ? p.T : 256 * 32;
+        note_launch("block_generic_kernel<%s> n=%d", p.bf16 ? "bf16" : "f32", node_size);
         if (p.bf16) block_generic_kernel<true><<<dim3((unsigned)gblocks), dim3(kWave), 0, s>>>(a);
         else block_generic_kernel<false><<<dim3((unsigned)gblocks), dim3(kWave), 0, s>>>(a);
         return hipGetLastError();

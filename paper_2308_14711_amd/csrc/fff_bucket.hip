@@ -388,6 +388,7 @@ hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, 
     const int64_t blocks = (NL + per_block - 1) / per_block;
     const size_t lds = sizeof(int32_t) * (size_t)(kOnepassWaves * per_block + per_block + 2 * kOnepassWaves);
     const int vec = (reinterpret_cast<uintptr_t>(leaf_idx) & 15u) == 0;
+    note_launch("bucket_onepass_kernel");
     bucket_onepass_kernel<<<dim3((unsigned)blocks), dim3(1024), lds, s>>>(leaf_idx, T, NL, (int)per_block, vec,
                                                                           count, offset, perm, slot_leaf);
     return hipGetLastError();
@@ -510,6 +511,7 @@ hipError_t launch_bucket_hist(const int32_t* leaf_idx, int64_t T, int depth, int
     if (chunk < 64) chunk = 64;
     const int64_t blocks = (T + chunk - 1) / chunk;
     const int vec = (reinterpret_cast<uintptr_t>(leaf_idx) & 15u) == 0;
+    note_launch("bucket_hist_kernel<%s>", T < 65536 ? "16+16" : "32+32");
     if (T < 65536)
         bucket_hist_kernel<true><<<dim3((unsigned)blocks), dim3(1024), sizeof(uint32_t) * (size_t)NL, s>>>(
             leaf_idx, T, NL, chunk, vec, count, offset, perm, slot_leaf);
@@ -613,6 +615,7 @@ hipError_t launch_bucket_segments(const int32_t* leaf_idx, int64_t T, int depth,
     const int64_t NL = (int64_t)1 << depth;
     const int64_t n_segs = (T + kSegTokens - 1) / kSegTokens;
     hipError_t e;
+    note_launch("seg_count_kernel + bucket_scan_kernel%s", perm ? " + seg_scatter_kernel" : "");
     seg_count_kernel<<<dim3((unsigned)n_segs), dim3(kWave), 0, s>>>(leaf_idx, T, (int)NL, n_segs, ws.chunk_cnt);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     bucket_scan_kernel<<<dim3((unsigned)((NL + 15) / 16)), dim3(1024), 0, s>>>(
@@ -633,6 +636,7 @@ hipError_t launch_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Wo
     const int64_t per_round = (T + kChunkTokens - 1) / kChunkTokens;
     const int rounds = (int)((per_round + ws.n_chunks - 1) / ws.n_chunks);
     hipError_t e;
+    note_launch("bucket_rank_kernel + bucket_scan_kernel%s", perm ? " + bucket_scatter_kernel" : "");
     if (T > 0) {
         const int64_t blocks = (per_round + rounds - 1) / rounds;
         bucket_rank_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(leaf_idx, T, rounds, ws.n_chunks,

@@ -43,16 +43,22 @@ constexpr int kTilesMaxLeafWidth = 32;   // widest leaf the MFMA tile path takes
 
 bool vec_ok(const void* p, int64_t row_elems, bool bf16);
 
+// Every launch function names the kernel it starts, with the tile parameters that select the
+// instantiation ("walk_kernel<bf16,16,6,4,512,fused,tight>"); a forward call's names, joined by
+// " + ", are what fff_last_launch returns.
+void note_launch(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+
 // K1: tree descent.  leaf_idx[t] for all t (any shape: falls back to element loads).
 hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 // Descent + leaf network + output row in one launch; needs fused_shape_ok(p).
 hipError_t launch_walk_fused(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 // Experiment switches of the walk kernel (0 = the built-in choice).
-// Compute units, the dynamic LDS a block may ask for, and the index of the current device (cached).
+// Compute units, the dynamic LDS a block may ask for, the L2 of one XCD and the index of the current device (cached).
 struct DeviceInfo {
     int cus = 0;
     size_t lds_per_block = 0;
     int dev = 0;
+    int64_t l2_bytes = 0;   // one XCD's L2
 };
 DeviceInfo device_info();
 
@@ -145,12 +151,6 @@ hipError_t launch_forward_block(const Problem& p, const void* gamma, const void*
                                 const void* node_w1, const void* node_b1, const void* node_w2,
                                 const void* node_b2, int node_size, bool residual, int32_t* leaf_idx,
                                 hipStream_t s, bool vector_rows = true);
-
-// Row-gather microbenchmark (fff_probe.hip): `blocks` blocks of 512 threads, every 16 lanes read
-// `iters` times `rows_in_flight` (1 or 4) random rows of `pieces` 16-byte pieces from a table of
-// table_rows rows (a power of two).
-hipError_t launch_gather_probe(const void* table, int64_t table_rows, int pieces, int rows_in_flight,
-                               int64_t blocks, int iters, bool dependent, uint32_t* sink, hipStream_t s);
 
 // Whole forward pass in one launch, one token per lane group (any shape).
 hipError_t launch_fused_generic(const Problem& p, int32_t* leaf_idx, hipStream_t s);

@@ -179,6 +179,7 @@ static hipError_t run_gather(const Problem& p, const int32_t* leaf_idx, const in
     const int nvec = (int)(p.D / Elem<BF16>::kPerVec);
     const int out_vec = vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
     const int64_t blocks = ((p.T + kGroups - 1) / kGroups + kXcds - 1) / kXcds * kXcds;
+    note_launch("leaf_gather_kernel<%s,%d,%d>%s", BF16 ? "bf16" : "f32", LPT, NV, split > 0 ? " split" : "");
     leaf_gather_kernel<BF16, LPT, NV><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(
         (const uint4*)p.x, (const uint4*)p.leaf_w1, p.leaf_b1, p.leaf_w2, p.leaf_b2, leaf_idx, order,
         p.L, p.act, p.T, nvec, p.O, out_vec, p.out, slot_leaf, split);
@@ -190,6 +191,7 @@ static hipError_t run_generic(const Problem& p, const int32_t* leaf_in, const in
                               int32_t* leaf_out, hipStream_t s) {
     const int64_t blocks = (p.T + 3) / 4;
     const size_t lds = sizeof(float) * 4 * (size_t)p.L;
+    note_launch("fused_generic_kernel<%s>", BF16 ? "bf16" : "f32");
     fused_generic_kernel<BF16><<<dim3((unsigned)blocks), dim3(256), lds, s>>>(
         p.x, p.node_w, p.node_b, p.leaf_w1, p.leaf_b1, p.leaf_w2, p.leaf_b2, leaf_in, order, p.depth,
         p.L, p.act, p.T, p.D, p.O, p.out, leaf_out);

@@ -422,6 +422,7 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const i
     a.units_per_tile = (n_ranges + kRangesPerWave - 1) / kRangesPerWave;
     const int64_t blocks_h = ((a.n_tiles + 3) / 4 + kXcds - 1) / kXcds * kXcds;
     const bool wide = p.L > 16;
+    note_launch("leaf_hidden_kernel<%s,%d>", p.D % 64 != 0 ? "ktail" : "k64", wide ? 2 : 1);
     if (p.D % 64 != 0) {
         if (wide) leaf_hidden_kernel<true, 2><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
         else leaf_hidden_kernel<true, 1><<<dim3((unsigned)blocks_h), dim3(256), 0, s>>>(a);
@@ -433,6 +434,7 @@ hipError_t launch_leaf_tiles(const Problem& p, const int32_t* slot_leaf, const i
     if (e != hipSuccess) return e;
     if (between) between(s);
     const int64_t blocks_o = ((a.n_tiles * a.units_per_tile + 3) / 4 + kXcds - 1) / kXcds * kXcds;
+    note_launch("leaf_output_kernel<%s>", wide ? "wide" : "narrow");
     if (wide) leaf_output_kernel<true><<<dim3((unsigned)blocks_o), dim3(256), 0, s>>>(a);
     else leaf_output_kernel<false><<<dim3((unsigned)blocks_o), dim3(256), 0, s>>>(a);
     return hipGetLastError();

@@ -164,6 +164,7 @@ hipError_t launch_moe_gate(const void* x, const void* gate_w, const void* gate_b
     a.D = (int)D;
     a.n_ttiles = (T + kGateTokens - 1) / kGateTokens;
     const int64_t blocks = (a.n_ttiles * a.n_eblocks + kXcds - 1) / kXcds * kXcds;
+    note_launch("moe_gate_kernel + moe_pick_kernel");
     moe_gate_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

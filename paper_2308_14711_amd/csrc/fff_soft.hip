@@ -245,6 +245,9 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
     float* ent_part = (float*)w;
     const int64_t mb = (p.T + kTileM - 1) / kTileM;
     hipError_t e;
+    note_launch("%ssoft_mix_kernel + soft_hidden_kernel + soft_w2x_kernel + soft_out_kernel%s",
+                a.NN > 0 ? "soft_nodes_kernel + " : "",
+                entropy_out && a.NN > 0 ? " + soft_entropy_part_kernel + soft_entropy_sum_kernel" : "");
     if (a.NN > 0) {
         soft_nodes_kernel<<<dim3((unsigned)(mb * ((a.NN + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
         if ((e = hipGetLastError()) != hipSuccess) return e;

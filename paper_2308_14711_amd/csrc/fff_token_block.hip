@@ -279,6 +279,7 @@ hipError_t run_token(const Problem& p, int32_t* leaf_idx, const int32_t* given_l
         }
     }
     const int64_t blocks = p.T < kTokenMaxBlocks ? p.T : kTokenMaxBlocks;
+    note_launch("token_block_kernel<%s,%d,%d,%s>", BF16 ? "bf16" : "f32", NV, S, OUTVEC ? "vec" : "elem");
     kern<<<dim3((unsigned)blocks), dim3(kTokenBlock), lds_bytes, s>>>(a);
     return hipGetLastError();
 }

@@ -300,15 +300,16 @@ bool vec_ok(const void* p, int64_t row_elems, bool bf16) {
 DeviceInfo device_info() {
     static DeviceInfo info[64];
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DeviceInfo{256, 64 * 1024};
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DeviceInfo{256, 64 * 1024, 0, 4 << 20};
     if (info[dev].cus == 0) {
         hipDeviceProp_t p;
         if (hipGetDeviceProperties(&p, dev) == hipSuccess) {
             info[dev].cus = p.multiProcessorCount > 0 ? p.multiProcessorCount : 256;
             info[dev].lds_per_block = p.sharedMemPerBlockOptin > 0 ? p.sharedMemPerBlockOptin : p.sharedMemPerBlock;
+            info[dev].l2_bytes = p.l2CacheSize > 0 ? p.l2CacheSize : 4 << 20;
         } else {
             (void)hipGetLastError();
-            info[dev] = DeviceInfo{256, 64 * 1024};
+            info[dev] = DeviceInfo{256, 64 * 1024, 0, 4 << 20};
         }
         info[dev].dev = dev;
     }
@@ -378,6 +379,8 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     a.L = p.L;
     a.act = p.act;
     a.out_vec = FUSED && vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
+    note_launch("walk_kernel<%s,%d,%d,%d,%d,%s,%s%s> top=%d", BF16 ? "bf16" : "f32", LPT, NV, TPG, kWalkBlock,
+                FUSED ? "fused" : "descent", TIGHT ? "tight" : "checked", PREFETCH ? ",prefetch" : "", top);
     kern<<<dim3((unsigned)blocks), dim3(kWalkBlock), lds_bytes, s>>>(a);
     return hipGetLastError();
 }
@@ -482,6 +485,7 @@ hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     if (walk_shape_ok(p))
         return p.bf16 ? dispatch_walk<true, false>(p, leaf_idx, s) : dispatch_walk<false, false>(p, leaf_idx, s);
     const int64_t blocks = (p.T + 3) / 4;
+    note_launch("descend_generic_kernel<%s>", p.bf16 ? "bf16" : "f32");
     if (p.bf16)
         descend_generic_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(p.x, p.node_w, p.node_b, p.depth,
                                                                                  p.T, p.D, leaf_idx);

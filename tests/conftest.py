@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # a run against another build of the oracle (the sanitized one of test_oracle_sanitized.py)
+    other = os.environ.get("FFF_ORACLE_LIB")
+    if other:
+        import oracle
+        oracle.use_library(other)
 
 
 def _has_gpu():

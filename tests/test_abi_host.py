@@ -140,19 +140,164 @@ def test_forward_block_rejects_bad_arguments_on_the_host(L):
     assert blk(out=ctypes.c_void_p((1 << 20) + 32)) == ALIAS
 
 
-def test_probe_gather_rejects_bad_arguments_on_the_host(L):
-    OK, NULL, SHAPE, RANGE, UNSUP = 0, 1, 2, 4, 5
+def test_bench_probe_library_is_separate_and_checks_its_arguments():
+    """The microbenchmarks of bench.py live in a library of their own: the product ABI exports none
+    of them, and the probe library rejects bad arguments on the host."""
+    import paper_2308_14711_amd as F
+    from paper_2308_14711_amd import build
+    assert not hasattr(F.lib(), "fff_probe_gather") and not hasattr(F.lib(), "fffb_gather")
+    P = ctypes.CDLL(build.PROBE_LIB)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    P.fffb_gather.argtypes = [vp, i64, i64, i32, i64, i32, i32, vp, vp]
+    P.fffb_copy.argtypes = [vp, vp, i64, i64, vp]
     p = lambda mb: ctypes.c_void_p(mb << 20)
-    probe = lambda **kw: L.fff_probe_gather(kw.get("table", p(1)), kw.get("rows", 1024), kw.get("row_bytes", 1536),
-                                            kw.get("k", 4), kw.get("blocks", 8), kw.get("iters", 2), 1,
-                                            kw.get("sink", p(64)), None)
-    assert probe(table=None) == NULL
-    assert probe(sink=None) == NULL
-    assert probe(rows=1000) == RANGE                  # a power of two
-    assert probe(row_bytes=100) == SHAPE
-    assert probe(k=3) == UNSUP
-    assert probe(blocks=0) == RANGE
-    assert probe(iters=0) == RANGE
+    probe = lambda **kw: P.fffb_gather(kw.get("table", p(1)), kw.get("rows", 1024), kw.get("row_bytes", 1536),
+                                       kw.get("k", 4), kw.get("blocks", 8), kw.get("iters", 2), 1,
+                                       kw.get("sink", p(64)), None)
+    for bad in (dict(table=None), dict(sink=None), dict(rows=1000), dict(row_bytes=100), dict(k=3), dict(blocks=0),
+                dict(iters=0)):
+        assert probe(**bad) == -1, bad
+    assert P.fffb_copy(None, p(1), 1024, 8, None) == -1
+    assert P.fffb_copy(p(2), p(1), 1000, 8, None) == -1      # whole 16-byte pieces only
+    assert P.fffb_copy(p(2), p(1), 1024, 0, None) == -1
+
+
+def test_workspace_entries_on_the_host(L):
+    """Sizing functions and the argument checks of fff_set_workspace (no device is touched: a
+    misaligned or too short buffer is rejected before the first HIP call)."""
+    import paper_2308_14711_amd as F
+    WORKSPACE = 6
+    hard = F.fff_workspace_bytes(4096, 10)
+    assert F.fff_workspace_bytes_moe(4096, 10) > hard            # plus the gating candidates
+    assert F.fff_workspace_bytes_moe(4096, 30) == 0 and F.fff_workspace_bytes_moe(-1, 3) == 0
+    soft = F.fff_workspace_bytes_soft(1000, 768, 8, 8)
+    # the documented estimate: 4 T 2^(d+1) + 2 (T + O) 2^d (l + 1) bytes
+    est = 4 * 1000 * 512 + 2 * (1000 + 768) * 256 * 9
+    assert est <= soft <= est * 1.1 + 4096
+    assert F.fff_workspace_bytes_soft(1000, 0, 8, 8) == 0 and F.fff_workspace_bytes_soft(1000, 768, 25, 8) == 0
+    assert F.fff_workspace_bytes_soft(1 << 20, 768, 24, 8) == 0   # would not fit any device
+    assert L.fff_set_workspace(ctypes.c_void_p(4096 + 64), 1 << 20, None) == WORKSPACE   # not 256-byte aligned
+    assert L.fff_set_workspace(ctypes.c_void_p(4096), 100, None) == WORKSPACE           # shorter than the control words
+    assert "workspace" in F.fff_status_string(WORKSPACE)
+
+
+def test_debug_switches_are_not_public_options(L):
+    import paper_2308_14711_amd as F
+    UNSUP = 5
+    for name in ("walk_tpg", "walk_block", "walk_top", "walk_bpc", "walk_prefetch", "block_top", "leaf_split",
+                 "bucket_kernel", "token_max_T"):
+        assert L.fff_set_option(name.encode(), 1) == UNSUP
+        old = F.fff_debug_option(name)
+        assert F.fff_debug_option(name, 3) == 3 and F.fff_debug_option(name) == 3
+        F.fff_debug_option(name, old)
+    assert L.fff_debug_option(b"path", 1, None) == UNSUP          # a public option is not a debug switch
+    assert L.fff_debug_option(None, 1, None) == UNSUP
+
+
+def _layer(T=6, D=8, O=4, depth=2, L=3, dtype=None):
+    import torch
+    dtype = dtype or torch.float32
+    NN, NL = (1 << depth) - 1, 1 << depth
+    z = lambda *s: torch.zeros(s, dtype=dtype)
+    return dict(x=z(T, D), node_w=z(NN, D), node_b=z(NN), leaf_w1=z(NL, L, D), leaf_b1=z(NL, L), leaf_w2=z(NL, L, O),
+                leaf_b2=z(NL, O), out=z(T, O), leaf_idx=torch.zeros(T, dtype=torch.int32))
+
+
+def test_binding_checks_every_extent_before_the_library_sees_a_pointer():
+    """The C ABI takes pointers and sizes and cannot see what is behind them; the binding checks each
+    tensor against the sizes the Definition implies.  CPU tensors throughout: a call whose shapes are
+    right gets as far as the 'must live on the GPU' check, every wrong one stops before it with
+    FFF_ERR_SHAPE or FFF_ERR_DTYPE."""
+    import torch
+    import paper_2308_14711_amd as F
+    SHAPE, DTYPE = 2, 3
+
+    def hard(a, depth=2, L=3):
+        F.fff_forward_hard(a["x"], a["node_w"], a["node_b"], a["leaf_w1"], a["leaf_b1"], a["leaf_w2"], a["leaf_b2"],
+                           depth, L, 0, a["out"], a["leaf_idx"])
+
+    with pytest.raises(ValueError, match="GPU"):
+        hard(_layer())
+    z = torch.zeros
+    bad = {
+        "node_w": z(2, 8), "node_b": z(4), "leaf_w1": z(4, 3, 7), "leaf_b1": z(4, 2), "leaf_w2": z(3, 3, 4),
+        "leaf_b2": z(4, 5), "out": z(5, 4), "leaf_idx": z(5, dtype=torch.int32), "x": z(6, 8, 1),
+    }
+    for k, t in bad.items():
+        a = _layer()
+        a[k] = t
+        with pytest.raises(F.FffError) as e:
+            hard(a)
+        assert e.value.status == SHAPE, k
+    a = _layer()
+    with pytest.raises(F.FffError) as e:       # a depth that does not match the tables
+        hard(a, depth=3)
+    assert e.value.status == SHAPE
+    with pytest.raises(F.FffError) as e:       # a leaf width that does not match them
+        hard(a, L=2)
+    assert e.value.status == SHAPE
+    for k in ("node_w", "leaf_w1", "leaf_b2", "out"):
+        a = _layer()
+        a[k] = a[k].to(torch.bfloat16)         # fp32 tokens with bf16 weights
+        with pytest.raises(F.FffError) as e:
+            hard(a)
+        assert e.value.status == DTYPE, k
+    a = _layer()
+    a["leaf_idx"] = a["leaf_idx"].to(torch.int64)
+    with pytest.raises(F.FffError) as e:
+        hard(a)
+    assert e.value.status == DTYPE
+
+    # the stage entry points and the widened ones go through the same checks
+    a = _layer()
+    with pytest.raises(F.FffError) as e:
+        F.fff_descend(a["x"], a["node_w"][:2], a["node_b"], 2, a["leaf_idx"])
+    assert e.value.status == SHAPE
+    with pytest.raises(F.FffError) as e:
+        F.fff_bucket(a["leaf_idx"], 2, count=z(3, dtype=torch.int32))
+    assert e.value.status == SHAPE
+    with pytest.raises(F.FffError) as e:
+        F.fff_bucket(a["leaf_idx"].to(torch.int64), 2)
+    assert e.value.status == DTYPE
+    with pytest.raises(F.FffError) as e:
+        F.fff_leaf_forward(a["x"], a["leaf_w1"], a["leaf_b1"], a["leaf_w2"], a["leaf_b2"], a["leaf_idx"][:5], 2, 3, 0,
+                           a["out"])
+    assert e.value.status == SHAPE
+    b = _layer(dtype=torch.bfloat16)
+    with pytest.raises(F.FffError) as e:
+        F.fff_moe_top1_forward(b["x"], z(3, 8, dtype=torch.bfloat16), None, b["leaf_w1"], b["leaf_b1"], b["leaf_w2"],
+                               b["leaf_b2"], 2, 3, 0, b["out"])
+    assert e.value.status == SHAPE
+    with pytest.raises(F.FffError) as e:
+        F.fff_forward_soft(b["x"], b["node_w"], b["node_b"], b["leaf_w1"], b["leaf_b1"], b["leaf_w2"], b["leaf_b2"], 2, 3,
+                           0, b["out"], mix=z(6, 3))
+    assert e.value.status == SHAPE
+    with pytest.raises(F.FffError) as e:
+        F.fff_forward_soft(b["x"], b["node_w"], b["node_b"], b["leaf_w1"], b["leaf_b1"], b["leaf_w2"], b["leaf_b2"], 2, 3,
+                           0, b["out"], mix=z(6, 4, dtype=torch.bfloat16))
+    assert e.value.status == DTYPE
+    c = _layer(O=8)
+    with pytest.raises(F.FffError) as e:       # node networks of 2 hidden neurons, a table built for 3
+        F.fff_forward_block(c["x"], z(8), z(8), 1e-5, z(3, 3, 8), z(3, 2), z(3, 2), z(3), c["leaf_w1"], c["leaf_b1"],
+                            c["leaf_w2"], c["leaf_b2"], 2, 2, 3, 0, True, c["out"])
+    assert e.value.status == SHAPE
+    with pytest.raises(F.FffError) as e:
+        F.fff_forward_block(c["x"], z(7), z(8), 1e-5, z(3, 2, 8), z(3, 2), z(3, 2), z(3), c["leaf_w1"], c["leaf_b1"],
+                            c["leaf_w2"], c["leaf_b2"], 2, 2, 3, 0, True, c["out"])
+    assert e.value.status == SHAPE
+    with pytest.raises(ValueError, match="GPU"):
+        F.fff_forward_block(c["x"], z(8), z(8), 1e-5, z(3, 2, 8), z(3, 2), z(3, 2), z(3), c["leaf_w1"], c["leaf_b1"],
+                            c["leaf_w2"], c["leaf_b2"], 2, 2, 3, 0, True, c["out"])
+
+
+def test_packed_fp32_forms_are_really_switched_off():
+    """The build passes a target feature that the host pass of hipcc does not know (and says so); what
+    matters is the device pass: with the flag no packed fp32 VALU instruction may be left in the gfx950
+    assembly of a kernel that otherwise gets them."""
+    from paper_2308_14711_amd import build
+    with_flag, without = build.packed_fp32_counts()
+    assert with_flag == 0
+    assert without > 0, "the probe kernel no longer invites packed instructions: the check shows nothing"
 
 
 def test_header_is_plain_c99_and_links_from_c(tmp_path):

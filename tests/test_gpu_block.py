@@ -171,7 +171,7 @@ def test_block_with_top_levels_in_lds(case):
     outs = []
     try:
         for top_option, expect in ((0, top), (2, 1), (1, 0)):
-            F.fff_set_option("block_top", top_option)
+            F.fff_debug_option("block_top", top_option)
             out = torch.empty((T, O), dtype=d[0].dtype, device="cuda")
             idx = torch.empty((T,), dtype=torch.int32, device="cuda")
             F.fff_forward_block(d[0], d[1], d[2], 1e-5, *d_w, depth, n, L, act, residual, out, idx)
@@ -179,7 +179,7 @@ def test_block_with_top_levels_in_lds(case):
             assert F.fff_get_option("last_block_top") == expect
             outs.append((out, idx))
     finally:
-        F.fff_set_option("block_top", 0)
+        F.fff_debug_option("block_top", 0)
     for out, idx in outs[1:]:
         assert torch.equal(outs[0][1], idx) and torch.equal(outs[0][0].view(bits), out.view(bits))
 

@@ -21,6 +21,9 @@ CASES = [
     ("bucketed",       5000, 256, 128, 6,  4,  True),
     ("bucketed_wide",  9000, 768, 768, 3,  32, False),
     ("many_experts",   129,  96,  24,  12, 1,  True),
+    # the end point of the paper's sweep (section "Inference speed comparison": 768-wide, experts of 32
+    # neurons, batch 256, up to 2^15 experts), at full size
+    ("sweep_end",      256,  768, 768, 15, 32, True),
 ]
 
 
@@ -30,7 +33,7 @@ def test_moe_top1_against_the_oracle(case):
     import paper_2308_14711_amd as F
     name, T, D, O, g, L, bias = case
     print("\n[case] moe %s T=%d D=%d O=%d experts=2^%d L=%d bias=%s seed 3" % (name, T, D, O, g, L, bias), flush=True)
-    w = W.make_layer(name, T, D, O, g, L, W.ACT_GELU, W.DTYPE_BF16, seed=3)
+    w = W.make_layer(name, T, D, O, g, L, W.ACT_GELU, W.DTYPE_BF16, seed=3, keep_f32=g < 14)
     gw, gb = W.moe_gate(1 << g, D, W.DTYPE_BF16, seed=3)
     dev = to_device(w)
     up = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)

@@ -225,7 +225,7 @@ def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
     import torch
     import paper_2308_14711_amd as F
     print("\n[case] bucket depth=%d T=%d %s kernel=%d" % (depth, T, kind, kernel), flush=True)
-    F.fff_set_option("bucket_kernel", kernel)
+    F.fff_debug_option("bucket_kernel", kernel)
     rng = np.random.default_rng(depth * 1000 + T)
     NL = 1 << depth
     if kind == "u":
@@ -250,7 +250,7 @@ def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
             assert np.array_equal(d_offset.cpu().numpy(), offset)
             assert np.array_equal(d_perm.cpu().numpy(), perm)
     finally:
-        F.fff_set_option("bucket_kernel", 0)
+        F.fff_debug_option("bucket_kernel", 0)
 
 
 def test_descend_and_leaf_stages():
@@ -353,7 +353,7 @@ def test_walk_kernel_switches(switches, path):
     w = W.make_layer("switches", T, D, D, 9, 1, W.ACT_GELU, W.DTYPE_BF16, seed=31, keep_f32=False)
     F.fff_set_option("path", path)
     for k, v in opts.items():
-        F.fff_set_option(k, v)
+        F.fff_debug_option(k, v)
     try:
         out, idx = run_forward(w)
         if "walk_top" in opts:
@@ -361,7 +361,7 @@ def test_walk_kernel_switches(switches, path):
     finally:
         F.fff_set_option("path", 0)
         for k in opts:
-            F.fff_set_option(k, 0)
+            F.fff_debug_option(k, 0)
     _log("switches %s path=%d" % (opts, path), check_against_oracle(w, out, idx))
 
 
@@ -370,15 +370,15 @@ def test_token_block_threshold_option():
     import paper_2308_14711_amd as F
     print("\n[case] token_max_T T=700 D=256 depth=6 L=2 bf16 seed 8", flush=True)
     w = W.make_layer("threshold", 700, 256, 64, 6, 2, W.ACT_RELU, W.DTYPE_BF16, seed=8)
-    old = F.fff_get_option("token_max_T")
+    old = F.fff_debug_option("token_max_T")
     try:
         for limit, expect in ((0, 1), (699, 1), (700, 4), (old, 1 if old < 700 else 4)):
-            F.fff_set_option("token_max_T", limit)
+            F.fff_debug_option("token_max_T", limit)
             out, idx = run_forward(w)
             assert F.fff_get_option("last_path") == expect, "token_max_T=%d took path %d" % (limit, F.fff_get_option("last_path"))
             _log("threshold %d" % limit, check_against_oracle(w, out, idx))
     finally:
-        F.fff_set_option("token_max_T", old)
+        F.fff_debug_option("token_max_T", old)
 
 
 SPLIT_CASES = [
@@ -408,14 +408,14 @@ def test_leaf_stage_split_between_tile_and_gather_kernels(case):
         _log("split %s auto" % name, check_against_oracle(w, out, idx))
         F.fff_set_option("leaf_path", 2)
         for split in (1, 2, 5, 8, 13, 16, 17, 0):
-            F.fff_set_option("leaf_split", split)
+            F.fff_debug_option("leaf_split", split)
             out, idx = run_forward(w)
             assert F.fff_get_option("last_leaf_path") == (3 if 1 <= split <= 16 else 2)
             _log("split %s %d" % (name, split), check_against_oracle(w, out, idx))
     finally:
         F.fff_set_option("path", 0)
         F.fff_set_option("leaf_path", 0)
-        F.fff_set_option("leaf_split", 0)
+        F.fff_debug_option("leaf_split", 0)
 
 
 @pytest.mark.parametrize("path", [1, 2, 4], ids=["fused", "staged", "token"])
