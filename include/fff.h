@@ -106,6 +106,29 @@ int fff_forward_hard(const void* x, const void* node_w, const void* node_b,
                      int64_t T, int64_t D, int64_t O, int dtype);
 
 /*
+ * fff_forward_hard_static: for callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc -- and do not want to manage a
+ * workspace either.  Same arguments, same kernels, same results as fff_forward_hard, but the
+ * intermediates of the staged path (bucket tables, the grouped token order, hidden activations)
+ * live in a fixed block of fff_static_scratch_bytes() = 16 MiB inside the library's device image:
+ * the call allocates nothing, frees nothing, creates no event ("stage_timing" is ignored) and
+ * never touches the device's workspace.  Every GPU the library runs on holds that block until the
+ * process ends.  Sizes whose intermediates do not fit (fff_workspace_bytes(T, depth) above
+ * fff_static_scratch_bytes(); the five workloads of this library's benchmark all fit) return
+ * FFF_ERR_WORKSPACE and enqueue nothing (the text of fff_last_device_error says how much was needed).
+ * All calls on one GPU share the one block, which keeps the last call's contents: the call clears
+ * the words that must start at zero itself, and two calls whose work overlaps in time on one GPU
+ * (different streams, or a replaying graph beside an eager call) race.
+ */
+int fff_forward_hard_static(const void* x, const void* node_w, const void* node_b,
+                            const void* leaf_w1, const void* leaf_b1,
+                            const void* leaf_w2, const void* leaf_b2,
+                            int depth, int leaf_width, int act,
+                            void* out, int32_t* leaf_idx, void* stream,
+                            int64_t T, int64_t D, int64_t O, int dtype);
+size_t fff_static_scratch_bytes(void);
+
+/*
  * The stages of fff_forward_hard on their own (same conventions, same
  * kernels); used by tests and profiles.
  *

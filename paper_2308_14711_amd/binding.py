@@ -50,6 +50,9 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(_build.LIB)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
         L.fff_forward_hard.argtypes = [vp] * 7 + [i32, i32, i32, vp, vp, vp, i64, i64, i64, i32]
+        L.fff_forward_hard_static.argtypes = L.fff_forward_hard.argtypes
+        L.fff_static_scratch_bytes.argtypes = []
+        L.fff_static_scratch_bytes.restype = ctypes.c_size_t
         L.fff_descend.argtypes = [vp, vp, vp, i32, vp, vp, i64, i64, i32]
         L.fff_bucket.argtypes = [vp, i64, i32, vp, vp, vp, vp]
         L.fff_leaf_forward.argtypes = [vp] * 6 + [i32, i32, i32, vp, vp, i64, i64, i64, i32]
@@ -154,9 +157,10 @@ def _check_leaves(where, x, T, D, O, depth, leaf_width, leaf_w1, leaf_b1, leaf_w
 
 
 def fff_forward_hard(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, leaf_width, act,
-                     out, leaf_idx=None, stream=None) -> None:
-    """Forward_I for x [T, D] -> out [T, O] (and leaf_idx [T] int32 if given)."""
-    where = "fff_forward_hard"
+                     out, leaf_idx=None, stream=None, static_scratch=False) -> None:
+    """Forward_I for x [T, D] -> out [T, O] (and leaf_idx [T] int32 if given).  static_scratch=True
+    calls fff_forward_hard_static, the variant that allocates nothing."""
+    where = "fff_forward_hard_static" if static_scratch else "fff_forward_hard"
     T, D = _rows(where, "x", x)
     _, O = _rows(where, "out", out)
     if _in_range(depth, leaf_width):
@@ -165,10 +169,20 @@ def fff_forward_hard(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, dept
             _expect(where, "node_b", node_b, ((1 << depth) - 1,), x.dtype)
         _check_leaves(where, x, T, D, O, depth, leaf_width, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, leaf_idx, "leaf_idx")
     _check_dense(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, leaf_idx)
-    _check(lib().fff_forward_hard(_ptr(x), _ptr(node_w), _ptr(node_b), _ptr(leaf_w1), _ptr(leaf_b1),
-                                  _ptr(leaf_w2), _ptr(leaf_b2), depth, leaf_width, act, _ptr(out),
-                                  _ptr(leaf_idx), _stream_handle(stream), T, D, O, _dtype_code(x)),
+    entry = lib().fff_forward_hard_static if static_scratch else lib().fff_forward_hard
+    _check(entry(_ptr(x), _ptr(node_w), _ptr(node_b), _ptr(leaf_w1), _ptr(leaf_b1), _ptr(leaf_w2), _ptr(leaf_b2),
+                 depth, leaf_width, act, _ptr(out), _ptr(leaf_idx), _stream_handle(stream), T, D, O, _dtype_code(x)),
            where)
+
+
+def fff_forward_hard_static(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, leaf_width, act,
+                            out, leaf_idx=None, stream=None) -> None:
+    fff_forward_hard(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, leaf_width, act, out, leaf_idx,
+                     stream, static_scratch=True)
+
+
+def fff_static_scratch_bytes() -> int:
+    return int(lib().fff_static_scratch_bytes())
 
 
 def fff_descend(x, node_w, node_b, depth, leaf_idx, stream=None) -> None:

@@ -13,6 +13,14 @@
 #include "../../include/fff.h"
 #include "fff_internal.h"
 
+// Scratch of fff_forward_hard_static, the entry point for callers that cannot allocate: a fixed
+// block in the device image of this library, so every GPU the library runs on holds one copy of it
+// (at an address of its own) until the process ends.  The name is a host-side stand-in: host code
+// never passes it anywhere, it asks each device for the array's address once (scratch_on_device)
+// and uses that pointer.
+#define FFF_STATIC_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char scratch[FFF_STATIC_SCRATCH_BYTES];
+
 namespace fff {
 namespace {
 
@@ -387,6 +395,25 @@ int check_forward_hard(const void* x, const void* node_w, const void* node_b, co
     return FFF_OK;
 }
 
+// The address of `scratch` on the current device, asked for once per device with that device
+// current (each device has its own copy of the array).
+void* g_scratch_ptr[kMaxDevices];
+
+int scratch_on_device(void** ptr) {
+    int dev = 0;
+    const int rc = current_device(&dev);
+    if (rc != FFF_OK) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return set_device_error(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return FFF_OK;
+}
+
 // The launches of Forward_I.  fixed_scratch == nullptr: the staged path works in the device's
 // workspace and the stages are bracketed by events when "stage_timing" is on.  Otherwise that block
 // of device memory (large enough for layout_for(T, depth): the caller has checked) is carved
@@ -461,6 +488,32 @@ int fff_forward_hard(const void* x, const void* node_w, const void* node_b, cons
     begin_device_call();
     return run_forward_hard(p, leaf_idx, (hipStream_t)stream, nullptr);
 }
+
+int fff_forward_hard_static(const void* x, const void* node_w, const void* node_b, const void* leaf_w1,
+                            const void* leaf_b1, const void* leaf_w2, const void* leaf_b2, int depth,
+                            int leaf_width, int act, void* out, int32_t* leaf_idx, void* stream, int64_t T,
+                            int64_t D, int64_t O, int dtype) {
+    bool empty = false;
+    const int rc = check_forward_hard(x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, depth, leaf_width, act,
+                                      out, T, D, O, dtype, &empty);
+    if (rc != FFF_OK || empty) return rc;
+    const size_t need = (size_t)layout_for(T, depth).total * sizeof(int32_t);
+    if (need > FFF_STATIC_SCRATCH_BYTES) {
+        g_last_error = "fff_forward_hard_static: T = " + std::to_string(T) + ", depth = " + std::to_string(depth) +
+                       " need " + std::to_string(need) + " bytes of scratch, the static array holds " +
+                       std::to_string((size_t)FFF_STATIC_SCRATCH_BYTES);
+        return FFF_ERR_WORKSPACE;
+    }
+    Problem p{x, node_w, node_b, leaf_w1, leaf_b1, leaf_w2, leaf_b2, out, leaf_idx,
+              T, D, O, depth, leaf_width, act, dtype == FFF_BF16};
+    begin_device_call();
+    void* ptr = nullptr;
+    const int rs = scratch_on_device(&ptr);
+    if (rs != FFF_OK) return rs;
+    return run_forward_hard(p, leaf_idx, (hipStream_t)stream, ptr);
+}
+
+size_t fff_static_scratch_bytes(void) { return FFF_STATIC_SCRATCH_BYTES; }
 
 int fff_descend(const void* x, const void* node_w, const void* node_b, int depth, int32_t* leaf_idx,
                 void* stream, int64_t T, int64_t D, int dtype) {
