@@ -582,7 +582,10 @@ def main():
     F.lib()   # fail loudly here if the HIP library is missing
     for kv in args.opt:
         k, v = kv.split("=")
-        F.fff_set_option(k, int(v))
+        try:
+            F.fff_set_option(k, int(v))
+        except F.FffError:
+            F.fff_debug_option(k, int(v))      # an experiment switch of the kernels
 
     if args.sweep == "widths":
         width_sweep(args, np, torch, W, F)

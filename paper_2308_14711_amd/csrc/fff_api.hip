@@ -80,7 +80,7 @@ int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
     int64_t n_chunks;
-    int64_t o_ctrl, o_leaf, o_rank, o_sleaf, o_perm, o_count, o_offset, o_tileoff, o_matrix, o_hidden, o_extra, total;
+    int64_t o_ctrl, o_leaf, o_rank, o_sleaf, o_perm, o_count, o_offset, o_tileoff, o_matrix, o_fold, o_hidden, o_extra, total;
 };
 
 // extra_words: room for a caller-specific scratch region (the gating candidates of the mixture of experts)
@@ -104,6 +104,7 @@ Layout layout_for(int64_t T, int depth, int64_t extra_words = 0) {
     l.o_offset = take(NL + 1);
     l.o_tileoff = take(NL + 1);
     l.o_matrix = take(c * NL);
+    l.o_fold = take(T > 0 && depth <= 10 ? kFoldWords : 0);   // per-block leaf counts of the descent
     l.o_hidden = take((int64_t)(kTilesMaxLeafWidth / 2) * T);   // T * L bf16 values, L up to the tile path's limit
     l.o_extra = take(extra_words);
     l.total = o;
@@ -182,6 +183,7 @@ void carve(void* base, const Layout& lay, Workspace* ws) {
     ws->offset = b + lay.o_offset;
     ws->tile_off = b + lay.o_tileoff;
     ws->chunk_cnt = b + lay.o_matrix;
+    ws->fold = b + lay.o_fold;
     ws->hidden = b + lay.o_hidden;
     ws->extra = b + lay.o_extra;
     ws->n_chunks = lay.n_chunks;
@@ -292,9 +294,25 @@ int choose_path(const Problem& p) {
 }
 
 // K2 with whichever kernel set takes the sizes; outputs may be null (then workspace arrays are used).
+// dc (optional): per-block leaf counts the descent left behind; then one fold launch finishes the job.
 int run_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& ws, int32_t* count,
-               int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s) {
+               int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s, const DescentCounts* dc = nullptr) {
     hipError_t e;
+    if (dc && dc->blocks > 0 && (g_opt.bucket_kernel == 0 || g_opt.bucket_kernel == 5)) {
+        e = launch_bucket_fold(leaf_idx, T, depth, *dc, count, offset, perm, slot_leaf, s);
+        return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
+    }
+    if (g_opt.bucket_kernel == 5 && T > 0 && depth <= 10) {   // the same kernel fed by a counting launch of its own
+        DescentCounts own;
+        own.M = ws.fold;
+        own.capacity = kFoldWords;
+        if ((e = launch_chunk_counts(leaf_idx, T, depth, &own, s)) != hipSuccess)
+            return set_device_error(e, "bucket kernel launch");
+        if (own.blocks > 0) {
+            e = launch_bucket_fold(leaf_idx, T, depth, own, count, offset, perm, slot_leaf, s);
+            return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
+        }
+    }
     if ((g_opt.bucket_kernel == 0 || g_opt.bucket_kernel == 3) && bucket_hist_ok(T, depth)) {
         e = launch_bucket_hist(leaf_idx, T, depth, count, offset, perm, slot_leaf, s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "bucket kernel launch");
@@ -321,7 +339,7 @@ int run_bucket(const int32_t* leaf_idx, int64_t T, int depth, const Workspace& w
 }
 
 int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& ws, hipStream_t s,
-                   bool timed = false) {
+                   bool timed = false, const DescentCounts* dc = nullptr) {
     hipError_t e;
     if (!g_opt.bucketing) {
         if (timed) stage_mark(s);
@@ -331,7 +349,7 @@ int run_leaf_stage(const Problem& p, const int32_t* leaf_idx, const Workspace& w
         if (timed) stage_mark(s);
         return e == hipSuccess ? FFF_OK : set_device_error(e, "leaf kernel launch");
     }
-    const int rc = run_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, ws.slot_leaf, s);
+    const int rc = run_bucket(leaf_idx, p.T, p.depth, ws, nullptr, nullptr, ws.perm, ws.slot_leaf, s, dc);
     if (rc != FFF_OK) return rc;
     if (timed) stage_mark(s);
     // the MFMA tile path pays once a leaf has a few neurons (for 1-2 the VALU gather kernel is leaner)
@@ -450,11 +468,16 @@ int run_forward_hard(const Problem& p, int32_t* leaf_idx, hipStream_t s, void* f
         if (rc != FFF_OK) return rc;
     }
     int32_t* li = leaf_idx ? leaf_idx : ws.leaf_idx;
+    // the descent leaves per-block leaf counts for the bucketing stage where the sizes allow it
+    DescentCounts dc;
+    const bool fold = g_opt.bucketing && p.depth <= 10 && (g_opt.bucket_kernel == 0 || g_opt.bucket_kernel == 5);
+    dc.M = fold ? ws.fold : nullptr;
+    dc.capacity = kFoldWords;
     if (marks) stage_mark(s);
-    e = launch_descend(p, li, s);
+    e = launch_descend(p, li, s, &dc);
     if (e != hipSuccess) return set_device_error(e, "descent kernel launch");
     if (marks) stage_mark(s);
-    return run_leaf_stage(p, li, ws, s, marks);
+    return run_leaf_stage(p, li, ws, s, marks, &dc);
 }
 
 }  // namespace
@@ -755,7 +778,12 @@ static int64_t* option_slot(const char* name) {
 //                    beyond that the segment kernels for up to 4096 leaves, else the leaf-range kernel
 //                    up to 2^21 tokens and 2^19 leaves, else the chunk-matrix kernels), 1 = the
 //                    leaf-range kernel, 2 = the chunk-matrix kernels, 3 = the token-chunk kernel,
-//                    4 = the segment kernels, each when the sizes allow it
+//                    4 = the segment kernels, 5 = the fold kernel on per-block leaf counts (the
+//                    descent's inside fff_forward_hard, a counting launch's otherwise; up to 1024
+//                    leaves and 1024 tokens a block), each when the sizes allow it; 0 also takes
+//                    the fold kernel whenever the descent has left counts
+//   "walk_plain_x"   the descent reads token rows 1 = without the streaming hint, 2 = with it,
+//                    0 = without it while the batch fits half the last-level cache
 static int64_t* debug_slot(const char* name) {
     if (!name) return nullptr;
     if (!std::strcmp(name, "token_max_T")) return &g_opt.token_max_T;
@@ -764,6 +792,7 @@ static int64_t* debug_slot(const char* name) {
     if (!std::strcmp(name, "walk_top")) return &g_walk_tuning.top;
     if (!std::strcmp(name, "walk_bpc")) return &g_walk_tuning.bpc;
     if (!std::strcmp(name, "walk_prefetch")) return &g_walk_tuning.prefetch;
+    if (!std::strcmp(name, "walk_plain_x")) return &g_walk_tuning.plain_x;
     if (!std::strcmp(name, "block_top")) return &g_block_tuning.top;
     if (!std::strcmp(name, "leaf_split")) return &g_opt.leaf_split;
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;

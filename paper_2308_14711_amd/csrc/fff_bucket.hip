@@ -521,6 +521,167 @@ hipError_t launch_bucket_hist(const int32_t* leaf_idx, int64_t T, int depth, int
     return hipGetLastError();
 }
 
+// ---- from per-block leaf counts: no histogram pass at all (up to 1024 leaves) ------------------
+//
+// The descent already knows, for every block, how many of its tokens reach each leaf: M[block][leaf]
+// (launch_descend with a DescentCounts; launch_chunk_counts makes the same matrix from a leaf_idx
+// array that came from elsewhere).  One launch with the same blocks and shares then finishes K2:
+// every block sums the columns of M (all blocks: the leaf's total; the blocks before it: where its
+// own tokens of that leaf start inside the leaf), scans the totals over the leaves, and places its
+// own tokens at start(leaf) + before(leaf) + rank inside the share (counted by comparing against
+// the share's leaf ids in LDS).  No atomics, ascending token order inside a leaf by construction.
+
+bool bucket_fold_ok(int depth, int64_t blocks, int64_t share) {
+    return depth <= 10 && share <= kFoldMaxShare && blocks >= 1 && (blocks << depth) <= kFoldWords;
+}
+
+__global__ __launch_bounds__(1024) void chunk_counts_kernel(const int32_t* __restrict__ leaf_idx, int64_t T,
+                                                            int n_leaves, int64_t share, int32_t* __restrict__ M) {
+    __shared__ int32_t s_hist[kFoldMaxLeaves];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < n_leaves; i += 1024) s_hist[i] = 0;
+    __syncthreads();
+    const int64_t t = (int64_t)blockIdx.x * share + tid;
+    if (tid < share && t < T) {
+        const int32_t leaf = leaf_idx[t];
+        if ((uint32_t)leaf < (uint32_t)n_leaves) atomicAdd(&s_hist[leaf], 1);
+    }
+    __syncthreads();
+    for (int i = tid; i < n_leaves; i += 1024) M[(int64_t)blockIdx.x * n_leaves + i] = s_hist[i];
+}
+
+__global__ __launch_bounds__(1024) void bucket_fold_kernel(const int32_t* __restrict__ leaf_idx, int64_t T,
+                                                           int n_leaves, int64_t share, int n_blocks,
+                                                           const int32_t* __restrict__ M,
+                                                           int32_t* __restrict__ count, int32_t* __restrict__ offset,
+                                                           int32_t* __restrict__ perm, int32_t* __restrict__ slot_leaf) {
+    __shared__ int32_t s_tot[4096], s_bef[4096];      // partial column sums: [range][leaf], at most 16 ranges
+    __shared__ int32_t s_base[kFoldMaxLeaves];        // where this block's tokens of a leaf start
+    __shared__ int32_t s_leaf[kFoldMaxShare];
+    __shared__ int32_t s_wsum[16];
+    const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave;
+    const int b = blockIdx.x;
+    const int64_t lo = (int64_t)b * share;
+    const int64_t hi = lo + share < T ? lo + share : T;
+    const int n_own = hi > lo ? (int)(hi - lo) : 0;
+    if (tid < n_own) s_leaf[tid] = leaf_idx[lo + tid];
+
+    // column sums of M (n_leaves is a power of two <= 1024): thread (r, g) takes the rows of range r
+    // for the four leaves of column group g, 16 bytes a load, and all loads of a batch are issued
+    // before the first is used -- a block is a chain of trips to L2 otherwise (256 blocks over 256
+    // leaves: 16 ranges of 16 rows, two batches)
+    int ranges;
+    if (n_leaves >= 4) {
+        const int groups = n_leaves / 4;
+        ranges = 1024 / groups < 16 ? 1024 / groups : 16;
+        const int g = tid % groups, r = tid / groups;
+        const int per = (n_blocks + ranges - 1) / ranges;
+        const int b0 = r * per, b1 = b0 + per < n_blocks ? b0 + per : n_blocks;
+        int4 tot = make_int4(0, 0, 0, 0), bef = make_int4(0, 0, 0, 0);
+        constexpr int kBatch = 8;
+        if (r < ranges) {
+            const int4* col = (const int4*)M + g;
+            for (int bb = b0; bb < b1; bb += kBatch) {
+                int4 v[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const int row = bb + u < b1 ? bb + u : b1 - 1;      // clamped: the load is unconditional
+                    v[u] = col[(int64_t)row * groups];
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const int in = bb + u < b1, early = bb + u < b;
+                    tot.x += in ? v[u].x : 0; tot.y += in ? v[u].y : 0; tot.z += in ? v[u].z : 0; tot.w += in ? v[u].w : 0;
+                    bef.x += early && in ? v[u].x : 0; bef.y += early && in ? v[u].y : 0;
+                    bef.z += early && in ? v[u].z : 0; bef.w += early && in ? v[u].w : 0;
+                }
+            }
+            ((int4*)s_tot)[r * groups + g] = tot;
+            ((int4*)s_bef)[r * groups + g] = bef;
+        }
+    } else {                                          // one or two leaves: a row is shorter than a vector
+        ranges = 16;
+        const int l = tid % n_leaves, r = tid / n_leaves;
+        const int per = (n_blocks + ranges - 1) / ranges;
+        const int b0 = r * per, b1 = b0 + per < n_blocks ? b0 + per : n_blocks;
+        if (r < ranges) {
+            int32_t tot = 0, bef = 0;
+            for (int bb = b0; bb < b1; ++bb) {
+                const int32_t c = M[(int64_t)bb * n_leaves + l];
+                tot += c;
+                bef += bb < b ? c : 0;
+            }
+            s_tot[r * n_leaves + l] = tot;
+            s_bef[r * n_leaves + l] = bef;
+        }
+    }
+    __syncthreads();
+    int32_t total = 0, before = 0;
+    if (tid < n_leaves) {
+        for (int q = 0; q < ranges; ++q) {
+            total += s_tot[q * n_leaves + tid];
+            before += s_bef[q * n_leaves + tid];
+        }
+    }
+    // exclusive scan of the totals over the leaves
+    const int32_t inc = wave_incl_scan(total, lane);
+    if (lane == kWave - 1) s_wsum[w] = inc;
+    __syncthreads();
+    int32_t start = inc - total;
+    for (int ww = 0; ww < w; ++ww) start += s_wsum[ww];
+    if (tid < n_leaves) {
+        s_base[tid] = start + before;
+        if (b == 0) {
+            if (count) count[tid] = total;
+            if (offset) offset[tid] = start;
+        }
+    }
+    if (b == 0 && offset && tid == 0) offset[n_leaves] = (int32_t)T;
+    __syncthreads();
+    if (!perm || tid >= n_own) return;
+
+    // rank of token lo + tid among the share's earlier tokens of the same leaf
+    const int32_t leaf = s_leaf[tid];
+    if ((uint32_t)leaf >= (uint32_t)n_leaves) return;
+    int rank = 0;
+    const int4* s4 = (const int4*)s_leaf;
+    for (int j4 = 0; 4 * j4 < tid; ++j4) {
+        const int4 v = s4[j4];
+        const int j = 4 * j4;
+        rank += (v.x == leaf) + (v.y == leaf && j + 1 < tid) + (v.z == leaf && j + 2 < tid) + (v.w == leaf && j + 3 < tid);
+    }
+    const int32_t pos = s_base[leaf] + rank;
+    perm[pos] = (int32_t)(lo + tid);
+    if (slot_leaf) slot_leaf[pos] = leaf;
+}
+
+hipError_t launch_chunk_counts(const int32_t* leaf_idx, int64_t T, int depth, DescentCounts* dc, hipStream_t s) {
+    dc->blocks = 0;
+    if (T <= 0 || !dc->M) return hipSuccess;
+    // as many blocks as the matrix has room for (at most 256), at least 64 tokens each
+    int64_t blocks = dc->capacity >> depth;
+    if (blocks > 256) blocks = 256;
+    if (blocks < 1) return hipSuccess;
+    int64_t share = (T + blocks - 1) / blocks;
+    if (share < 64) share = 64;
+    blocks = (T + share - 1) / share;
+    if (!bucket_fold_ok(depth, blocks, share) || (blocks << depth) > dc->capacity) return hipSuccess;
+    note_launch("chunk_counts_kernel");
+    chunk_counts_kernel<<<dim3((unsigned)blocks), dim3(1024), 0, s>>>(leaf_idx, T, 1 << depth, share, dc->M);
+    dc->blocks = (int)blocks;
+    dc->share = share;
+    return hipGetLastError();
+}
+
+hipError_t launch_bucket_fold(const int32_t* leaf_idx, int64_t T, int depth, const DescentCounts& dc,
+                              int32_t* count, int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s) {
+    if (dc.blocks <= 0 || !bucket_fold_ok(depth, dc.blocks, dc.share)) return hipErrorInvalidValue;
+    note_launch("bucket_fold_kernel");
+    bucket_fold_kernel<<<dim3((unsigned)dc.blocks), dim3(1024), 0, s>>>(leaf_idx, T, 1 << depth, dc.share, dc.blocks,
+                                                                       dc.M, count, offset, perm, slot_leaf);
+    return hipGetLastError();
+}
+
 // ---- many tokens over few leaves (up to 4096): segments of 1024 tokens, a wave each ----------
 //
 //   count    a wave histograms its segment in LDS and writes M[leaf][segment] for every leaf (so M

@@ -31,6 +31,7 @@ struct Workspace {
     int32_t* offset;     // [NL + 1]
     int32_t* tile_off;   // [NL + 1] exclusive prefix of per-leaf tile counts
     int32_t* chunk_cnt;  // [C, NL]  per-chunk histograms, then per-chunk bases
+    int32_t* fold;       // [kFoldWords] per-block leaf counts of the descent (DescentCounts::M)
     int32_t* hidden;     // [16 T]   hidden activations of the tile path, T * L bf16 (L <= 32)
     int32_t* extra;      // caller-specific region (gating candidates of the mixture of experts)
     int32_t* ctrl;       // [16]     ticket counters and totals
@@ -48,8 +49,23 @@ bool vec_ok(const void* p, int64_t row_elems, bool bf16);
 // " + ", are what fff_last_launch returns.
 void note_launch(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
 
+// Per-block leaf counts, the hand-over from the descent to the bucketing stage: block b of the
+// descent owns tokens [b * share, (b + 1) * share) and leaves M[b][leaf] = how many of them reach
+// `leaf`, so that the bucketing stage needs no histogram pass of its own (launch_bucket_fold).
+struct DescentCounts {
+    int32_t* M = nullptr;    // in: room for `capacity` words
+    int64_t capacity = 0;
+    int blocks = 0;          // out: blocks that wrote a row of M; 0 = the launch left no counts
+    int64_t share = 0;       // out: tokens per block
+};
+constexpr int kFoldMaxLeaves = 1024;
+constexpr int kFoldMaxShare = 1024;
+constexpr int64_t kFoldWords = 128 * 1024;   // [blocks, leaves] counters the fold kernel reads per block
+bool bucket_fold_ok(int depth, int64_t blocks, int64_t share);
+
 // K1: tree descent.  leaf_idx[t] for all t (any shape: falls back to element loads).
-hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+// dc (optional): the launch also leaves per-block leaf counts there when bucket_fold_ok.
+hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s, DescentCounts* dc = nullptr);
 // Descent + leaf network + output row in one launch; needs fused_shape_ok(p).
 hipError_t launch_walk_fused(const Problem& p, int32_t* leaf_idx, hipStream_t s);
 // Experiment switches of the walk kernel (0 = the built-in choice).
@@ -68,6 +84,7 @@ struct WalkTuning {
     int64_t top = 0;     // k + 1 forces at most k LDS-staged levels
     int64_t bpc = 0;     // persistent blocks per compute unit
     int64_t prefetch = 0; // 1: request the next tile's token rows one iteration ahead
+    int64_t plain_x = 0;  // descent: 1 = read token rows without the streaming hint, 2 = with it, 0 = by batch size
     int64_t last_top = 0; // read-only: tree levels the last walk launch kept in LDS
 };
 extern WalkTuning g_walk_tuning;
@@ -89,6 +106,13 @@ hipError_t launch_bucket_onepass(const int32_t* leaf_idx, int64_t T, int depth, 
 bool bucket_hist_ok(int64_t T, int depth);
 hipError_t launch_bucket_hist(const int32_t* leaf_idx, int64_t T, int depth, int32_t* count, int32_t* offset,
                               int32_t* perm, int32_t* slot_leaf, hipStream_t s);
+
+// K2 from per-block leaf counts (the descent's, or launch_chunk_counts' for a leaf_idx array that
+// came from elsewhere): one launch of dc.blocks blocks, each sums the columns of M, scans the leaves
+// and places its own share of the tokens.  Needs dc.blocks > 0.
+hipError_t launch_chunk_counts(const int32_t* leaf_idx, int64_t T, int depth, DescentCounts* dc, hipStream_t s);
+hipError_t launch_bucket_fold(const int32_t* leaf_idx, int64_t T, int depth, const DescentCounts& dc,
+                              int32_t* count, int32_t* offset, int32_t* perm, int32_t* slot_leaf, hipStream_t s);
 
 // K2 for many tokens over few leaves (up to 4096): segments of 1024 tokens, three launches (count, scan,
 // scatter); the matrix region of the workspace must hold a column per segment (bucket_segments_ok).

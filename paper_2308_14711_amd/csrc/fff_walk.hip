@@ -23,6 +23,7 @@
 namespace fff {
 
 constexpr int kFusedMaxLeafWidth = 8;
+constexpr int64_t kLastLevelCacheBytes = (int64_t)256 << 20;   // memory-side cache of the device (not reported by the runtime)
 
 // xv . row, where row[v] is fetched by LOAD(v)
 // TIGHT: the row is exactly LPT * NV vectors long, so no lane needs a bounds check.
@@ -75,20 +76,28 @@ struct WalkArgs {
     int64_t share;       // tokens per block (the last block may get fewer)
     int chunk;           // tokens per round, at most one tile
     int depth, top, nvec, L, act, out_vec;
+    int32_t* block_counts;   // descent only, may be null: [blocks, 2^depth] tokens of every leaf in each block's share
+    int plain_x;             // descent only: read the token rows without the streaming hint
 };
 
 // FUSED = false: writes leaf_idx only.  FUSED = true: also the leaf network (L <= 8).
 // TIGHT: D (and, when FUSED with vector output, O) is exactly LPT * NV vectors.
 template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT, bool PREFETCH>
 __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
-    extern __shared__ uint4 lds[];                 // [(2^top - 1) * nvec] rows, then (2^top - 1) biases
+    extern __shared__ uint4 lds[];                 // [(2^top - 1) * nvec] rows, then (2^top - 1) biases, then the leaf counts
     constexpr int VE = Elem<BF16>::kPerVec;
     const int nvec = a.nvec;
     const int n_top = (1 << a.top) - 1;
     float* lds_bias = (float*)(lds + (int64_t)n_top * nvec);
+    // descent feeding the bucketing stage: how many of this block's tokens reach each leaf
+    int* lds_hist = (int*)(lds_bias + n_top);
+    const bool counting = !FUSED && a.block_counts != nullptr;
+    const int n_leaves = 1 << a.depth;
 
     for (int i = threadIdx.x; i < n_top * nvec; i += kWalkBlock) lds[i] = a.node_w[i];
     for (int i = threadIdx.x; i < n_top; i += kWalkBlock) lds_bias[i] = Elem<BF16>::load(a.node_b, i);
+    if (counting)
+        for (int i = threadIdx.x; i < n_leaves; i += kWalkBlock) lds_hist[i] = 0;
     __syncthreads();
 
     const int sub = threadIdx.x % LPT;
@@ -107,7 +116,8 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 const int v = sub + i * LPT;
-                xr[k][i] = (TIGHT || v < nvec) ? load_stream(xrow + v) : make_uint4(0, 0, 0, 0);
+                xr[k][i] = (TIGHT || v < nvec) ? ((!FUSED && a.plain_x) ? xrow[v] : load_stream(xrow + v))
+                                               : make_uint4(0, 0, 0, 0);
             }
         }
     };
@@ -170,6 +180,7 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
         for (int k = 0; k < TPG; ++k) {
             leaf[k] = node[k] - n_nodes;
             if (a.leaf_idx && live[k] && sub == 0) a.leaf_idx[t[k]] = (int32_t)leaf[k];
+            if (counting && live[k] && sub == 0) atomicAdd(&lds_hist[leaf[k]], 1);
         }
         if (!FUSED) {
             if (PREFETCH) {
@@ -268,6 +279,11 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
                 for (int i = 0; i < NV; ++i) xv[k][i] = xn[k][i];
         }
     }
+    if (counting) {
+        __syncthreads();
+        int32_t* row = a.block_counts + (int64_t)blockIdx.x * n_leaves;
+        for (int i = threadIdx.x; i < n_leaves; i += kWalkBlock) row[i] = lds_hist[i];
+    }
 }
 
 // Any D, any alignment: one wave per token, element-wise loads.
@@ -319,6 +335,9 @@ DeviceInfo device_info() {
 WalkTuning g_walk_tuning;
 namespace {
 
+// set by launch_descend for the duration of its dispatch: where the launch may leave per-block leaf counts
+thread_local DescentCounts* t_counts = nullptr;
+
 template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT, bool PREFETCH = false>
 hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     constexpr int kGroups = kWalkBlock / LPT;
@@ -336,10 +355,24 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     const int64_t rounds = (tokens_per_block + tile - 1) / tile;
     int64_t chunk = ((tokens_per_block + rounds - 1) / rounds + TPG - 1) / TPG * TPG;
     if (chunk > tile) chunk = tile;
+    // a descent that feeds the bucketing stage also counts, per block, the tokens of every leaf
+    // (one LDS counter per leaf), when the tree and the shares are small enough for the fold kernel
+    DescentCounts* dc = FUSED ? nullptr : t_counts;
+    size_t hist_bytes = 0;
+    if (dc) {
+        dc->blocks = 0;
+        if (dc->M && bucket_fold_ok(p.depth, blocks, tokens_per_block) &&
+            (blocks << p.depth) <= dc->capacity) {
+            hist_bytes = sizeof(int32_t) << p.depth;
+            dc->blocks = (int)blocks;
+            dc->share = tokens_per_block;
+        }
+    }
     // stage the top levels while a block handles at least two tokens per staged row and they fit
     const int64_t row_bytes = p.D * (BF16 ? 2 : 4);
     size_t lds_cap = di.lds_per_block;
     if (lds_cap > 144 * 1024) lds_cap = 144 * 1024;
+    lds_cap -= hist_bytes;
     int top = 0;
     while (top < p.depth) {
         const int64_t rows = ((int64_t)1 << (top + 1)) - 1;
@@ -347,16 +380,17 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
         ++top;
     }
     if (g_walk_tuning.top > 0 && g_walk_tuning.top - 1 < top) top = (int)g_walk_tuning.top - 1;
-    const size_t lds_bytes = (size_t)(((int64_t)1 << top) - 1) * (row_bytes + 4);
+    const size_t lds_bytes = (size_t)(((int64_t)1 << top) - 1) * (row_bytes + 4) + hist_bytes;
     auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED, TIGHT, PREFETCH>;
     // raise this instantiation's dynamic LDS limit once per device (the limit only ever grows)
     static size_t lds_allowed_on[64];
     size_t& lds_allowed = lds_allowed_on[di.dev];
     if (lds_bytes > 48 * 1024 && lds_bytes > lds_allowed) {
+        const size_t lds_max = lds_cap + hist_bytes;
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds_cap);
+                                           (int)lds_max);
         if (e != hipSuccess) return e;
-        lds_allowed = lds_cap;
+        lds_allowed = lds_max;
     }
     WalkArgs a;
     a.x = (const uint4*)p.x;
@@ -379,8 +413,16 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     a.L = p.L;
     a.act = p.act;
     a.out_vec = FUSED && vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
+    a.block_counts = hist_bytes ? dc->M : nullptr;
+    // The descent of the staged path is followed by a leaf kernel that reads the same token rows
+    // again: without the streaming hint they stay in the last-level cache for it (the ViT-block
+    // workload: hidden kernel 19.9 -> 18.3 us, descent 25.0 -> 25.6).  Batches that cannot stay there
+    // anyway (more than half of its 256 MB) keep the hint.
+    const int64_t x_bytes = p.T * row_bytes;
+    a.plain_x = g_walk_tuning.plain_x == 1 || (g_walk_tuning.plain_x == 0 && x_bytes <= kLastLevelCacheBytes / 2);
     note_launch("walk_kernel<%s,%d,%d,%d,%d,%s,%s%s> top=%d", BF16 ? "bf16" : "f32", LPT, NV, TPG, kWalkBlock,
-                FUSED ? "fused" : "descent", TIGHT ? "tight" : "checked", PREFETCH ? ",prefetch" : "", top);
+                FUSED ? "fused" : (hist_bytes ? "descent+counts" : "descent"), TIGHT ? "tight" : "checked",
+                PREFETCH ? ",prefetch" : "", top);
     kern<<<dim3((unsigned)blocks), dim3(kWalkBlock), lds_bytes, s>>>(a);
     return hipGetLastError();
 }
@@ -480,10 +522,15 @@ bool fused_shape_ok(const Problem& p) {
     return walk_shape_ok(p) && vec_ok(p.leaf_w1, p.D, p.bf16) && p.L <= kFusedMaxLeafWidth;
 }
 
-hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s, DescentCounts* dc) {
+    if (dc) dc->blocks = 0;
     if (p.T == 0) return hipSuccess;
-    if (walk_shape_ok(p))
-        return p.bf16 ? dispatch_walk<true, false>(p, leaf_idx, s) : dispatch_walk<false, false>(p, leaf_idx, s);
+    if (walk_shape_ok(p)) {
+        t_counts = dc;
+        const hipError_t e = p.bf16 ? dispatch_walk<true, false>(p, leaf_idx, s) : dispatch_walk<false, false>(p, leaf_idx, s);
+        t_counts = nullptr;
+        return e;
+    }
     const int64_t blocks = (p.T + 3) / 4;
     note_launch("descend_generic_kernel<%s>", p.bf16 ? "bf16" : "f32");
     if (p.bf16)

@@ -219,8 +219,9 @@ def test_runs_on_a_side_stream():
                                           (6, 4096, "one"), (19, 70001, "zipf"), (10, 300000, "u"),
                                           (8, 50432, "u"), (12, 131072, "zipf"), (12, 131071, "u"), (2, 63, "u"),
                                           (9, 16385, "zipf"), (3, 65535, "one"), (3, 65536, "one"),
-                                          (8, 806912, "u"), (12, 131073, "zipf")])
-@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4])
+                                          (8, 806912, "u"), (12, 131073, "zipf"), (10, 131072, "zipf"),
+                                          (10, 100003, "u"), (7, 12001, "u"), (9, 262144, "one")])
+@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4, 5])
 def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
     import torch
     import paper_2308_14711_amd as F
@@ -249,8 +250,36 @@ def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
             assert np.array_equal(d_count.cpu().numpy(), count)
             assert np.array_equal(d_offset.cpu().numpy(), offset)
             assert np.array_equal(d_perm.cpu().numpy(), perm)
+            if kernel == 5 and depth <= 10 and T <= min(256, (128 * 1024) >> depth) * 1024:
+                assert "bucket_fold_kernel" in F.fff_last_launch(), F.fff_last_launch()
     finally:
         F.fff_debug_option("bucket_kernel", 0)
+
+
+def test_descent_hands_leaf_counts_to_the_bucketing_stage():
+    """On the staged path the descent counts, per block, the tokens of every leaf, and one fold launch
+    turns the counts into the grouped order: same rows, bit for bit, as with a bucketing kernel that
+    histograms leaf_idx itself; routing and rows against the oracle."""
+    import torch
+    import paper_2308_14711_amd as F
+    for T, depth, L, seed in ((12000, 6, 8, 51), (50432, 8, 8, 52), (9000, 9, 4, 53), (20000, 3, 16, 54)):
+        print("\n[case] descent counts T=%d D=768 O=768 depth=%d L=%d bf16 seed %d path=2" % (T, depth, L, seed), flush=True)
+        w = W.make_layer("fold", T, 768, 768, depth, L, W.ACT_GELU, W.DTYPE_BF16, seed=seed, keep_f32=T < 30000)
+        dev = to_device(w)
+        F.fff_set_option("path", 2)
+        try:
+            out, idx = run_forward(w, dev)
+            launch = F.fff_last_launch()
+            assert "descent+counts" in launch and "bucket_fold_kernel" in launch, launch
+            F.fff_debug_option("bucket_kernel", 3)
+            out3, idx3 = run_forward(w, dev)
+            assert "bucket_hist_kernel" in F.fff_last_launch()
+        finally:
+            F.fff_set_option("path", 0)
+            F.fff_debug_option("bucket_kernel", 0)
+        assert torch.equal(out.view(torch.int16), out3.view(torch.int16)) and torch.equal(idx, idx3)
+        if T < 30000:
+            _log("descent counts T=%d" % T, check_against_oracle(w, out, idx))
 
 
 def test_descend_and_leaf_stages():
