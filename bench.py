@@ -161,6 +161,10 @@ def algorithmic_bytes(w, ref_idx):
         # with the output weights, output rows out; both read the grouped order and the slots' leaves
         "leaf_hidden": T * D * s + 8 * T + u_leaf * (L * D * s + L * s) + T * L * 2,
         "leaf_output": T * L * 2 + 8 * T + u_leaf * (L * O * s + O * s) + T * O * s,
+        # the fused launch cut in two: token rows in, leaf ids and hidden activations (fp32) out; those
+        # back in with the output weights and biases, output rows out
+        "walk_hidden": T * D * s + 4 * T + node_bytes + u_leaf * (L * D * s + L * s) + 4 * T * L,
+        "leaf_slices": 4 * T + 4 * T * L + u_leaf * (L * O * s + O * s) + T * O * s,
     }
 
 
@@ -711,7 +715,7 @@ def hard_bench(name, args, np, torch, W, F, headline=True):
                     "std_ms": round(float(np.std(batch_ms)), 5), "median_ms": round(float(np.median(batch_ms)), 5)}
 
     alg = algorithmic_bytes(w, ref_idx)
-    path_names = {1: "fused", 2: "staged", 3: "generic", 4: "token_block"}
+    path_names = {1: "fused", 2: "staged", 3: "generic", 4: "token_block", 5: "split"}
 
     # per-stage durations: HIP events recorded by the library on the call's stream
     stages = {}
@@ -722,8 +726,10 @@ def hard_bench(name, args, np, torch, W, F, headline=True):
         torch.cuda.synchronize()
         d_ms, b_ms, l_ms, l2_ms, calls = F.fff_stage_times()
         F.fff_set_option("stage_timing", 0)
-        single = F.fff_get_option("last_path") != 2
-        if single:     # one launch did the whole path: it carries the whole path's bytes
+        single = F.fff_get_option("last_path") not in (2, 5)
+        if F.fff_get_option("last_path") == 5:      # walk + hidden neurons per token, then output rows by column slices
+            names = (("walk_hidden", d_ms), ("leaf_slices", l_ms))
+        elif single:     # one launch did the whole path: it carries the whole path's bytes
             alg = dict(alg, walk_fused=alg["path"], token_block=alg["path"])
             names = ((("token_block" if F.fff_get_option("last_path") == 4 else "walk_fused"), d_ms),)
         elif F.fff_get_option("last_leaf_path") == 2:   # the leaf stage ran as two kernels
@@ -742,7 +748,7 @@ def hard_bench(name, args, np, torch, W, F, headline=True):
         names_in_order = [k.strip() for k in kernels.split(" + ")]
         dom_kernel = kernels if len(stages) == 1 else None
         if dom_kernel is None:
-            pos = {"descent": 0, "leaf_output": -1, "leaf_hidden": -2, "leaf": -1}.get(dom)
+            pos = {"descent": 0, "leaf_output": -1, "leaf_hidden": -2, "leaf": -1, "walk_hidden": 0, "leaf_slices": -1}.get(dom)
             dom_kernel = names_in_order[pos] if pos is not None and names_in_order else dom
         measured = None if args.tokens else measured_traffic(w.name, dom_kernel)
         ceiling = copy_ceiling_once(torch)
@@ -758,13 +764,14 @@ def hard_bench(name, args, np, torch, W, F, headline=True):
     # whether the weight table fits an L2: measure random row fetches over tables of the next smaller
     # and next larger power-of-two row count (the probe library's fffb_gather) and report the time the launch's
     # gathered rows alone would take at those rates
-    if headline and roofline and dom == "walk_fused" and w.O == w.D:
+    if headline and roofline and dom in ("walk_fused", "walk_hidden") and w.O == w.D:
         es = 2 if w.dtype == W.DTYPE_BF16 else 4
         rb = w.D * es
         if rb % 16 == 0:
             top = F.fff_get_option("last_walk_top")
-            rows_per_token = (w.depth - top) + 2 * w.leaf_width + 1          # node rows past LDS, W1, W2, b2
-            table_rows = max(1, alg["u_node"] - ((1 << top) - 1)) + alg["u_leaf"] * (2 * w.leaf_width + 1)
+            leaf_rows = 2 * w.leaf_width + 1 if dom == "walk_fused" else w.leaf_width   # W1, W2, b2 / W1 alone
+            rows_per_token = (w.depth - top) + leaf_rows                      # plus the node rows past LDS
+            table_rows = max(1, alg["u_node"] - ((1 << top) - 1)) + alg["u_leaf"] * leaf_rows
             gathered = float(w.T) * rows_per_token * rb
             sink = torch.zeros((4,), dtype=torch.int32, device="cuda")
             bracket = []

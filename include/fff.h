@@ -283,8 +283,11 @@ int fff_release_workspace(void);
  *   "path"           0 = choose by shape and batch size (default), 1 = one fused launch
  *                    (walk, leaf network and output row per token; leaf_width <= 8),
  *                    2 = staged (descent, bucketing, leaf kernels), 3 = the element-wise
- *                    fallback kernel, 4 = one block per token (small batches); a path the
- *                    shape does not allow falls back to one it does
+ *                    fallback kernel, 4 = one block per token (small batches), 5 = the fused
+ *                    launch cut in two (walk and hidden neurons per token, then the output
+ *                    rows by column slices, one slice of all rows per XCD; leaf_width <= 8,
+ *                    16-byte aligned output rows); a path the shape does not allow falls back
+ *                    to one it does
  *   "leaf_path"      staged path only: 0 = choose by shape and bucket size (default),
  *                    1 = always the gather kernel, 2 = the MFMA tile kernels whenever the
  *                    shape allows them (bf16, leaf_width <= 32, D % 8 == 0, O % 8 == 0,
@@ -293,7 +296,7 @@ int fff_release_workspace(void);
  *                    0 = in token order (no bucketing stage)
  *   "stage_timing"   1 = fff_forward_hard records hipEvents around its stages
  *                    (read them with fff_stage_times); 0 (default) = off
- * Read-only, describing the last call: "last_path" (1..4 as above), "last_leaf_path"
+ * Read-only, describing the last call: "last_path" (1..5 as above), "last_leaf_path"
  * (1 = gather kernel, 2 = the two tile kernels, 3 = both, each on its share of the tiles),
  * "last_walk_top" (tree levels the descent or fused launch kept in LDS),
  * "last_block_kernel" (fff_forward_block: 1 = a vector kernel, 2 = the element-wise one),

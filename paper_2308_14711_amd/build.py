@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libfff_hip.so")
 PROBE_LIB = os.path.join(HERE, "libfff_bench_probes.so")   # measuring sticks of bench.py, not the product
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["fff_api.hip", "fff_walk.hip", "fff_bucket.hip", "fff_leaf.hip", "fff_leaf_tiles.hip",
+SOURCES = ["fff_api.hip", "fff_walk.hip", "fff_bucket.hip", "fff_leaf.hip", "fff_leaf_tiles.hip", "fff_leaf_slices.hip",
            "fff_token_block.hip", "fff_moe_gate.hip", "fff_soft.hip", "fff_block.hip"]
 PROBE_SOURCES = ["bench_probes.hip"]
 HEADERS = ["fff_device.h", "fff_internal.h", "fff_mfma_tile.h", os.path.join("..", "..", "include", "fff.h")]

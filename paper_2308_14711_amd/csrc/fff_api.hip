@@ -245,7 +245,7 @@ bool staged_shape_ok(const Problem& p) {
     return walk_shape_ok(p) && vec_ok(p.leaf_w1, p.D, p.bf16) && p.L <= 64;
 }
 
-enum { kPathAuto = 0, kPathFused = 1, kPathStaged = 2, kPathGeneric = 3, kPathToken = 4 };
+enum { kPathAuto = 0, kPathFused = 1, kPathStaged = 2, kPathGeneric = 3, kPathToken = 4, kPathSplit = 5 };
 
 // One launch that keeps the token row in registers from the root to the output
 // row wins while a leaf is narrow (its weights are a few rows per token, like a
@@ -253,7 +253,9 @@ enum { kPathAuto = 0, kPathFused = 1, kPathStaged = 2, kPathGeneric = 3, kPathTo
 // weights are read once per group.
 int choose_path(const Problem& p) {
     const bool fused_ok = fused_shape_ok(p), staged_ok = staged_shape_ok(p), token_ok = token_shape_ok(p);
+    const bool split_ok = fused_ok && slices_shape_ok(p);
     if (g_opt.path == kPathToken && token_ok) return kPathToken;
+    if (g_opt.path == kPathSplit && split_ok) return kPathSplit;
     if (g_opt.path == kPathFused && fused_ok) return kPathFused;
     if (g_opt.path == kPathStaged && staged_ok) return kPathStaged;
     if (g_opt.path == kPathGeneric) return kPathGeneric;
@@ -265,7 +267,30 @@ int choose_path(const Problem& p) {
         p.T <= (fused_ok ? g_opt.token_max_T : 6 * g_opt.token_max_T))
         return kPathToken;
     if (!fused_ok && !staged_ok) return token_ok ? kPathToken : kPathGeneric;
-    if (!staged_ok) return kPathFused;
+    // The fused launch gathers, per token, the leaf's output-weight and bias rows from a table of
+    // 2^depth (leaf_width + 1) rows.  Once that table outgrows the L2 of an XCD most of those rows
+    // come back from memory; the launch cut in two (walk and hidden neurons per token, then the
+    // output rows by column slices, one slice of all rows per XCD) keeps each slice in its L2.
+    // Measured on 768-wide rows, 65536 tokens, one neuron a leaf: depth 11 (6 MB of output rows)
+    // 80 -> 70 us, depth 12 93 -> 82, depth 13 106 -> 101; two neurons, depth 11: 99 -> 86;
+    // 4096-wide rows, 16384 tokens, depth 10: 140 -> 108.  With one neuron a leaf and a full batch
+    // (256 tokens per compute unit and more) it is ahead for smaller tables too (depth 8: 57 -> 53),
+    // since the walk then runs in the descent's leaner tile shape.  Rows shorter than 1 KB and
+    // batches of up to 32 tokens per compute unit stay on the single launch (two launches cost
+    // more than they save: 16384 tokens, depth 10: 20.6 against 21.4 us).
+    const auto fused_or_split = [&]() {
+        if (!split_ok || g_opt.path == kPathFused) return (int)kPathFused;
+        const DeviceInfo di = device_info();
+        const int64_t es = p.bf16 ? 2 : 4;
+        const int64_t out_table = ((int64_t)(p.L + 1) * p.O * es) << p.depth;
+        const bool full_rows = p.O * es >= 1024 && p.D * es >= 1024;
+        const bool big_batch = p.T > 32 * (int64_t)di.cus;
+        const bool split = full_rows && big_batch &&
+                           out_table <= 64 * di.l2_bytes &&     // beyond that no slice of it stays in an L2 either
+                           (out_table >= di.l2_bytes || (p.L == 1 && p.T >= 256 * (int64_t)di.cus));
+        return split ? (int)kPathSplit : (int)kPathFused;
+    };
+    if (!staged_ok) return fused_or_split();
     if (!fused_ok) return kPathStaged;
     // Grouping pays once the leaf rows a token meets are many bytes -- 24 KB (8 neurons on 768-wide
     // bf16 rows), or 12 KB (4 neurons) where the leaf weights together (8 MB) outgrow the 4 MB L2 of one XCD,
@@ -290,7 +315,7 @@ int choose_path(const Problem& p) {
                       (token_leaf_bytes * 8 >= 3 * kVectorL1Bytes && leaf_bytes >= 2 * di.l2_bytes) ||
                       (token_leaf_bytes * 4 >= kVectorL1Bytes && leaf_bytes >= 4 * di.l2_bytes);
     const bool visited = p.T > 32 * (int64_t)di.cus && p.depth < 40 && p.T >= ((int64_t)3 << p.depth);
-    return (wide && visited) ? kPathStaged : kPathFused;
+    return (wide && visited) ? (int)kPathStaged : fused_or_split();
 }
 
 // K2 with whichever kernel set takes the sizes; outputs may be null (then workspace arrays are used).
@@ -462,12 +487,24 @@ int run_forward_hard(const Problem& p, int32_t* leaf_idx, hipStream_t s, void* f
     if (fixed_scratch) {
         lay = layout_for(p.T, p.depth);
         carve(fixed_scratch, lay, &ws);
-        if ((e = launch_zero(ws.ctrl, kCtrlWords, s)) != hipSuccess) return set_device_error(e, "zero kernel launch");
+        if (path == kPathStaged && (e = launch_zero(ws.ctrl, kCtrlWords, s)) != hipSuccess)
+            return set_device_error(e, "zero kernel launch");
     } else {
         const int rc = get_workspace(p.T, p.depth, &ws, &lay, s);
         if (rc != FFF_OK) return rc;
     }
     int32_t* li = leaf_idx ? leaf_idx : ws.leaf_idx;
+    if (path == kPathSplit) {
+        // walk and hidden neurons per token, then the output rows by column slices; the hidden
+        // activations (fp32, at most 8 a token) use the workspace's hidden-activation region
+        float* hid = (float*)ws.hidden;
+        if (marks) stage_mark(s);
+        if ((e = launch_walk_hidden(p, li, hid, s)) != hipSuccess) return set_device_error(e, "walk kernel launch");
+        for (int k = 0; marks && k < 2; ++k) stage_mark(s);
+        if ((e = launch_leaf_slices(p, li, hid, s)) != hipSuccess) return set_device_error(e, "slice kernel launch");
+        for (int k = 0; marks && k < 2; ++k) stage_mark(s);
+        return FFF_OK;
+    }
     // the descent leaves per-block leaf counts for the bucketing stage where the sizes allow it
     DescentCounts dc;
     const bool fold = g_opt.bucketing && p.depth <= 10 && (g_opt.bucket_kernel == 0 || g_opt.bucket_kernel == 5);

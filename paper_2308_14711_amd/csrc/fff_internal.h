@@ -68,6 +68,14 @@ bool bucket_fold_ok(int depth, int64_t blocks, int64_t share);
 hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s, DescentCounts* dc = nullptr);
 // Descent + leaf network + output row in one launch; needs fused_shape_ok(p).
 hipError_t launch_walk_fused(const Problem& p, int32_t* leaf_idx, hipStream_t s);
+// The fused launch cut in two for leaf tables that outgrow an L2: walk + hidden neurons per token
+// (launch_walk_hidden: leaf_idx [T] and hidden [T, L] fp32 out), then the output rows by column
+// slices (launch_leaf_slices): every XCD writes one slice of all rows, so that its L2 only ever
+// holds that slice of the output weights and biases.  Same arithmetic in the same order as the
+// single launch.  Needs fused_shape_ok and slices_shape_ok.
+hipError_t launch_walk_hidden(const Problem& p, int32_t* leaf_idx, float* hidden, hipStream_t s);
+bool slices_shape_ok(const Problem& p);
+hipError_t launch_leaf_slices(const Problem& p, const int32_t* leaf_idx, const float* hidden, hipStream_t s);
 // Experiment switches of the walk kernel (0 = the built-in choice).
 // Compute units, the dynamic LDS a block may ask for, the L2 of one XCD and the index of the current device (cached).
 struct DeviceInfo {

@@ -76,14 +76,18 @@ struct WalkArgs {
     int64_t share;       // tokens per block (the last block may get fewer)
     int chunk;           // tokens per round, at most one tile
     int depth, top, nvec, L, act, out_vec;
+    float* hidden_out;       // fused only, may be null: [T, L] hidden activations (fp32) instead of the output rows
     int32_t* block_counts;   // descent only, may be null: [blocks, 2^depth] tokens of every leaf in each block's share
     int plain_x;             // descent only: read the token rows without the streaming hint
 };
 
-// FUSED = false: writes leaf_idx only.  FUSED = true: also the leaf network (L <= 8).
-// TIGHT: D (and, when FUSED with vector output, O) is exactly LPT * NV vectors.
-template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT, bool PREFETCH>
+// MODE: kWalkDescend writes leaf_idx only; kWalkFused also the leaf network (L <= 8) and the output
+// row; kWalkHidden the leaf's hidden neurons, stored fp32 for a launch that writes the rows.
+// TIGHT: D (and, when fused with vector output, O) is exactly LPT * NV vectors.
+constexpr int kWalkDescend = 0, kWalkFused = 1, kWalkHidden = 2;
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, int MODE, bool TIGHT, bool PREFETCH>
 __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
+    constexpr bool HIDDEN = MODE == kWalkHidden, DESCEND = MODE == kWalkDescend;   // else the fused launch
     extern __shared__ uint4 lds[];                 // [(2^top - 1) * nvec] rows, then (2^top - 1) biases, then the leaf counts
     constexpr int VE = Elem<BF16>::kPerVec;
     const int nvec = a.nvec;
@@ -91,7 +95,7 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
     float* lds_bias = (float*)(lds + (int64_t)n_top * nvec);
     // descent feeding the bucketing stage: how many of this block's tokens reach each leaf
     int* lds_hist = (int*)(lds_bias + n_top);
-    const bool counting = !FUSED && a.block_counts != nullptr;
+    const bool counting = DESCEND && a.block_counts != nullptr;
     const int n_leaves = 1 << a.depth;
 
     for (int i = threadIdx.x; i < n_top * nvec; i += kWalkBlock) lds[i] = a.node_w[i];
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 const int v = sub + i * LPT;
-                xr[k][i] = (TIGHT || v < nvec) ? ((!FUSED && a.plain_x) ? xrow[v] : load_stream(xrow + v))
+                xr[k][i] = (TIGHT || v < nvec) ? ((DESCEND && a.plain_x) ? xrow[v] : load_stream(xrow + v))
                                                : make_uint4(0, 0, 0, 0);
             }
         }
@@ -182,7 +186,7 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
             if (a.leaf_idx && live[k] && sub == 0) a.leaf_idx[t[k]] = (int32_t)leaf[k];
             if (counting && live[k] && sub == 0) atomicAdd(&lds_hist[leaf[k]], 1);
         }
-        if (!FUSED) {
+        if (DESCEND) {
             if (PREFETCH) {
 #pragma unroll
                 for (int k = 0; k < TPG; ++k)
@@ -210,6 +214,24 @@ __global__ __launch_bounds__(kWalkBlock) void walk_kernel(const WalkArgs a) {
 #pragma unroll
                 for (int k = 0; k < TPG; ++k) h[k][r] = 0.f;
             }
+        }
+        if (HIDDEN) {
+            // the output rows are left to a launch of their own (leaf_slices_kernel): lane r of the
+            // group stores the r-th hidden activation, fp32 as it stands in the registers
+#pragma unroll
+            for (int k = 0; k < TPG; ++k) {
+                float hv = h[k][0];
+#pragma unroll
+                for (int q = 1; q < kFusedMaxLeafWidth; ++q) hv = q == sub ? h[k][q] : hv;
+                if (live[k] && sub < a.L) a.hidden_out[t[k] * a.L + sub] = hv;
+            }
+            if (PREFETCH) {
+#pragma unroll
+                for (int k = 0; k < TPG; ++k)
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) xv[k][i] = xn[k][i];
+            }
+            continue;
         }
         // output row: y[o] = sum_r h[r] W2[leaf][r][o] + b2[leaf][o]
 #pragma unroll
@@ -337,9 +359,13 @@ namespace {
 
 // set by launch_descend for the duration of its dispatch: where the launch may leave per-block leaf counts
 thread_local DescentCounts* t_counts = nullptr;
+// set by launch_walk_hidden for the duration of its dispatch: where the fused launch leaves the hidden
+// activations instead of writing output rows
+thread_local float* t_hidden_out = nullptr;
 
-template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED, bool TIGHT, bool PREFETCH = false>
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, int MODE, bool TIGHT, bool PREFETCH = false>
 hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+    constexpr bool FUSED = MODE == kWalkFused, HIDDEN = MODE == kWalkHidden;
     constexpr int kGroups = kWalkBlock / LPT;
     const DeviceInfo di = device_info();
     const int64_t tile = (int64_t)kGroups * TPG;
@@ -357,7 +383,7 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     if (chunk > tile) chunk = tile;
     // a descent that feeds the bucketing stage also counts, per block, the tokens of every leaf
     // (one LDS counter per leaf), when the tree and the shares are small enough for the fold kernel
-    DescentCounts* dc = FUSED ? nullptr : t_counts;
+    DescentCounts* dc = MODE == kWalkDescend ? t_counts : nullptr;
     size_t hist_bytes = 0;
     if (dc) {
         dc->blocks = 0;
@@ -381,7 +407,7 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     }
     if (g_walk_tuning.top > 0 && g_walk_tuning.top - 1 < top) top = (int)g_walk_tuning.top - 1;
     const size_t lds_bytes = (size_t)(((int64_t)1 << top) - 1) * (row_bytes + 4) + hist_bytes;
-    auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, FUSED, TIGHT, PREFETCH>;
+    auto kern = walk_kernel<BF16, LPT, NV, TPG, kWalkBlock, MODE, TIGHT, PREFETCH>;
     // raise this instantiation's dynamic LDS limit once per device (the limit only ever grows)
     static size_t lds_allowed_on[64];
     size_t& lds_allowed = lds_allowed_on[di.dev];
@@ -414,6 +440,7 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     a.act = p.act;
     a.out_vec = FUSED && vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
     a.block_counts = hist_bytes ? dc->M : nullptr;
+    a.hidden_out = HIDDEN ? t_hidden_out : nullptr;
     // The descent of the staged path is followed by a leaf kernel that reads the same token rows
     // again: without the streaming hint they stay in the last-level cache for it (the ViT-block
     // workload: hidden kernel 19.9 -> 18.3 us, descent 25.0 -> 25.6).  Batches that cannot stay there
@@ -421,23 +448,26 @@ hipError_t run_walk_t(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     const int64_t x_bytes = p.T * row_bytes;
     a.plain_x = g_walk_tuning.plain_x == 1 || (g_walk_tuning.plain_x == 0 && x_bytes <= kLastLevelCacheBytes / 2);
     note_launch("walk_kernel<%s,%d,%d,%d,%d,%s,%s%s> top=%d", BF16 ? "bf16" : "f32", LPT, NV, TPG, kWalkBlock,
-                FUSED ? "fused" : (hist_bytes ? "descent+counts" : "descent"), TIGHT ? "tight" : "checked",
+                FUSED ? "fused" : HIDDEN ? "walk+hidden" : (hist_bytes ? "descent+counts" : "descent"),
+                TIGHT ? "tight" : "checked",
                 PREFETCH ? ",prefetch" : "", top);
     kern<<<dim3((unsigned)blocks), dim3(kWalkBlock), lds_bytes, s>>>(a);
     return hipGetLastError();
 }
 
-template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, bool FUSED>
+template <bool BF16, int LPT, int NV, int TPG, int kWalkBlock, int MODE>
 hipError_t run_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+    constexpr bool FUSED = MODE == kWalkFused;
     const int64_t per = Elem<BF16>::kPerVec;
     const bool out_vec = FUSED && vec_ok(p.out, p.O, BF16) && vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
     const bool tight = p.D == per * LPT * NV && (!FUSED || !out_vec || p.O == per * LPT * NV);
-    return tight ? run_walk_t<BF16, LPT, NV, TPG, kWalkBlock, FUSED, true>(p, leaf_idx, s)
-                 : run_walk_t<BF16, LPT, NV, TPG, kWalkBlock, FUSED, false>(p, leaf_idx, s);
+    return tight ? run_walk_t<BF16, LPT, NV, TPG, kWalkBlock, MODE, true>(p, leaf_idx, s)
+                 : run_walk_t<BF16, LPT, NV, TPG, kWalkBlock, MODE, false>(p, leaf_idx, s);
 }
 
-template <bool BF16, bool FUSED>
+template <bool BF16, int MODE>
 hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
+    constexpr bool FUSED = MODE == kWalkFused;     // the walk + hidden launch takes the descent's tiles
     const int64_t nvec = p.D / Elem<BF16>::kPerVec;
     // (lanes per token, 16-byte vectors per lane, tokens per group, block size): blocks of 1024
     // threads leave 128 VGPRs per lane, blocks of 512 leave 256 for the long-row variants
@@ -448,15 +478,15 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     const bool untuned = g_walk_tuning.tpg == 0 && g_walk_tuning.block == 0;
     const int64_t cus = device_info().cus;
     const bool small_batch = untuned && p.T <= 32 * cus, smallish_batch = untuned && p.T <= 64 * cus;
-    if (nvec <= 16) return smallish_batch ? run_walk<BF16, 16, 1, 1, 512, FUSED>(p, leaf_idx, s)
-                                          : run_walk<BF16, 16, 1, 4, 1024, FUSED>(p, leaf_idx, s);
-    if (nvec <= 32) return smallish_batch ? run_walk<BF16, 16, 2, 1, 512, FUSED>(p, leaf_idx, s)
-                                          : run_walk<BF16, 16, 2, 2, 1024, FUSED>(p, leaf_idx, s);
-    if (nvec <= 64) return smallish_batch ? run_walk<BF16, 16, 4, 1, 512, FUSED>(p, leaf_idx, s)
-                                          : run_walk<BF16, 16, 4, 2, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 16) return smallish_batch ? run_walk<BF16, 16, 1, 1, 512, MODE>(p, leaf_idx, s)
+                                          : run_walk<BF16, 16, 1, 4, 1024, MODE>(p, leaf_idx, s);
+    if (nvec <= 32) return smallish_batch ? run_walk<BF16, 16, 2, 1, 512, MODE>(p, leaf_idx, s)
+                                          : run_walk<BF16, 16, 2, 2, 1024, MODE>(p, leaf_idx, s);
+    if (nvec <= 64) return smallish_batch ? run_walk<BF16, 16, 4, 1, 512, MODE>(p, leaf_idx, s)
+                                          : run_walk<BF16, 16, 4, 2, 1024, MODE>(p, leaf_idx, s);
     if (nvec <= 96) {
         const int64_t tpg = g_walk_tuning.tpg, blk = g_walk_tuning.block;
-        if (tpg == 1 && blk == 512) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
+        if (tpg == 1 && blk == 512) return run_walk<BF16, 16, 6, 1, 512, MODE>(p, leaf_idx, s);
         // measured best for the fused launch on 768-wide rows: blocks of 512 (256 VGPRs per lane) with
         // four tokens per lane group (82 us on the BERT-base-sized workload, against 83 with two and
         // 86 with two plus the next tile's rows requested one iteration ahead); the descent-only
@@ -464,14 +494,14 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
         const bool exact = nvec == 96 && FUSED && p.O == p.D && vec_ok(p.out, p.O, BF16) &&
                            vec_ok(p.leaf_w2, p.O, BF16) && vec_ok(p.leaf_b2, p.O, BF16);
         if (exact && g_walk_tuning.prefetch)
-            return run_walk_t<BF16, 16, 6, 2, 512, FUSED, true, true>(p, leaf_idx, s);
+            return run_walk_t<BF16, 16, 6, 2, 512, MODE, true, true>(p, leaf_idx, s);
         if (tpg == 0 && blk == 0) {
             // at most one tile per compute unit before tiles get larger: 32 tokens a block up
             // to 8192 tokens, 64 up to 16384, then 128 (fused launch, depth 11, one neuron a leaf:
             // 2048 tokens 9.5 us against 23.4 with tiles of 128, 8192 tokens 14.8 against 30.3,
             // 16384 tokens 24.3 against 32.7, 24576 tokens 37.1 with tiles of 64 against 35.7).
-            if (p.T <= 32 * cus) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
-            if (p.T <= 64 * cus) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
+            if (p.T <= 32 * cus) return run_walk<BF16, 16, 6, 1, 512, MODE>(p, leaf_idx, s);
+            if (p.T <= 64 * cus) return run_walk<BF16, 16, 6, 1, 1024, MODE>(p, leaf_idx, s);
             if (FUSED) {
                 // Beyond that a block takes its share in several rounds, and a round costs about
                 // the same whether its tile is full or not: up to 512 tokens per compute unit a
@@ -484,31 +514,31 @@ hipError_t dispatch_walk(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
                 if (p.T <= 512 * cus)
                     for (const int64_t cand : {(int64_t)96, (int64_t)64, (int64_t)32})
                         if (busy(cand) * 115 <= busy(tile) * 100) tile = cand;
-                if (tile == 96) return run_walk<BF16, 16, 6, 3, 512, FUSED>(p, leaf_idx, s);
-                if (tile == 64) return run_walk<BF16, 16, 6, 2, 512, FUSED>(p, leaf_idx, s);
-                if (tile == 32) return run_walk<BF16, 16, 6, 1, 512, FUSED>(p, leaf_idx, s);
-                return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
+                if (tile == 96) return run_walk<BF16, 16, 6, 3, 512, MODE>(p, leaf_idx, s);
+                if (tile == 64) return run_walk<BF16, 16, 6, 2, 512, MODE>(p, leaf_idx, s);
+                if (tile == 32) return run_walk<BF16, 16, 6, 1, 512, MODE>(p, leaf_idx, s);
+                return run_walk<BF16, 16, 6, 4, 512, MODE>(p, leaf_idx, s);
             }
         }
-        if (tpg == 1) return run_walk<BF16, 16, 6, 1, 1024, FUSED>(p, leaf_idx, s);
-        if (tpg == 2 && blk == 512) return run_walk<BF16, 16, 6, 2, 512, FUSED>(p, leaf_idx, s);
-        if (tpg == 4 && blk == 512) return run_walk<BF16, 16, 6, 4, 512, FUSED>(p, leaf_idx, s);
-        if (tpg == 3 && blk == 512) return run_walk<BF16, 16, 6, 3, 512, FUSED>(p, leaf_idx, s);
-        if (tpg == 4 && blk == 256) return run_walk<BF16, 16, 6, 4, 256, FUSED>(p, leaf_idx, s);
-        return run_walk<BF16, 16, 6, 2, 1024, FUSED>(p, leaf_idx, s);
+        if (tpg == 1) return run_walk<BF16, 16, 6, 1, 1024, MODE>(p, leaf_idx, s);
+        if (tpg == 2 && blk == 512) return run_walk<BF16, 16, 6, 2, 512, MODE>(p, leaf_idx, s);
+        if (tpg == 4 && blk == 512) return run_walk<BF16, 16, 6, 4, 512, MODE>(p, leaf_idx, s);
+        if (tpg == 3 && blk == 512) return run_walk<BF16, 16, 6, 3, 512, MODE>(p, leaf_idx, s);
+        if (tpg == 4 && blk == 256) return run_walk<BF16, 16, 6, 4, 256, MODE>(p, leaf_idx, s);
+        return run_walk<BF16, 16, 6, 2, 1024, MODE>(p, leaf_idx, s);
     }
-    if (nvec <= 128) return small_batch ? run_walk<BF16, 16, 8, 1, 512, FUSED>(p, leaf_idx, s)
-                                        : run_walk<BF16, 16, 8, 2, 512, FUSED>(p, leaf_idx, s);
-    if (nvec <= 256) return run_walk<BF16, 64, 4, 2, 1024, FUSED>(p, leaf_idx, s);
+    if (nvec <= 128) return small_batch ? run_walk<BF16, 16, 8, 1, 512, MODE>(p, leaf_idx, s)
+                                        : run_walk<BF16, 16, 8, 2, 512, MODE>(p, leaf_idx, s);
+    if (nvec <= 256) return run_walk<BF16, 64, 4, 2, 1024, MODE>(p, leaf_idx, s);
     if (nvec <= 512) {
         const int64_t tpg = g_walk_tuning.tpg, blk = g_walk_tuning.block;
-        if (tpg == 1 && blk == 1024) return run_walk<BF16, 64, 8, 1, 1024, FUSED>(p, leaf_idx, s);
-        if (tpg == 3 && blk == 512) return run_walk<BF16, 64, 8, 3, 512, FUSED>(p, leaf_idx, s);
-        if (tpg == 4 && blk == 256) return run_walk<BF16, 64, 8, 4, 256, FUSED>(p, leaf_idx, s);
-        if (tpg == 6 && blk == 256) return run_walk<BF16, 64, 8, 6, 256, FUSED>(p, leaf_idx, s);
-        return run_walk<BF16, 64, 8, 2, 512, FUSED>(p, leaf_idx, s);
+        if (tpg == 1 && blk == 1024) return run_walk<BF16, 64, 8, 1, 1024, MODE>(p, leaf_idx, s);
+        if (tpg == 3 && blk == 512) return run_walk<BF16, 64, 8, 3, 512, MODE>(p, leaf_idx, s);
+        if (tpg == 4 && blk == 256) return run_walk<BF16, 64, 8, 4, 256, MODE>(p, leaf_idx, s);
+        if (tpg == 6 && blk == 256) return run_walk<BF16, 64, 8, 6, 256, MODE>(p, leaf_idx, s);
+        return run_walk<BF16, 64, 8, 2, 512, MODE>(p, leaf_idx, s);
     }
-    return run_walk<BF16, 64, 16, 1, 512, FUSED>(p, leaf_idx, s);
+    return run_walk<BF16, 64, 16, 1, 512, MODE>(p, leaf_idx, s);
 }
 
 }  // namespace
@@ -527,7 +557,7 @@ hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s, De
     if (p.T == 0) return hipSuccess;
     if (walk_shape_ok(p)) {
         t_counts = dc;
-        const hipError_t e = p.bf16 ? dispatch_walk<true, false>(p, leaf_idx, s) : dispatch_walk<false, false>(p, leaf_idx, s);
+        const hipError_t e = p.bf16 ? dispatch_walk<true, kWalkDescend>(p, leaf_idx, s) : dispatch_walk<false, kWalkDescend>(p, leaf_idx, s);
         t_counts = nullptr;
         return e;
     }
@@ -545,7 +575,19 @@ hipError_t launch_descend(const Problem& p, int32_t* leaf_idx, hipStream_t s, De
 // Descent, leaf network and output row in one launch (needs fused_shape_ok).
 hipError_t launch_walk_fused(const Problem& p, int32_t* leaf_idx, hipStream_t s) {
     if (p.T == 0) return hipSuccess;
-    return p.bf16 ? dispatch_walk<true, true>(p, leaf_idx, s) : dispatch_walk<false, true>(p, leaf_idx, s);
+    return p.bf16 ? dispatch_walk<true, kWalkFused>(p, leaf_idx, s) : dispatch_walk<false, kWalkFused>(p, leaf_idx, s);
+}
+
+// The same launch stopping after the leaf's hidden neurons: leaf_idx [T] (required) and hidden [T, L]
+// (fp32) are left for launch_leaf_slices.
+hipError_t launch_walk_hidden(const Problem& p, int32_t* leaf_idx, float* hidden, hipStream_t s) {
+    if (p.T == 0) return hipSuccess;
+    if (!leaf_idx || !hidden) return hipErrorInvalidValue;
+    t_hidden_out = hidden;
+    const hipError_t e = p.bf16 ? dispatch_walk<true, kWalkHidden>(p, leaf_idx, s)
+                                : dispatch_walk<false, kWalkHidden>(p, leaf_idx, s);
+    t_hidden_out = nullptr;
+    return e;
 }
 
 }  // namespace fff

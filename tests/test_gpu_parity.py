@@ -53,7 +53,7 @@ def test_batch_beyond_the_token_chunk_bucketing():
     _log("large_batch", check_against_oracle(w, out, idx))
 
 
-@pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
+@pytest.mark.parametrize("path", [0, 1, 2, 5], ids=["auto", "fused", "staged", "split"])
 def test_large_skewed_workload(path, c5_workload):
     """C5 at full size (2.4 GB of leaf weights, Zipf leaf occupancy), both launch configurations."""
     import paper_2308_14711_amd as F
@@ -112,8 +112,8 @@ SMALL = [
 
 # (path, leaf_path): the staged path picks its leaf kernels by bucket size, so the tile kernels get
 # a run of their own on every shape they take
-@pytest.mark.parametrize("path", [(0, 0), (1, 0), (2, 0), (2, 2), (4, 0)],
-                         ids=["auto", "fused", "staged", "staged_tiles", "token"])
+@pytest.mark.parametrize("path", [(0, 0), (1, 0), (2, 0), (2, 2), (4, 0), (5, 0)],
+                         ids=["auto", "fused", "staged", "staged_tiles", "token", "split"])
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
 def test_small_and_edge_shapes(case, path):
     import paper_2308_14711_amd as F
@@ -256,6 +256,35 @@ def test_bucket_stage_is_bit_exact(depth, T, kind, kernel):
         F.fff_debug_option("bucket_kernel", 0)
 
 
+def test_split_launch_equals_the_fused_one_bit_for_bit():
+    """The fused launch cut in two (walk + hidden neurons, then output rows by column slices) does the
+    same additions in the same order as the single launch: same bits, on rows of 12 lines (4 slices),
+    of 8 lines (8 slices), of a line and a half (one short slice), fp32, no leaf_idx buffer."""
+    import torch
+    import paper_2308_14711_amd as F
+    cases = [(20000, 768, 768, 9, 1, W.DTYPE_BF16), (9000, 512, 512, 7, 2, W.DTYPE_BF16), (5000, 256, 96, 6, 8, W.DTYPE_BF16),
+             (7000, 768, 1032, 5, 3, W.DTYPE_BF16), (6000, 256, 200, 6, 2, W.DTYPE_F32), (3000, 64, 8, 4, 1, W.DTYPE_BF16)]
+    for T, D, O, depth, L, dtype in cases:
+        print("\n[case] split vs fused T=%d D=%d O=%d depth=%d L=%d dtype=%d seed 61" % (T, D, O, depth, L, dtype), flush=True)
+        w = W.make_layer("split", T, D, O, depth, L, W.ACT_GELU, dtype, seed=61)
+        dev = to_device(w)
+        res = {}
+        for path in (1, 5):
+            F.fff_set_option("path", path)
+            try:
+                res[path] = run_forward(w, dev, want_idx=path == 1)
+                assert F.fff_get_option("last_path") == path
+            finally:
+                F.fff_set_option("path", 0)
+        bits = torch.int16 if dtype == W.DTYPE_BF16 else torch.int32
+        assert torch.equal(res[1][0].view(bits), res[5][0].view(bits))
+        _log("split T=%d" % T, check_against_oracle(w, res[1][0], res[1][1]))
+    # the BERT-base-sized shape takes the split launch by itself
+    w = W.config("C4", keep_f32=False)
+    out, idx = run_forward(w)
+    assert F.fff_get_option("last_path") == 5 and "leaf_slices_kernel" in F.fff_last_launch(), F.fff_last_launch()
+
+
 def test_descent_hands_leaf_counts_to_the_bucketing_stage():
     """On the staged path the descent counts, per block, the tokens of every leaf, and one fold launch
     turns the counts into the grouped order: same rows, bit for bit, as with a bucketing kernel that
@@ -306,7 +335,7 @@ def test_descend_and_leaf_stages():
     assert err.max() <= 2e-2
 
 
-@pytest.mark.parametrize("opt", [("bucketing", 0), ("path", 1), ("path", 2), ("path", 3), ("path", 4),
+@pytest.mark.parametrize("opt", [("bucketing", 0), ("path", 1), ("path", 2), ("path", 3), ("path", 4), ("path", 5),
                                  ("leaf_path", 1)])
 def test_alternative_paths_agree_with_the_oracle(opt):
     import paper_2308_14711_amd as F
@@ -341,7 +370,7 @@ TILE_SIZES = [
 ]
 
 
-@pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
+@pytest.mark.parametrize("path", [1, 2, 5], ids=["fused", "staged", "split"])
 @pytest.mark.parametrize("case", TILE_SIZES, ids=[c[0] for c in TILE_SIZES])
 def test_tile_sizes_of_the_walk_kernels(case, path):
     import paper_2308_14711_amd as F
@@ -370,7 +399,7 @@ WALK_SWITCHES = [
 ]
 
 
-@pytest.mark.parametrize("path", [1, 2], ids=["fused", "staged"])
+@pytest.mark.parametrize("path", [1, 2, 5], ids=["fused", "staged", "split"])
 @pytest.mark.parametrize("switches", WALK_SWITCHES, ids=["_".join("%s%d" % (k[5:], v) for k, v in o.items()) + "_w%d" % d
                                                          for o, d in WALK_SWITCHES])
 def test_walk_kernel_switches(switches, path):
@@ -447,7 +476,7 @@ def test_leaf_stage_split_between_tile_and_gather_kernels(case):
         F.fff_debug_option("leaf_split", 0)
 
 
-@pytest.mark.parametrize("path", [1, 2, 4], ids=["fused", "staged", "token"])
+@pytest.mark.parametrize("path", [1, 2, 4, 5], ids=["fused", "staged", "token", "split"])
 def test_capture_in_a_hip_graph_and_replay(path):
     """The call only enqueues kernels on the given stream (no allocation once the workspace is
     reserved, no memset nodes): it can be captured, and every replay, with eager work and
@@ -505,7 +534,7 @@ def _random_cases(n, seed):
 RANDOM_CASES = _random_cases(36, seed=2024)
 
 
-@pytest.mark.parametrize("path", [(0, 0), (2, 0), (2, 2)], ids=["auto", "staged", "staged_tiles"])
+@pytest.mark.parametrize("path", [(0, 0), (2, 0), (2, 2), (5, 0)], ids=["auto", "staged", "staged_tiles", "split"])
 @pytest.mark.parametrize("case", RANDOM_CASES, ids=["%s_T%d_D%d_O%d_d%d_L%d_%s" % (c[0], c[1], c[2], c[3], c[4], c[5],
                                                                                     "bf16" if c[7] else "f32")
                                                     for c in RANDOM_CASES])
@@ -527,7 +556,7 @@ def test_random_shapes(case, path):
     _log("%s path=%d took=%d" % (name, path, took), check_against_oracle(w, out, idx))
 
 
-@pytest.mark.parametrize("path", [1, 2, 4], ids=["fused", "staged", "token"])
+@pytest.mark.parametrize("path", [1, 2, 4, 5], ids=["fused", "staged", "token", "split"])
 def test_nan_tokens_go_left_and_do_not_disturb_their_neighbours(path):
     """A NaN logit compares false with 0: such a token takes the left child at every node (the
     oracle's `logit >= 0` does the same) and its output row is NaN; every other token is unaffected."""
