@@ -544,6 +544,11 @@ def main():
                     help="token count in place of the workload's own (same recipe; 0 = as defined)")
     ap.add_argument("--sets", type=int, default=0, help="distinct x/out buffer sets to rotate (0 = auto)")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value (repeatable)")
+    ap.add_argument("--force-top", type=int, default=0,
+                    help="an experiment on the weights, not a workload: the biases of the top K nodes on the rightmost "
+                         "path are set so that every token takes the right child there; the batch then lands in "
+                         "1/2^K of the tree and the weight rows it gathers shrink by that factor (how much of a "
+                         "launch's time is rows that no longer fit an L2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
@@ -612,7 +617,7 @@ def main():
         return
 
     line = hard_bench(args.config, args, np, torch, W, F, headline=True)
-    if args.others and not (args.tokens or args.opt):
+    if args.others and not (args.tokens or args.opt or args.force_top):
         # the other two bandwidth-bound workloads, timed the same way (fewer extras): the default run
         # then covers all three configurations the bandwidth target is stated for
         line["others"] = {}
@@ -637,6 +642,16 @@ def hard_bench(name, args, np, torch, W, F, headline=True):
     no_dense = args.no_dense or not headline
     w = W.config(name, keep_f32=False, T=args.tokens or None)
     tdt = torch.bfloat16 if w.dtype == W.DTYPE_BF16 else torch.float32
+    if args.force_top:          # concentrate the routing: a large bias on the top nodes of the rightmost path
+        nb = np.array(w.device_array("node_b"), copy=True)
+        node = 0
+        for _ in range(min(args.force_top, w.depth)):
+            nb[node] = 0x42C8 if nb.dtype == np.uint16 else 100.0      # 100.0 as bf16 bits / fp32
+            node = 2 * node + 2
+        if w.dtype == W.DTYPE_BF16:
+            w.bits["node_b"] = nb
+        else:
+            w.f32["node_b"] = nb
 
     def up(a):
         a = np.ascontiguousarray(a)
@@ -846,7 +861,7 @@ def hard_bench(name, args, np, torch, W, F, headline=True):
         "dtype": "bf16" if w.dtype == W.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": "%s: %s" % (w.name, w.note), "T": w.T, "D": w.D, "O": w.O, "depth": w.depth,
                    "leaf_width": w.leaf_width, "act": "gelu" if w.act else "relu", "buffer_sets": nsets,
-                   "seed": 0, "options": args.opt,
+                   "seed": 0, "options": args.opt, "force_top": args.force_top,
                    "launch_path": path_names.get(F.fff_get_option("last_path"), "?"), "kernels": kernels},
         "roofline": roofline,
         "path": {"alg_bytes": alg["path"], "GBps": round(path_gbs, 1), "frac": round(path_gbs / HBM_PEAK_GBS, 4),
