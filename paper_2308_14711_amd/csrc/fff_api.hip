@@ -285,13 +285,20 @@ int choose_path(const Problem& p) {
         const int64_t out_table = ((int64_t)(p.L + 1) * p.O * es) << p.depth;
         const bool full_rows = p.O * es >= 1024 && p.D * es >= 1024;
         const bool big_batch = p.T > 32 * (int64_t)di.cus;
+        // (from 128 tokens per compute unit on, three quarters of an L2 are enough: 100000 tokens, 512-wide
+        // rows, two neurons, depth 10 -- 3.1 MB of output rows -- 94 us fused, 78 split)
+        const int64_t table_min = p.T >= 128 * (int64_t)di.cus ? di.l2_bytes * 3 / 4 : di.l2_bytes;
         const bool split = full_rows && big_batch &&
                            out_table <= 64 * di.l2_bytes &&     // beyond that no slice of it stays in an L2 either
-                           (out_table >= di.l2_bytes || (p.L == 1 && p.T >= 256 * (int64_t)di.cus));
+                           (out_table >= table_min || (p.L == 1 && p.T >= 256 * (int64_t)di.cus));
         return split ? (int)kPathSplit : (int)kPathFused;
     };
     if (!staged_ok) return fused_or_split();
     if (!fused_ok) return kPathStaged;
+    // one or two neurons a leaf are "three more tree levels" whatever the row length: never worth
+    // the passes of the staged path (9000 tokens, 3072 inputs, 768 outputs, two neurons, depth 9:
+    // 71 us staged, 62 fused, 55 split; 768-wide rows, two neurons, depth 13: 133 / 132 / 128)
+    if (p.L <= 2) return fused_or_split();
     // Grouping pays once the leaf rows a token meets are many bytes -- 24 KB (8 neurons on 768-wide
     // bf16 rows), or 12 KB (4 neurons) where the leaf weights together (8 MB) outgrow the 4 MB L2 of one XCD,
     // which the fused launch relies on for its per-token row fetches, or 8 KB (3 neurons) from 16 MB
