@@ -826,6 +826,8 @@ static int64_t* option_slot(const char* name) {
 //                    descent's inside fff_forward_hard, a counting launch's otherwise; up to 1024
 //                    leaves and 1024 tokens a block), each when the sizes allow it; 0 also takes
 //                    the fold kernel whenever the descent has left counts
+//   "soft_small_tiles" 1 = fff_forward_soft uses the 64 x 128 MFMA tile for every contraction (default:
+//                    the 128 x 256 tile where batch and width fill it)
 //   "walk_plain_x"   the descent reads token rows 1 = without the streaming hint, 2 = with it,
 //                    0 = without it while the batch fits half the last-level cache
 static int64_t* debug_slot(const char* name) {
@@ -840,6 +842,7 @@ static int64_t* debug_slot(const char* name) {
     if (!std::strcmp(name, "block_top")) return &g_block_tuning.top;
     if (!std::strcmp(name, "leaf_split")) return &g_opt.leaf_split;
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
+    if (!std::strcmp(name, "soft_small_tiles")) return &g_soft_small_tiles;
     return nullptr;
 }
 

@@ -86,6 +86,24 @@ __device__ __forceinline__ float activate(float v, int act) {
     return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
 }
 
+// The same activation for epilogues that apply it to hundreds of millions of values (the dense
+// contractions of the soft forward pass), where the library erf is what bounds the kernel:
+// erfc(z) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-z^2), t = 1 / (1 + p z) for z >= 0
+// (Abramowitz & Stegun 7.1.26, absolute error <= 1.5e-7), 1 + erf(v / sqrt 2) = 2 - erfc(z) for v >= 0,
+// erfc(z) for v < 0, z = |v| / sqrt 2.  The result differs from activate() by less than 5e-7 in absolute value (|v| <= 12, fp32 arithmetic),
+// three orders below the bf16 rounding those epilogues end in.
+__device__ __forceinline__ float activate_bulk(float v, int act) {
+    if (act == 0) return fmaxf(v, 0.0f);
+    const float z = fabsf(v) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float erfc_z = p * t * __expf(-z * z);
+    return 0.5f * v * (v >= 0.0f ? 2.0f - erfc_z : erfc_z);
+}
+
 // Streaming 16-byte load (tokens are read once; keep them out of the way of the weights).
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_stream(const uint4* p) {
@@ -113,5 +131,20 @@ constexpr int kXcds = 8;
 __device__ __forceinline__ int64_t xcd_contiguous_block() {
     return (int64_t)(blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
 }
+
+// Slot (16 bytes) of piece c of row r in an LDS tile of 128-byte rows that MFMA operands are read
+// from: 8 r + ((c + rot(r)) mod 8), rot(r) = bit 1 of r + 4 * bit 2 of r.
+//
+// ds_read_b128 serves a wave in four passes of 16 lanes, and the passes are not runs of
+// consecutive lanes: lanes {0-3, 12-15, 20-27}, {4-11, 16-19, 28-31}, and the same two sets + 32
+// (measured with pairs of lanes aimed at one bank).  An operand read has lane (j, kg) on row j,
+// piece 2 kg + u, so a pass holds every row j once: rows 0-3 and 12-15 with one kg, rows 4-11 with
+// the neighbouring kg, two pieces apart.  The 16 slots of a pass must differ mod 16 (64 banks);
+// rows of equal parity are told apart by rot(r), which takes {0, 1, 4, 5} on rows {0-3, 12-15} and
+// the same values on rows {4-11}: adding the two-piece distance gives {2, 3, 6, 7} there.  With this
+// rotation the operand reads run at the full 256 bytes a clock (the plain r / 2 rotation: half),
+// and the 16-byte stores of whole rows (8 consecutive lanes per row) at the full store rate.
+__device__ __forceinline__ int lds_rot(int row) { return ((row >> 1) & 1) + 4 * ((row >> 2) & 1); }
+__device__ __forceinline__ int tile_swz(int row, int piece) { return 8 * row + ((piece + lds_rot(row)) & 7); }
 
 }  // namespace fff

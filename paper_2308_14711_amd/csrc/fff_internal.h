@@ -163,6 +163,7 @@ hipError_t launch_moe_gate(const void* x, const void* gate_w, const void* gate_b
 
 // Forward_T (fff_soft.hip): the soft mixture over all leaves on the matrix cores.  scratch holds
 // soft_scratch_words(p) 32-bit words; mix [T, 2^depth] and entropy [2^depth - 1] (fp32) are optional outputs.
+extern int64_t g_soft_small_tiles;
 bool soft_shape_ok(const Problem& p);
 int64_t soft_scratch_words(const Problem& p);
 hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_out, float* entropy_out,

@@ -95,8 +95,8 @@ __device__ __forceinline__ int32_t leaf_of_run(const TileColumn& c, int run) {
 // 64 pp + 16 kg + 8 u of its row, so a pair of steps consumes one 128-byte line of every row.
 // Token rows come from HBM with 8 consecutive lanes on one line (two loads cover the 16 rows of
 // a pair) and are turned into the MFMA operand layout through a wave-private LDS buffer; piece c
-// (16 bytes) of row r sits at slot 8 r + ((c + r / 2) mod 8), which keeps both the writes and the
-// operand reads free of bank conflicts.
+// (16 bytes) of row r sits at slot tile_swz(r, c), which keeps both the writes and the operand
+// reads free of bank conflicts.
 //
 // NB = 1: leaf width <= 16, several runs per pass.  NB = 2: leaf width 17..32, one run per pass,
 // its neurons in two blocks of 16 rows that share the token operand (two accumulators).
@@ -122,10 +122,9 @@ __global__ __launch_bounds__(256) void leaf_hidden_kernel(const TilesArgs a) {
     const int32_t tok_lo = __shfl(c.tok, lr, 64), tok_hi = __shfl(c.tok, lr + 8, 64);
     const uint16_t* src_lo = a.x + (int64_t)(tok_lo >= 0 ? tok_lo : 0) * D + 8 * lc;
     const uint16_t* src_hi = a.x + (int64_t)(tok_hi >= 0 ? tok_hi : 0) * D + 8 * lc;
-    const int slot_lo = 8 * lr + ((lc + (lr >> 1)) & 7);
-    const int slot_hi = 8 * (lr + 8) + ((lc + ((lr + 8) >> 1)) & 7);
+    const int slot_lo = tile_swz(lr, lc), slot_hi = tile_swz(lr + 8, lc);
     // operand role: pieces 2 kg and 2 kg + 1 of row j
-    const int rd0 = 8 * j + ((2 * kg + (j >> 1)) & 7), rd1 = 8 * j + ((2 * kg + 1 + (j >> 1)) & 7);
+    const int rd0 = tile_swz(j, 2 * kg), rd1 = tile_swz(j, 2 * kg + 1);
 
     for (int pass = 0; pass < c.n_runs; pass += P) {
         int32_t row_leaf = -1;

@@ -4,8 +4,8 @@
 // fp32 accumulation on v_mfma_f32_16x16x32_bf16.
 //
 // A block of 256 threads (4 waves) walks K in chunks of 64 through double-buffered LDS tiles
-// (16-byte pieces, coalesced loads, piece c of row r at slot 8 r + ((c + r / 2) mod 8): stores and
-// operand reads are both free of bank conflicts).  Wave w owns columns 32 w .. 32 w + 31 of the
+// (16-byte pieces, coalesced loads, piece c of row r at slot tile_swz(r, c): stores and operand
+// reads are both free of bank conflicts).  Wave w owns columns 32 w .. 32 w + 31 of the
 // tile and all 64 rows: acc[mt][nt], lane (j, kg) of which holds rows 16 mt + 4 kg + q (q = 0..3)
 // against column 32 w + 16 nt + j.
 #pragma once
@@ -16,8 +16,6 @@ namespace fff {
 constexpr int kTileM = 64;      // rows (tokens) per block
 constexpr int kTileN = 128;     // columns per block
 constexpr int kTileK = 64;      // K elements per chunk (8 pieces of 16 bytes per row)
-
-__device__ __forceinline__ int tile_swz(int row, int piece) { return 8 * row + ((piece + (row >> 1)) & 7); }
 
 struct TileLds {
     uint4 a[2][kTileM * 8];
@@ -165,6 +163,143 @@ __device__ __forceinline__ void tile_store_bf16(TileLds& lds, const f32x4_t (&ac
             *(uint4*)(C + t * ldc + n) = *(const uint4*)(st + r * kTileN + 8 * pc);
         } else {
             for (int e = 0; e < 8 && n + e < N; ++e) C[t * ldc + n + e] = st[r * kTileN + 8 * pc + e];
+        }
+    }
+}
+
+// ---- the 128 x 256 tile of the large dense contractions (soft forward pass) -------------------
+//
+// A compute unit's LDS delivers 128 bytes a clock, its four matrix cores together 4096 bf16 flops
+// a clock: a tile has to do at least 32 flops per byte that passes through LDS or LDS is what
+// bounds it.  For a block tile of M x N with four waves in a 2 x 2 arrangement every chunk of K
+// is written once ((M + N) K 2 bytes) and read once per wave ((M/2 + N/2) K 2 bytes, four waves),
+// 2 M N K flops in all: M N / (3 (M + N)) flops per byte -- 14 for the 64 x 128 tile above (its
+// waves each hold all 64 rows, which makes it 12 reads for 16 MFMAs), 28 for 128 x 256.  So:
+// 256 threads, wave (wm, wn) owns rows 64 wm .. + 63 and columns 128 wn .. + 127 as 4 x 8
+// accumulators of v_mfma_f32_16x16x32_bf16 (128 registers); K walks in chunks of 64 through ONE
+// LDS stage (16 KB of A rows, 32 KB of B rows, the same rotation swizzle), the next chunk
+// travelling in registers meanwhile (12 pieces a thread); two blocks fit a compute unit, so one
+// block's barriers and its wait for the chunk are covered by the other's arithmetic.
+constexpr int kBigM = 128, kBigN = 256;
+
+struct BigTileLds {
+    uint4 a[kBigM * 8];      // 16 KB
+    uint4 b[kBigN * 8];      // 32 KB
+    uint4 pad[1024];         // the epilogue stages the tile's 128 x 256 bf16 results in all 64 KB
+};
+
+template <bool kInterior>
+__device__ __forceinline__ void mfma_tile_128x256_body(const uint16_t* __restrict__ A, int64_t lda, int64_t M,
+                                                  const uint16_t* __restrict__ B, int64_t ldb, int64_t N, int K,
+                                                  int64_t m0, int64_t n0, BigTileLds& lds, f32x4_t (&acc)[4][8]) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int j = lane & 15, kg = lane >> 4;
+    const int wm = wv >> 1, wn = wv & 1;
+    const int n_chunks = (K + kTileK - 1) / kTileK;
+    // loader roles: 8 consecutive threads fetch one row's 128 bytes of the chunk; a thread takes
+    // piece pc of rows r0 + 32 i: 4 rows of the A tile, 8 of the B tile.  Loads are unconditional
+    // with clamped addresses; rows past the end and K past the end are zeroed on the way to LDS.
+    const int pc = tid & 7, r0 = tid >> 3;
+    const uint16_t* pa[4];
+    const uint16_t* pb[8];
+    bool va[4], vb[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t r = m0 + r0 + 32 * i;
+        va[i] = r < M;
+        pa[i] = A + (va[i] ? r : M - 1) * lda + 8 * pc;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int64_t r = n0 + r0 + 32 * i;
+        vb[i] = r < N;
+        pb[i] = B + (vb[i] ? r : N - 1) * ldb + 8 * pc;
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) acc[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    uint4 qa[4], qb[8];
+    auto fetch = [&](int kc) {
+        const int koff = kInterior || kc * kTileK + 8 * pc < K ? kc * kTileK : 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qa[i] = *(const uint4*)(pa[i] + koff);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) qb[i] = *(const uint4*)(pb[i] + koff);
+    };
+    fetch(0);
+    for (int kc = 0; kc < n_chunks; ++kc) {
+        const bool kin = kInterior || kc * kTileK + 8 * pc < K;
+        __syncthreads();                                  // the previous chunk's operand reads are done
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lds.a[tile_swz(r0 + 32 * i, pc)] = kInterior ? qa[i] : keep_if(kin && va[i], qa[i]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lds.b[tile_swz(r0 + 32 * i, pc)] = kInterior ? qb[i] : keep_if(kin && vb[i], qb[i]);
+        __syncthreads();
+        fetch(kc + 1 < n_chunks ? kc + 1 : kc);           // travels while this chunk is multiplied
+        __builtin_amdgcn_sched_barrier(0);                // (left alone the scheduler sinks these loads to the next stash)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            bf16x8_t fa[4], fb[8];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+                fa[mt] = __builtin_bit_cast(bf16x8_t, lds.a[tile_swz(64 * wm + 16 * mt + j, 2 * kg + u)]);
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt)
+                fb[nt] = __builtin_bit_cast(bf16x8_t, lds.b[tile_swz(128 * wn + 16 * nt + j, 2 * kg + u)]);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+}
+
+// Tiles with every row inside both matrices and K a whole number of chunks (all but the ragged
+// edge) skip the zeroing selects on the way to LDS: a block-uniform choice.
+__device__ __forceinline__ void mfma_tile_128x256(const uint16_t* __restrict__ A, int64_t lda, int64_t M,
+                                                  const uint16_t* __restrict__ B, int64_t ldb, int64_t N, int K,
+                                                  int64_t m0, int64_t n0, BigTileLds& lds, f32x4_t (&acc)[4][8]) {
+    if (m0 + kBigM <= M && n0 + kBigN <= N && K % kTileK == 0)
+        mfma_tile_128x256_body<true>(A, lda, M, B, ldb, N, K, m0, n0, lds, acc);
+    else
+        mfma_tile_128x256_body<false>(A, lda, M, B, ldb, N, K, m0, n0, lds, acc);
+}
+
+// Epilogue of the 128 x 256 tile: value(r, c, v) maps row r, column c of the tile and the
+// accumulated v to the number stored as bf16; staged through all 64 KB of the tile's LDS so that
+// the rows leave as 16-byte pieces (32 consecutive threads on one row); rows past M and columns
+// past N are dropped.
+template <typename Value>
+__device__ __forceinline__ void big_tile_store_bf16(BigTileLds& lds, const f32x4_t (&acc)[4][8], uint16_t* __restrict__ C,
+                                                    int64_t ldc, int64_t M, int64_t N, int64_t m0, int64_t n0,
+                                                    Value value) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int j = lane & 15, kg = lane >> 4;
+    const int wm = wv >> 1, wn = wv & 1;
+    uint16_t* st = (uint16_t*)&lds;
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r = 64 * wm + 16 * mt + 4 * kg + q, c = 128 * wn + 16 * nt + j;
+                st[r * kBigN + c] = f32_to_bf16(value(r, c, acc[mt][nt][q]));
+            }
+    __syncthreads();
+    const bool vec = (ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(C) & 15u) == 0;
+    for (int idx = tid; idx < kBigM * (kBigN / 8); idx += 256) {
+        const int r = idx >> 5, pc = idx & 31;
+        const int64_t t = m0 + r, n = n0 + 8 * pc;
+        if (t >= M || n >= N) continue;
+        if (vec && n + 8 <= N) {
+            *(uint4*)(C + t * ldc + n) = *(const uint4*)(st + r * kBigN + 8 * pc);
+        } else {
+            for (int e = 0; e < 8 && n + e < N; ++e) C[t * ldc + n + e] = st[r * kBigN + 8 * pc + e];
         }
     }
 }

@@ -6,8 +6,8 @@
 //
 // The work is a dense [T, D] x [D, G] contraction, so it goes to the matrix cores: a block owns
 // 64 tokens x 128 experts, walks K = D in chunks of 64 through double-buffered LDS tiles
-// (16-byte pieces, coalesced loads, the rotation swizzle that keeps the operand reads free of
-// bank conflicts: piece c of row r at slot 8 r + ((c + r / 2) mod 8)), and each of its 4 waves
+// (16-byte pieces, coalesced loads, the rotation swizzle tile_swz that keeps the operand reads free
+// of bank conflicts), and each of its 4 waves
 // holds 4 x 2 accumulator tiles of v_mfma_f32_16x16x32_bf16.  The logits never reach memory: a
 // wave reduces its 32 experts per token with DPP row steps, the waves meet in LDS, and the block
 // writes one (value, index) candidate per token; a second small kernel picks the best candidate

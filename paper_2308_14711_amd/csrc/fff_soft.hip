@@ -18,6 +18,7 @@
 #include "fff_mfma_tile.h"
 
 namespace fff {
+int64_t g_soft_small_tiles = 0;     // experiment switch: 1 = the 64 x 128 tile for every contraction
 namespace {
 
 struct SoftArgs {
@@ -84,6 +85,41 @@ __global__ __launch_bounds__(256) void soft_mix_kernel(const SoftArgs a) {
         for (int64_t k = a.NL * (a.L + 1); k < a.K2; ++k) a.hid[t * a.K2 + k] = 0;
 }
 
+// The same for trees of up to 1024 leaves, a wave per token: the products grow level by level in a
+// wave-private LDS row (entry n of level m = entry n / 2 of level m - 1 times c or 1 - c of that
+// node), so a token's scores are read once, along the row, instead of once per leaf and level; the
+// factors are multiplied in the same order as above (root first): same bits.
+constexpr int kMixMaxLeaves = 1024;
+__global__ __launch_bounds__(256) void soft_mix_rows_kernel(const SoftArgs a) {
+    extern __shared__ float mix_lds[];                       // per wave: two rows of NL products
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int NL = (int)a.NL;
+    float* cur = mix_lds + (size_t)wv * 2 * NL;
+    float* nxt = cur + NL;
+    for (int64_t t = (int64_t)blockIdx.x * 4 + wv; t < a.T; t += (int64_t)gridDim.x * 4) {
+        const float* c = a.choice + t * a.NN;
+        if (lane == 0) cur[0] = 1.0f;
+        __builtin_amdgcn_wave_barrier();
+        for (int lvl = 0; lvl < a.depth; ++lvl) {
+            const int n_nodes = 1 << lvl;                    // nodes of this level; 2 n_nodes entries come out
+            const float* cl = c + (n_nodes - 1);
+            for (int e = lane; e < 2 * n_nodes; e += kWave) {
+                const float cs = cl[e >> 1];
+                nxt[e] = cur[e >> 1] * ((e & 1) ? cs : 1.0f - cs);
+            }
+            __builtin_amdgcn_wave_barrier();                 // LDS executes a wave's accesses in order
+            float* tmp = cur; cur = nxt; nxt = tmp;
+        }
+        for (int leaf = lane; leaf < NL; leaf += kWave) {
+            const float m = cur[leaf];
+            a.mix[t * a.NL + leaf] = m;
+            a.hid[t * a.K2 + a.NL * a.L + leaf] = f32_to_bf16(m);
+        }
+        for (int64_t k = a.NL * (a.L + 1) + lane; k < a.K2; k += kWave) a.hid[t * a.K2 + k] = 0;
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 // hidden: act(x . W1 + b1) scaled by the mixture weight of the neuron's leaf
 __global__ __launch_bounds__(256) void soft_hidden_kernel(const SoftArgs a) {
     __shared__ TileLds tile;
@@ -114,8 +150,70 @@ __global__ __launch_bounds__(256) void soft_hidden_kernel(const SoftArgs a) {
     __syncthreads();
     tile_store_bf16(tile, acc, a.hid, a.K2, a.T, NH, t0, n0, [&](int r, int c, float v) {
         const int nt = (c >> 4) & 1;
-        return activate(v + bias[nt], a.act) * mixt[r * n_leaf + lcol[nt]];
+        return activate_bulk(v + bias[nt], a.act) * mixt[r * n_leaf + lcol[nt]];
     });
+}
+
+// The same two contractions over the 128 x 256 tile (batches and widths that fill it).
+// Block -> tile so that the column tiles of one row tile run back to back on ONE XCD (blocks are
+// dealt to the 8 XCDs round robin): the first of them brings the row tile's A rows into that
+// XCD's L2, the others hit there instead of fetching them again from memory.  Row tile
+// 8 (i / ncb) + xcd, column tile i % ncb for the i-th block of an XCD; the grid is rounded up to
+// whole groups of 8 row tiles and blocks past the last row tile leave at once.
+__device__ __forceinline__ bool big_tile_of_block(int64_t ncb, int64_t M, int64_t& m0, int64_t& n0) {
+    const int64_t xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
+    m0 = (8 * (i / ncb) + xcd) * kBigM;
+    n0 = (i % ncb) * kBigN;
+    return m0 < M;
+}
+inline unsigned big_grid(int64_t M, int64_t ncb) {
+    const int64_t row_tiles = (M + kBigM - 1) / kBigM;
+    return (unsigned)(((row_tiles + 7) / 8) * 8 * ncb);
+}
+
+__global__ __launch_bounds__(256, 2) void soft_hidden_big_kernel(const SoftArgs a) {
+    __shared__ BigTileLds tile;
+    const int64_t NH = a.NL * a.L;
+    const int64_t ncb = (NH + kBigN - 1) / kBigN;
+    int64_t t0, n0;
+    if (!big_tile_of_block(ncb, a.T, t0, n0)) return;
+    f32x4_t acc[4][8];
+    mfma_tile_128x256(a.x, a.D, a.T, a.w1, a.D, NH, a.D, t0, n0, tile, acc);
+    // bias, activation and the mixture weight of the column's leaf, straight from the mixture matrix
+    // (a lane's 16 columns of a row are consecutive neurons: a handful of leaves, L2 hits)
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15, kg = lane >> 4;
+    const int wm = wv >> 1, wn = wv & 1;
+    int leaf[8];
+    float bias[8];
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) {
+        const int64_t n = n0 + 128 * wn + 16 * nt + j;
+        bias[nt] = n < NH ? bf16_to_f32(a.b1[n]) : 0.0f;
+        leaf[nt] = n < NH ? (int)(n / a.L) : -1;
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t t = t0 + 64 * wm + 16 * mt + 4 * kg + q;
+            const float* __restrict__ mrow = a.mix + (t < a.T ? t : a.T - 1) * a.NL;
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) {
+                const float m = leaf[nt] >= 0 ? mrow[leaf[nt]] : 0.0f;
+                acc[mt][nt][q] = activate_bulk(acc[mt][nt][q] + bias[nt], a.act) * m;
+            }
+        }
+    big_tile_store_bf16(tile, acc, a.hid, a.K2, a.T, NH, t0, n0, [](int, int, float v) { return v; });
+}
+
+__global__ __launch_bounds__(256, 2) void soft_out_big_kernel(const SoftArgs a) {
+    __shared__ BigTileLds tile;
+    const int64_t ncb = ((int64_t)a.O + kBigN - 1) / kBigN;
+    int64_t t0, n0;
+    if (!big_tile_of_block(ncb, a.T, t0, n0)) return;
+    f32x4_t acc[4][8];
+    mfma_tile_128x256(a.hid, a.K2, a.T, a.w2x, a.K2, a.O, (int)a.K2, t0, n0, tile, acc);
+    big_tile_store_bf16(tile, acc, a.out, a.O, a.T, a.O, t0, n0, [](int, int, float v) { return v; });
 }
 
 // W2x[o][k] = W2[k][o] for k < NL * L, b2[k - NL * L][o] for the next NL, zeros up to K2.
@@ -245,20 +343,37 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
     float* ent_part = (float*)w;
     const int64_t mb = (p.T + kTileM - 1) / kTileM;
     hipError_t e;
-    note_launch("%ssoft_mix_kernel + soft_hidden_kernel + soft_w2x_kernel + soft_out_kernel%s",
-                a.NN > 0 ? "soft_nodes_kernel + " : "",
+    note_launch("%ssoft_mix%s_kernel + soft_hidden_kernel + soft_w2x_kernel + soft_out_kernel%s",
+                a.NN > 0 ? "soft_nodes_kernel + " : "", a.NL <= kMixMaxLeaves ? "_rows" : "",
                 entropy_out && a.NN > 0 ? " + soft_entropy_part_kernel + soft_entropy_sum_kernel" : "");
     if (a.NN > 0) {
         soft_nodes_kernel<<<dim3((unsigned)(mb * ((a.NN + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    soft_mix_kernel<<<dim3((unsigned)((p.T * a.NL + 255) / 256)), dim3(256), 0, s>>>(a);
+    if (a.NL <= kMixMaxLeaves) {
+        int64_t blocks = (p.T + 3) / 4;
+        const int64_t cap = (int64_t)device_info().cus * 8;
+        if (blocks > cap) blocks = cap;
+        soft_mix_rows_kernel<<<dim3((unsigned)blocks), dim3(256), sizeof(float) * 8 * (size_t)a.NL, s>>>(a);
+    } else {
+        soft_mix_kernel<<<dim3((unsigned)((p.T * a.NL + 255) / 256)), dim3(256), 0, s>>>(a);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    soft_hidden_kernel<<<dim3((unsigned)(mb * ((a.NL * a.L + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
+    // the large tile where the batch and the width fill it (at least two tiles per compute unit's worth
+    // of rows, a full tile of columns)
+    const bool big = !g_soft_small_tiles && p.T >= 16 * kBigM;
+    const bool big_hidden = big && a.NL * a.L >= kBigN, big_out = big && p.O >= kBigN;
+    if (big_hidden)
+        soft_hidden_big_kernel<<<dim3(big_grid(p.T, (a.NL * a.L + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
+    else
+        soft_hidden_kernel<<<dim3((unsigned)(mb * ((a.NL * a.L + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     soft_w2x_kernel<<<dim3((unsigned)(((a.K2 + 31) / 32) * ((p.O + 31) / 32))), dim3(256), 0, s>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    soft_out_kernel<<<dim3((unsigned)(mb * ((p.O + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
+    if (big_out)
+        soft_out_big_kernel<<<dim3(big_grid(p.T, (p.O + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
+    else
+        soft_out_kernel<<<dim3((unsigned)(mb * ((p.O + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (entropy_out && a.NN > 0) {
         const int64_t n_parts = (p.T + kEntTokens - 1) / kEntTokens;
