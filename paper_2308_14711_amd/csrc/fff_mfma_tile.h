@@ -200,20 +200,23 @@ __device__ __forceinline__ void mfma_tile_128x256_body(const uint16_t* __restric
     // piece pc of rows r0 + 32 i: 4 rows of the A tile, 8 of the B tile.  Loads are unconditional
     // with clamped addresses; rows past the end and K past the end are zeroed on the way to LDS.
     const int pc = tid & 7, r0 = tid >> 3;
-    const uint16_t* pa[4];
-    const uint16_t* pb[8];
+    // addresses as a block-uniform base (tile origin + chunk) plus a 32-bit byte offset per row: half the
+    // registers of twelve 64-bit pointers (a tile spans at most 256 rows, far below 4 GB)
+    const char* const a_base = (const char*)(A + m0 * lda);
+    const char* const b_base = (const char*)(B + n0 * ldb);
+    uint32_t oa[4], ob[8];
     bool va[4], vb[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int64_t r = m0 + r0 + 32 * i;
-        va[i] = r < M;
-        pa[i] = A + (va[i] ? r : M - 1) * lda + 8 * pc;
+        const int64_t r = r0 + 32 * i;
+        va[i] = m0 + r < M;
+        oa[i] = (uint32_t)((va[i] ? r : M - 1 - m0) * lda * 2 + 16 * pc);
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int64_t r = n0 + r0 + 32 * i;
-        vb[i] = r < N;
-        pb[i] = B + (vb[i] ? r : N - 1) * ldb + 8 * pc;
+        const int64_t r = r0 + 32 * i;
+        vb[i] = n0 + r < N;
+        ob[i] = (uint32_t)((vb[i] ? r : N - 1 - n0) * ldb * 2 + 16 * pc);
     }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
@@ -221,24 +224,38 @@ __device__ __forceinline__ void mfma_tile_128x256_body(const uint16_t* __restric
         for (int nt = 0; nt < 8; ++nt) acc[mt][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     uint4 qa[4], qb[8];
-    auto fetch = [&](int kc) {
-        const int koff = kInterior || kc * kTileK + 8 * pc < K ? kc * kTileK : 0;
+    // chunk kc of every row: the chunk's byte offset is uniform for interior tiles; at the ragged end of K a
+    // thread whose piece lies past K re-reads chunk 0 (its value is zeroed on the way to LDS)
+#define FFF_BIG_LOAD(BASE, OFF, KC) \
+    (*(const uint4*)((BASE) + (kInterior ? (size_t)(KC) * (kTileK * 2) : (size_t)0) + \
+                     ((OFF) + (kInterior ? 0u : ((KC) * kTileK + 8 * pc < K ? (uint32_t)(KC) * (kTileK * 2) : 0u)))))
 #pragma unroll
-        for (int i = 0; i < 4; ++i) qa[i] = *(const uint4*)(pa[i] + koff);
+    for (int i = 0; i < 4; ++i) qa[i] = FFF_BIG_LOAD(a_base, oa[i], 0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) qb[i] = *(const uint4*)(pb[i] + koff);
-    };
-    fetch(0);
+    for (int i = 0; i < 8; ++i) qb[i] = FFF_BIG_LOAD(b_base, ob[i], 0);
     for (int kc = 0; kc < n_chunks; ++kc) {
         const bool kin = kInterior || kc * kTileK + 8 * pc < K;
+        const int kn = kc + 1 < n_chunks ? kc + 1 : kc;
         __syncthreads();                                  // the previous chunk's operand reads are done
+        // each piece goes to LDS and its register is refilled from the next chunk at once: the LDS
+        // stores and the address unit's work on the loads overlap instead of queueing one behind the
+        // other, and the loads travel while this chunk is multiplied
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lds.a[tile_swz(r0 + 32 * i, pc)] = kInterior ? qa[i] : keep_if(kin && va[i], qa[i]);
+        for (int i = 0; i < 4; ++i) {
+            lds.a[tile_swz(r0 + 32 * i, pc)] = kInterior ? qa[i] : keep_if(kin && va[i], qa[i]);
+            qa[i] = FFF_BIG_LOAD(a_base, oa[i], kn);
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) lds.b[tile_swz(r0 + 32 * i, pc)] = kInterior ? qb[i] : keep_if(kin && vb[i], qb[i]);
+        for (int i = 0; i < 8; ++i) {
+            lds.b[tile_swz(r0 + 32 * i, pc)] = kInterior ? qb[i] : keep_if(kin && vb[i], qb[i]);
+            qb[i] = FFF_BIG_LOAD(b_base, ob[i], kn);
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
         __syncthreads();
-        fetch(kc + 1 < n_chunks ? kc + 1 : kc);           // travels while this chunk is multiplied
-        __builtin_amdgcn_sched_barrier(0);                // (left alone the scheduler sinks these loads to the next stash)
+        __builtin_amdgcn_sched_barrier(0);                // (left alone the scheduler sinks the loads to the next stash)
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             bf16x8_t fa[4], fb[8];
@@ -256,6 +273,7 @@ __device__ __forceinline__ void mfma_tile_128x256_body(const uint16_t* __restric
         }
     }
     __syncthreads();
+#undef FFF_BIG_LOAD
 }
 
 // Tiles with every row inside both matrices and K a whole number of chunks (all but the ragged

@@ -171,6 +171,30 @@ inline unsigned big_grid(int64_t M, int64_t ncb) {
     return (unsigned)(((row_tiles + 7) / 8) * 8 * ncb);
 }
 
+__global__ __launch_bounds__(256, 2) void soft_nodes_big_kernel(const SoftArgs a) {
+    __shared__ BigTileLds tile;
+    const int64_t ncb = (a.NN + kBigN - 1) / kBigN;
+    int64_t t0, n0;
+    if (!big_tile_of_block(ncb, a.T, t0, n0)) return;
+    f32x4_t acc[4][8];
+    mfma_tile_128x256(a.x, a.D, a.T, a.node_w, a.D, a.NN, a.D, t0, n0, tile, acc);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15, kg = lane >> 4;
+    const int wm = wv >> 1, wn = wv & 1;
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) {
+        const int64_t n = n0 + 128 * wn + 16 * nt + j;
+        if (n >= a.NN) continue;
+        const float b = bf16_to_f32(a.node_b[n]);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t t = t0 + 64 * wm + 16 * mt + 4 * kg + q;
+                if (t < a.T) a.choice[t * a.NN + n] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
+            }
+    }
+}
+
 __global__ __launch_bounds__(256, 2) void soft_hidden_big_kernel(const SoftArgs a) {
     __shared__ BigTileLds tile;
     const int64_t NH = a.NL * a.L;
@@ -343,11 +367,20 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
     float* ent_part = (float*)w;
     const int64_t mb = (p.T + kTileM - 1) / kTileM;
     hipError_t e;
-    note_launch("%ssoft_mix%s_kernel + soft_hidden_kernel + soft_w2x_kernel + soft_out_kernel%s",
-                a.NN > 0 ? "soft_nodes_kernel + " : "", a.NL <= kMixMaxLeaves ? "_rows" : "",
+    // the large tile where the batch and the width fill it (a batch of at least 16 row tiles, a full tile
+    // of columns)
+    const bool big = !g_soft_small_tiles && p.T >= 16 * kBigM;
+    const bool big_nodes = big && a.NN >= kBigN - 1;
+    const bool big_hidden = big && a.NL * a.L >= kBigN, big_out = big && p.O >= kBigN;
+    note_launch("%s%ssoft_mix%s_kernel + soft_hidden%s_kernel + soft_w2x_kernel + soft_out%s_kernel%s",
+                a.NN > 0 ? (big_nodes ? "soft_nodes_big_kernel" : "soft_nodes_kernel") : "", a.NN > 0 ? " + " : "",
+                a.NL <= kMixMaxLeaves ? "_rows" : "", big_hidden ? "_big" : "", big_out ? "_big" : "",
                 entropy_out && a.NN > 0 ? " + soft_entropy_part_kernel + soft_entropy_sum_kernel" : "");
     if (a.NN > 0) {
-        soft_nodes_kernel<<<dim3((unsigned)(mb * ((a.NN + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
+        if (big_nodes)
+            soft_nodes_big_kernel<<<dim3(big_grid(p.T, (a.NN + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
+        else
+            soft_nodes_kernel<<<dim3((unsigned)(mb * ((a.NN + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (a.NL <= kMixMaxLeaves) {
@@ -359,10 +392,6 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
         soft_mix_kernel<<<dim3((unsigned)((p.T * a.NL + 255) / 256)), dim3(256), 0, s>>>(a);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    // the large tile where the batch and the width fill it (at least two tiles per compute unit's worth
-    // of rows, a full tile of columns)
-    const bool big = !g_soft_small_tiles && p.T >= 16 * kBigM;
-    const bool big_hidden = big && a.NL * a.L >= kBigN, big_out = big && p.O >= kBigN;
     if (big_hidden)
         soft_hidden_big_kernel<<<dim3(big_grid(p.T, (a.NL * a.L + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
     else

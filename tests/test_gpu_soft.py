@@ -19,6 +19,9 @@ CASES = [
     ("wide_leaves",  1000, 96,  40,  2, 32, W.ACT_RELU),
     ("one_token",    1,    64,  8,   5, 1,  W.ACT_GELU),
     ("odd_k2",       77,   72,  200, 1, 2,  W.ACT_GELU),      # 2 leaves x 3 columns = 6, padded to 8
+    # batches of 2048 rows or more take the 128 x 256 tile: ragged in rows, columns and K; then whole tiles
+    ("big_ragged",   2100, 200, 300, 7, 5,  W.ACT_GELU),
+    ("big_whole",    2304, 128, 256, 8, 1,  W.ACT_RELU),
 ]
 
 
