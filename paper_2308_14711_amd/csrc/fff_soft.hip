@@ -65,6 +65,13 @@ __global__ __launch_bounds__(256) void soft_nodes_kernel(const SoftArgs a) {
     }
 }
 
+// entropy of a Bernoulli variable of parameter c, natural logarithm
+__device__ __forceinline__ float bernoulli_entropy(float c) {
+    const float h0 = c > 0.0f ? -c * __logf(c) : 0.0f;
+    const float h1 = c < 1.0f ? -(1.0f - c) * __logf(1.0f - c) : 0.0f;
+    return h0 + h1;
+}
+
 // mixture weights: one thread per (token, leaf); also the bias columns of the hidden matrix
 __global__ __launch_bounds__(256) void soft_mix_kernel(const SoftArgs a) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -195,6 +202,107 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_big_kernel(const SoftArgs a
     }
 }
 
+// Trees of up to 256 leaves (all nodes in one column tile): the node contraction, the mixture weights and
+// the entropy sums in one launch -- the scores never go to memory.  After the contraction the tile's
+// scores pass through LDS 64 rows at a time (column n of row r at 256 r + (n xor 16 ((r / 4) mod 4)):
+// the accumulator layout has lane groups four rows apart on equal columns, the xor spreads them over
+// the banks; the readers below run along a row).  Then a wave takes 16 of the rows and multiplies
+// every leaf's path, root first (the factors and their order are those of soft_mix_kernel: same bits),
+// writing the mixture weights and the bias columns of the hidden matrix; thread n adds the entropies
+// of node n over the tile's rows in row order into part[row tile][n].
+__global__ __launch_bounds__(256, 2) void soft_nodes_mix_kernel(const SoftArgs a, float* __restrict__ ent_part) {
+    __shared__ BigTileLds tile;
+    int64_t t0, n0;
+    if (!big_tile_of_block(1, a.T, t0, n0)) return;
+    f32x4_t acc[4][8];
+    mfma_tile_128x256(a.x, a.D, a.T, a.node_w, a.D, a.NN, a.D, t0, 0, tile, acc);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, j = lane & 15, kg = lane >> 4;
+    const int wm = wv >> 1, wn = wv & 1;
+    const int NL = (int)a.NL, NN = (int)a.NN;
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) {
+        const int n = 128 * wn + 16 * nt + j;
+        const float b = n < NN ? bf16_to_f32(a.node_b[n]) : 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[mt][nt][q] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
+    }
+    float* const S = (float*)&tile;                     // [64][256] scores of one half of the tile's rows
+    const int per_log = NL >= 256 ? 2 : NL >= 128 ? 1 : 0;   // leaves per lane: 4, 2 or 1
+    const bool mix_vec = (reinterpret_cast<uintptr_t>(a.mix) & 15u) == 0;
+    float ent = 0.0f;
+    for (int h = 0; h < 2; ++h) {
+        if (wm == h) {
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        S[256 * (16 * mt + 4 * kg + q) + ((128 * wn + 16 * nt + j) ^ (16 * kg))] = acc[mt][nt][q];
+        }
+        __syncthreads();
+        for (int rr = 0; rr < 16; ++rr) {
+            const int r = 16 * wv + rr;
+            const int64_t t = t0 + 64 * h + r;
+            if (t >= a.T) break;
+            const float* Sr = S + 256 * r;
+            const int sw = 16 * ((r >> 2) & 3);
+            // a lane takes `per` consecutive leaves (4 for 256 leaves): their paths share all but the last
+            // log2(per) levels, so the shared factors are multiplied once, root first, and the product
+            // then splits level by level -- every leaf still sees its factors in root-to-leaf order
+            const int first = lane << per_log;
+            if (first < NL) {
+                float m[4];
+                m[0] = 1.0f;
+                const int shared = a.depth - per_log;
+                for (int lvl = 0; lvl < shared; ++lvl) {
+                    const int pos = first >> (a.depth - lvl);
+                    const int bit = (first >> (a.depth - 1 - lvl)) & 1;
+                    const float cs = Sr[(((1 << lvl) - 1) + pos) ^ sw];
+                    m[0] *= bit ? cs : 1.0f - cs;
+                }
+                if (per_log == 2) {
+                    const int n6 = ((1 << shared) - 1) + lane;                 // the lane's node on level depth - 2
+                    const float c6 = Sr[n6 ^ sw];
+                    const float c70 = Sr[(2 * n6 + 1) ^ sw], c71 = Sr[(2 * n6 + 2) ^ sw];
+                    const float lo = m[0] * (1.0f - c6), hi = m[0] * c6;
+                    m[0] = lo * (1.0f - c70); m[1] = lo * c70; m[2] = hi * (1.0f - c71); m[3] = hi * c71;
+                    // one 16-byte store (a caller's mixture matrix may start anywhere: checked) and one 8-byte store
+                    // (the hidden matrix is the library's, K2 a multiple of 8)
+                    float* mp = a.mix + t * a.NL + first;
+                    if (mix_vec) {
+                        *(float4*)mp = make_float4(m[0], m[1], m[2], m[3]);
+                    } else {
+                        mp[0] = m[0]; mp[1] = m[1]; mp[2] = m[2]; mp[3] = m[3];
+                    }
+                    *(uint2*)(a.hid + t * a.K2 + a.NL * a.L + first) =
+                        make_uint2((uint32_t)f32_to_bf16(m[0]) | ((uint32_t)f32_to_bf16(m[1]) << 16),
+                                   (uint32_t)f32_to_bf16(m[2]) | ((uint32_t)f32_to_bf16(m[3]) << 16));
+                } else if (per_log == 1) {
+                    const float c7 = Sr[(((1 << shared) - 1) + lane) ^ sw];
+                    m[1] = m[0] * c7; m[0] = m[0] * (1.0f - c7);
+                    float* mp = a.mix + t * a.NL + first;
+                    mp[0] = m[0]; mp[1] = m[1];
+                    uint16_t* hp = a.hid + t * a.K2 + a.NL * a.L + first;
+                    hp[0] = f32_to_bf16(m[0]); hp[1] = f32_to_bf16(m[1]);
+                } else {
+                    a.mix[t * a.NL + first] = m[0];
+                    a.hid[t * a.K2 + a.NL * a.L + first] = f32_to_bf16(m[0]);
+                }
+            }
+            for (int64_t k = a.NL * (a.L + 1) + lane; k < a.K2; k += kWave) a.hid[t * a.K2 + k] = 0;
+        }
+        if (ent_part != nullptr && tid < NN) {
+            for (int r = 0; r < 64 && t0 + 64 * h + r < a.T; ++r)
+                ent += bernoulli_entropy(S[256 * r + (tid ^ (16 * ((r >> 2) & 3)))]);
+        }
+        __syncthreads();
+    }
+    if (ent_part != nullptr && tid < NN) ent_part[(t0 / kBigM) * a.NN + tid] = ent;
+}
+
 __global__ __launch_bounds__(256, 2) void soft_hidden_big_kernel(const SoftArgs a) {
     __shared__ BigTileLds tile;
     const int64_t NH = a.NL * a.L;
@@ -287,10 +395,7 @@ __global__ __launch_bounds__(256) void soft_entropy_part_kernel(const float* __r
     for (int64_t n = threadIdx.x; n < NN; n += 256) {
         float s = 0.0f;
         for (int64_t t = t0; t < t1; ++t) {
-            const float c = choice[t * NN + n];
-            const float h0 = c > 0.0f ? -c * __logf(c) : 0.0f;
-            const float h1 = c < 1.0f ? -(1.0f - c) * __logf(1.0f - c) : 0.0f;
-            s += h0 + h1;
+            s += bernoulli_entropy(choice[t * NN + n]);
         }
         part[(int64_t)blockIdx.x * NN + n] = s;
     }
@@ -372,26 +477,38 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
     const bool big = !g_soft_small_tiles && p.T >= 16 * kBigM;
     const bool big_nodes = big && a.NN >= kBigN - 1;
     const bool big_hidden = big && a.NL * a.L >= kBigN, big_out = big && p.O >= kBigN;
-    note_launch("%s%ssoft_mix%s_kernel + soft_hidden%s_kernel + soft_w2x_kernel + soft_out%s_kernel%s",
-                a.NN > 0 ? (big_nodes ? "soft_nodes_big_kernel" : "soft_nodes_kernel") : "", a.NN > 0 ? " + " : "",
-                a.NL <= kMixMaxLeaves ? "_rows" : "", big_hidden ? "_big" : "", big_out ? "_big" : "",
-                entropy_out && a.NN > 0 ? " + soft_entropy_part_kernel + soft_entropy_sum_kernel" : "");
-    if (a.NN > 0) {
-        if (big_nodes)
-            soft_nodes_big_kernel<<<dim3(big_grid(p.T, (a.NN + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
-        else
-            soft_nodes_kernel<<<dim3((unsigned)(mb * ((a.NN + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
+    // nodes, mixture weights and entropy sums in one launch where all nodes fit one column tile
+    const bool fused_nodes = big && a.NN > 0 && a.NN < kBigN;
+    const bool want_entropy = entropy_out && a.NN > 0;
+    if (fused_nodes)
+        note_launch("soft_nodes_mix_kernel + soft_hidden%s_kernel + soft_w2x_kernel + soft_out%s_kernel%s",
+                    big_hidden ? "_big" : "", big_out ? "_big" : "", want_entropy ? " + soft_entropy_sum_kernel" : "");
+    else
+        note_launch("%s%ssoft_mix%s_kernel + soft_hidden%s_kernel + soft_w2x_kernel + soft_out%s_kernel%s",
+                    a.NN > 0 ? (big_nodes ? "soft_nodes_big_kernel" : "soft_nodes_kernel") : "", a.NN > 0 ? " + " : "",
+                    a.NL <= kMixMaxLeaves ? "_rows" : "", big_hidden ? "_big" : "", big_out ? "_big" : "",
+                    want_entropy ? " + soft_entropy_part_kernel + soft_entropy_sum_kernel" : "");
+    if (fused_nodes) {
+        soft_nodes_mix_kernel<<<dim3(big_grid(p.T, 1)), dim3(256), 0, s>>>(a, want_entropy ? ent_part : nullptr);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    } else {
+        if (a.NN > 0) {
+            if (big_nodes)
+                soft_nodes_big_kernel<<<dim3(big_grid(p.T, (a.NN + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
+            else
+                soft_nodes_kernel<<<dim3((unsigned)(mb * ((a.NN + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
+        if (a.NL <= kMixMaxLeaves) {
+            int64_t blocks = (p.T + 3) / 4;
+            const int64_t cap = (int64_t)device_info().cus * 8;
+            if (blocks > cap) blocks = cap;
+            soft_mix_rows_kernel<<<dim3((unsigned)blocks), dim3(256), sizeof(float) * 8 * (size_t)a.NL, s>>>(a);
+        } else {
+            soft_mix_kernel<<<dim3((unsigned)((p.T * a.NL + 255) / 256)), dim3(256), 0, s>>>(a);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    if (a.NL <= kMixMaxLeaves) {
-        int64_t blocks = (p.T + 3) / 4;
-        const int64_t cap = (int64_t)device_info().cus * 8;
-        if (blocks > cap) blocks = cap;
-        soft_mix_rows_kernel<<<dim3((unsigned)blocks), dim3(256), sizeof(float) * 8 * (size_t)a.NL, s>>>(a);
-    } else {
-        soft_mix_kernel<<<dim3((unsigned)((p.T * a.NL + 255) / 256)), dim3(256), 0, s>>>(a);
-    }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
     if (big_hidden)
         soft_hidden_big_kernel<<<dim3(big_grid(p.T, (a.NL * a.L + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
     else
@@ -404,10 +521,13 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
     else
         soft_out_kernel<<<dim3((unsigned)(mb * ((p.O + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (entropy_out && a.NN > 0) {
-        const int64_t n_parts = (p.T + kEntTokens - 1) / kEntTokens;
-        soft_entropy_part_kernel<<<dim3((unsigned)n_parts), dim3(256), 0, s>>>(a.choice, p.T, a.NN, ent_part);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (want_entropy) {
+        int64_t n_parts = (p.T + kBigM - 1) / kBigM;        // the fused launch leaves one partial sum per row tile
+        if (!fused_nodes) {
+            n_parts = (p.T + kEntTokens - 1) / kEntTokens;
+            soft_entropy_part_kernel<<<dim3((unsigned)n_parts), dim3(256), 0, s>>>(a.choice, p.T, a.NN, ent_part);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
         soft_entropy_sum_kernel<<<dim3((unsigned)a.NN), dim3(256), 0, s>>>(ent_part, n_parts, p.T, a.NN, entropy_out);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }

@@ -22,6 +22,8 @@ CASES = [
     # batches of 2048 rows or more take the 128 x 256 tile: ragged in rows, columns and K; then whole tiles
     ("big_ragged",   2100, 200, 300, 7, 5,  W.ACT_GELU),
     ("big_whole",    2304, 128, 256, 8, 1,  W.ACT_RELU),
+    ("big_shallow",  2200, 96,  24,  2, 4,  W.ACT_GELU),      # three nodes in the fused nodes + mixture launch
+    ("big_deep",     2050, 64,  40,  9, 1,  W.ACT_RELU),      # 511 nodes: two column tiles, separate mixture kernel
 ]
 
 
