@@ -62,6 +62,30 @@ def test_forward_soft_against_the_oracle(case):
     print("  soft %s: max row error %.2e, mixture %.1e, entropy %.1e" % (name, err.max(), mix_err, ent_err), flush=True)
 
 
+def test_mixture_weights_into_a_buffer_that_is_only_4_byte_aligned():
+    """The fused nodes + mixture launch stores a lane's four weights as one 16-byte piece when the caller's
+    matrix allows it; a matrix that starts 4 bytes into an allocation takes the scalar stores: same bits."""
+    import torch
+    import paper_2308_14711_amd as F
+    T, D, O, depth, L = 2304, 64, 32, 8, 1
+    w = W.make_layer("mix_align", T, D, O, depth, L, W.ACT_RELU, W.DTYPE_BF16, seed=5)
+    dev = to_device(w)
+    NL = 1 << depth
+    out = torch.empty((T, O), dtype=torch.bfloat16, device="cuda")
+    aligned = torch.full((T, NL), float("nan"), dtype=torch.float32, device="cuda")
+    backing = torch.full((T * NL + 4,), float("nan"), dtype=torch.float32, device="cuda")
+    shifted = backing[1:1 + T * NL].view(T, NL)
+    assert shifted.data_ptr() % 16 == 4
+    for mix in (aligned, shifted):
+        F.fff_forward_soft(dev["x"], dev["node_w"], dev["node_b"], dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"],
+                           dev["leaf_b2"], depth, L, w.act, out, mix, None)
+    torch.cuda.synchronize()
+    assert "soft_nodes_mix_kernel" in F.fff_last_launch()
+    assert bool(torch.isfinite(shifted).all())
+    assert torch.equal(aligned, shifted)
+    assert bool(torch.isnan(backing[0])) and bool(torch.isnan(backing[1 + T * NL:]).all())
+
+
 def test_forward_soft_at_the_vit_block_size():
     """The soft pass at the full size of the ViT-block workload (50432 tokens against all 256 leaves), in
     the launch configuration the benchmark times: output rows and mixture weights on a strided sample of
