@@ -149,10 +149,13 @@ def algorithmic_bytes(w, ref_idx):
         cur = np.unique(cur >> 1)
         nodes.update(((1 << m) - 1 + cur).tolist())
     u_node, u_leaf = len(nodes), int(leaves.size)
+    counts = np.bincount(np.asarray(ref_idx, dtype=np.int64), minlength=1 << d)
+    occupancy = {"leaves": 1 << d, "non_empty": u_leaf, "max_bucket": int(counts.max()),
+                 "singletons": int((counts == 1).sum()), "mean_bucket_of_non_empty": round(T / max(u_leaf, 1), 2)}
     node_bytes = u_node * (D * s + s)
     leaf_bytes = u_leaf * (L * D * s + L * s + L * O * s + O * s)
     return {
-        "u_node": u_node, "u_leaf": u_leaf,
+        "u_node": u_node, "u_leaf": u_leaf, "occupancy": occupancy,
         "path": T * D * s + T * O * s + 4 * T + node_bytes + leaf_bytes,
         "descent": T * D * s + 4 * T + node_bytes,
         "bucketing": 4 * T + 4 * T,                     # leaf_idx in, perm out
@@ -629,6 +632,7 @@ def main():
                                     "launch_path": o["config"]["launch_path"], "kernels": o["config"]["kernels"],
                                     "alg_bytes": o["path"]["alg_bytes"], "path_frac": o["path"]["frac"],
                                     "path_frac_of_copy_ceiling": o["path"].get("frac_of_copy_ceiling"),
+                                    "leaf_occupancy": o["leaf_occupancy"],
                                     "stages": o["stages"], "parity": o["parity"],
                                     "workload": o["config"]["workload"]}
     print(json.dumps(line))
@@ -867,6 +871,7 @@ def hard_bench(name, args, np, torch, W, F, headline=True):
         "path": {"alg_bytes": alg["path"], "GBps": round(path_gbs, 1), "frac": round(path_gbs / HBM_PEAK_GBS, 4),
                  "frac_of_copy_ceiling": round(path_gbs / copy_ceiling_once(torch)["GBps"], 4),
                  "u_node": alg["u_node"], "u_leaf": alg["u_leaf"]},
+        "leaf_occupancy": alg["occupancy"],
         "copy_ceiling": copy_ceiling_once(torch),
         "stages": stages,
         "timing_stats": timing_stats,

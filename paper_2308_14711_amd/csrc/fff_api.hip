@@ -135,6 +135,8 @@ int current_device(int* dev) {
     return FFF_OK;
 }
 
+int64_t g_fail_growths = 0;   // debug option "fail_workspace_growth": how many of the next growths fail
+
 // Makes the current device's library-owned block at least `need` bytes (g_mu held).  Growing frees
 // the old block (which waits for the device) and cannot be done while `s` is being captured.
 int grow_owned(DeviceWs& d, size_t need, hipStream_t s, bool check_capture) {
@@ -156,7 +158,12 @@ int grow_owned(DeviceWs& d, size_t need, hipStream_t s, bool check_capture) {
         if (e != hipSuccess) return set_device_error(e, "hipFree(workspace)");
     }
     void* p = nullptr;
-    e = hipMalloc(&p, need);
+    if (g_fail_growths > 0) {          // test hook: this growth fails the way an exhausted device would
+        --g_fail_growths;
+        e = hipErrorOutOfMemory;
+    } else {
+        e = hipMalloc(&p, need);
+    }
     if (e != hipSuccess) {
         (void)hipGetLastError();
         g_last_error = std::string("hipMalloc(workspace): ") + hipGetErrorString(e);
@@ -826,6 +833,8 @@ static int64_t* option_slot(const char* name) {
 //                    descent's inside fff_forward_hard, a counting launch's otherwise; up to 1024
 //                    leaves and 1024 tokens a block), each when the sizes allow it; 0 also takes
 //                    the fold kernel whenever the descent has left counts
+//   "fail_workspace_growth" n = the next n growths of the library's own workspace fail as if the device
+//                    were out of memory (FFF_ERR_WORKSPACE; the call after them allocates again)
 //   "soft_small_tiles" 1 = fff_forward_soft uses the 64 x 128 MFMA tile for every contraction (default:
 //                    the 128 x 256 tile where batch and width fill it)
 //   "walk_plain_x"   the descent reads token rows 1 = without the streaming hint, 2 = with it,
@@ -843,6 +852,7 @@ static int64_t* debug_slot(const char* name) {
     if (!std::strcmp(name, "leaf_split")) return &g_opt.leaf_split;
     if (!std::strcmp(name, "bucket_kernel")) return &g_opt.bucket_kernel;
     if (!std::strcmp(name, "soft_small_tiles")) return &g_soft_small_tiles;
+    if (!std::strcmp(name, "fail_workspace_growth")) return &g_fail_growths;
     return nullptr;
 }
 

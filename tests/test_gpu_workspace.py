@@ -168,3 +168,34 @@ def test_moe_and_soft_on_a_caller_workspace():
     finally:
         F.fff_set_workspace(None)
         F.fff_set_option("path", 0)
+
+
+def test_a_failed_growth_is_an_error_and_the_next_call_recovers():
+    """The library's own workspace cannot grow (forced through the test hook that makes the next growth
+    fail the way an exhausted device does): the call returns FFF_ERR_WORKSPACE with nothing enqueued, the
+    output is untouched, and the call after it allocates again and is right."""
+    import torch
+    import paper_2308_14711_amd as F
+    print("\n[case] forced workspace growth failure: T=6000 D=128 O=64 depth=5 L=2 bf16 seed 31 path=2", flush=True)
+    w = W.make_layer("ws_fail", 6000, 128, 64, 5, 2, W.ACT_RELU, W.DTYPE_BF16, seed=31)
+    dev = to_device(w)
+    torch.cuda.synchronize()
+    F.fff_set_workspace(None)
+    F.fff_release_workspace()                      # the next call has to allocate
+    F.fff_set_option("path", 2)
+    try:
+        out = torch.full((w.T, w.O), float("nan"), dtype=torch.bfloat16, device="cuda")
+        idx = torch.full((w.T,), -7, dtype=torch.int32, device="cuda")
+        assert F.fff_debug_option("fail_workspace_growth", 1) == 1
+        with pytest.raises(F.FffError) as e:
+            _forward(F, w, dev, out, idx)
+        assert e.value.status == WORKSPACE and "hipMalloc" in str(e.value)
+        assert F.fff_debug_option("fail_workspace_growth") == 0      # the hook was used up
+        torch.cuda.synchronize()
+        assert bool(torch.isnan(out.float()).all()) and bool((idx == -7).all())
+        _forward(F, w, dev, out, idx)
+        torch.cuda.synchronize()
+        check_against_oracle(w, out, idx)
+    finally:
+        F.fff_debug_option("fail_workspace_growth", 0)
+        F.fff_set_option("path", 0)
