@@ -62,6 +62,49 @@ def test_forward_soft_against_the_oracle(case):
     print("  soft %s: max row error %.2e, mixture %.1e, entropy %.1e" % (name, err.max(), mix_err, ent_err), flush=True)
 
 
+def _random_soft_cases():
+    rng = np.random.default_rng(2024)
+    cases = []
+    for i in range(8):
+        depth = int(rng.integers(1, 10))
+        L = int(rng.integers(1, 7))
+        cases.append(("random%d" % i, int(rng.integers(2048, 3200)), 8 * int(rng.integers(2, 40)),
+                      8 * int(rng.integers(1, 50)), depth, L, int(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_soft_cases(), ids=lambda c: c[0])
+def test_forward_soft_on_seeded_random_shapes_that_take_the_large_tiles(case):
+    """Batches of 2048 rows and more (the 128 x 256 tile wherever the widths fill it, the 64 x 128 tile
+    elsewhere, the fused or the separate mixture launch by depth) against the oracle."""
+    import torch
+    import paper_2308_14711_amd as F
+    name, T, D, O, depth, L, act = case
+    print("\n[case] soft %s T=%d D=%d O=%d depth=%d L=%d act=%d seed 77" % (name, T, D, O, depth, L, act), flush=True)
+    w = W.make_layer(name, T, D, O, depth, L, act, W.DTYPE_BF16, seed=77)
+    dev = to_device(w)
+    NL, NN = 1 << depth, (1 << depth) - 1
+    out = torch.full((T, O), float("nan"), dtype=torch.bfloat16, device="cuda")
+    mix = torch.full((T, NL), float("nan"), dtype=torch.float32, device="cuda")
+    ent = torch.full((NN,), float("nan"), dtype=torch.float32, device="cuda")
+    F.fff_forward_soft(dev["x"], dev["node_w"], dev["node_b"], dev["leaf_w1"], dev["leaf_b1"], dev["leaf_w2"],
+                       dev["leaf_b2"], depth, L, act, out, mix, ent)
+    torch.cuda.synchronize()
+    launched = F.fff_last_launch()
+    ref_out, ref_mix = oracle.forward_soft(*oracle_inputs(w), depth, L, act)
+    got = out_to_f64(out)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref_out).max(axis=1) / np.maximum(np.abs(ref_out).max(axis=1), 1e-30)
+    mix_err = np.abs(mix.cpu().numpy().astype(np.float64) - ref_mix).max()
+    ref_ent = oracle.node_entropy(w.bits["x"], w.bits["node_w"], w.bits["node_b"], depth)
+    ent_err = np.abs(ent.cpu().numpy().astype(np.float64) - ref_ent).max()
+    print("  soft %s: %s: max row error %.2e, mixture %.1e, entropy %.1e" % (name, launched, err.max(), mix_err, ent_err),
+          flush=True)
+    assert mix_err <= 1e-4 and ent_err <= 1e-4
+    assert err.max() <= TOL[W.DTYPE_BF16], "row error %.3e" % err.max()
+    assert ("soft_nodes_mix_kernel" in launched) == (depth <= 8)
+
+
 def test_mixture_weights_into_a_buffer_that_is_only_4_byte_aligned():
     """The fused nodes + mixture launch stores a lane's four weights as one 16-byte piece when the caller's
     matrix allows it; a matrix that starts 4 bytes into an allocation takes the scalar stores: same bits."""
