@@ -176,7 +176,11 @@ __device__ __forceinline__ void tile_store_bf16(TileLds& lds, const f32x4_t (&ac
 // 2 M N K flops in all: M N / (3 (M + N)) flops per byte -- 14 for the 64 x 128 tile above (its
 // waves each hold all 64 rows, which makes it 12 reads for 16 MFMAs), 28 for 128 x 256.  So:
 // 256 threads, wave (wm, wn) owns rows 64 wm .. + 63 and columns 128 wn .. + 127 as 4 x 8
-// accumulators of v_mfma_f32_16x16x32_bf16 (128 registers); K walks in chunks of 64 through ONE
+// accumulators of v_mfma_f32_16x16x32_bf16 (128 registers).  The B rows go in as the instruction's
+// first operand, so acc[mt][nt] of lane (j, kg) holds row 64 wm + 16 mt + j against the FOUR
+// CONSECUTIVE columns 128 wn + 16 nt + 4 kg + q (q = 0..3): an epilogue handles 8 bytes of a bf16
+// output row (or 16 of an fp32 one) per lane and tile, and whatever it looks up per column group
+// (a bias, the leaf a neuron belongs to) once for four values; K walks in chunks of 64 through ONE
 // LDS stage (16 KB of A rows, 32 KB of B rows, the same rotation swizzle), the next chunk
 // travelling in registers meanwhile (12 pieces a thread); two blocks fit a compute unit, so one
 // block's barriers and its wait for the chunk are covered by the other's arithmetic.
@@ -269,7 +273,7 @@ __device__ __forceinline__ void mfma_tile_128x256_body(const uint16_t* __restric
             for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < 8; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[nt], fa[mt], acc[mt][nt], 0, 0, 0);
         }
     }
     __syncthreads();
@@ -287,39 +291,53 @@ __device__ __forceinline__ void mfma_tile_128x256(const uint16_t* __restrict__ A
         mfma_tile_128x256_body<false>(A, lda, M, B, ldb, N, K, m0, n0, lds, acc);
 }
 
-// Epilogue of the 128 x 256 tile: value(r, c, v) maps row r, column c of the tile and the
-// accumulated v to the number stored as bf16; staged through all 64 KB of the tile's LDS so that
-// the rows leave as 16-byte pieces (32 consecutive threads on one row); rows past M and columns
-// past N are dropped.
-template <typename Value>
-__device__ __forceinline__ void big_tile_store_bf16(BigTileLds& lds, const f32x4_t (&acc)[4][8], uint16_t* __restrict__ C,
-                                                    int64_t ldc, int64_t M, int64_t N, int64_t m0, int64_t n0,
-                                                    Value value) {
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+// Epilogue of the 128 x 256 tile: the accumulators (already finished by the caller: bias,
+// activation, ...) leave as bf16 through all 64 KB of the tile's LDS so that the rows go out as
+// 16-byte pieces (32 consecutive threads on one row); rows past M and columns past N are dropped.
+// A lane's four values of a tile are 8 bytes of one row; piece p (16 bytes) of row r sits at piece
+// p xor (r mod 32) of that row, which spreads the 16 rows that the lanes of a group write at once
+// over the banks (the rows are 512 bytes apart).  The main loop ends with a barrier, so the staging may
+// begin at once ...
+// ... in two steps, so that an epilogue can finish, pack and stage one accumulator at a time (128
+// finished values held until the end do not fit beside what the finishing needs):
+// big_tile_stage puts the four values of acc[mt][nt] in place, big_tile_flush writes the tile out.
+__device__ __forceinline__ void big_tile_stage(BigTileLds& lds, int mt, int nt, const f32x4_t& v) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int j = lane & 15, kg = lane >> 4;
     const int wm = wv >> 1, wn = wv & 1;
-    uint16_t* st = (uint16_t*)&lds;
-#pragma unroll
-    for (int nt = 0; nt < 8; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int r = 64 * wm + 16 * mt + 4 * kg + q, c = 128 * wn + 16 * nt + j;
-                st[r * kBigN + c] = f32_to_bf16(value(r, c, acc[mt][nt][q]));
-            }
+    uint2* st = (uint2*)&lds;                        // [128 rows][64 half pieces of 8 bytes]
+    const int r = 64 * wm + 16 * mt + j;
+    const int piece = (16 * wn + 2 * nt + (kg >> 1)) ^ (r & 31);
+    st[r * 64 + 2 * piece + (kg & 1)] = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+}
+
+__device__ __forceinline__ void big_tile_flush(BigTileLds& lds, uint16_t* __restrict__ C, int64_t ldc, int64_t M, int64_t N,
+                                               int64_t m0, int64_t n0) {
+    const int tid = threadIdx.x;
     __syncthreads();
+    const uint4* sp = (const uint4*)&lds;            // [128 rows][32 pieces]
     const bool vec = (ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(C) & 15u) == 0;
     for (int idx = tid; idx < kBigM * (kBigN / 8); idx += 256) {
         const int r = idx >> 5, pc = idx & 31;
         const int64_t t = m0 + r, n = n0 + 8 * pc;
         if (t >= M || n >= N) continue;
+        const uint4 v = sp[r * 32 + (pc ^ (r & 31))];
         if (vec && n + 8 <= N) {
-            *(uint4*)(C + t * ldc + n) = *(const uint4*)(st + r * kBigN + 8 * pc);
+            *(uint4*)(C + t * ldc + n) = v;
         } else {
-            for (int e = 0; e < 8 && n + e < N; ++e) C[t * ldc + n + e] = st[r * kBigN + 8 * pc + e];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            for (int e = 0; e < 8 && n + e < N; ++e) C[t * ldc + n + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
         }
     }
+}
+
+__device__ __forceinline__ void big_tile_store_bf16(BigTileLds& lds, const f32x4_t (&acc)[4][8], uint16_t* __restrict__ C,
+                                                    int64_t ldc, int64_t M, int64_t N, int64_t m0, int64_t n0) {
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) big_tile_stage(lds, mt, nt, acc[mt][nt]);
+    big_tile_flush(lds, C, ldc, M, N, m0, n0);
 }
 
 }  // namespace fff

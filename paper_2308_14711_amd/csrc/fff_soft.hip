@@ -189,27 +189,31 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_big_kernel(const SoftArgs a
     const int wm = wv >> 1, wn = wv & 1;
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) {
-        const int64_t n = n0 + 128 * wn + 16 * nt + j;
-        if (n >= a.NN) continue;
-        const float b = bf16_to_f32(a.node_b[n]);
+        const int64_t n = n0 + 128 * wn + 16 * nt + 4 * kg;          // this lane's nodes n .. n + 3
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int q = 0; q < 4; ++q) {
+            if (n + q >= a.NN) continue;
+            const float b = bf16_to_f32(a.node_b[n + q]);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t t = t0 + 64 * wm + 16 * mt + 4 * kg + q;
-                if (t < a.T) a.choice[t * a.NN + n] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
+            for (int mt = 0; mt < 4; ++mt) {
+                const int64_t t = t0 + 64 * wm + 16 * mt + j;
+                if (t < a.T) a.choice[t * a.NN + n + q] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
             }
+        }
     }
 }
 
 // Trees of up to 256 leaves (all nodes in one column tile): the node contraction, the mixture weights and
 // the entropy sums in one launch -- the scores never go to memory.  After the contraction the tile's
-// scores pass through LDS 64 rows at a time (column n of row r at 256 r + (n xor 16 ((r / 4) mod 4)):
-// the accumulator layout has lane groups four rows apart on equal columns, the xor spreads them over
-// the banks; the readers below run along a row).  Then a wave takes 16 of the rows and multiplies
+// scores pass through LDS 64 rows at a time (column n of row r at 256 r + (n xor 4 (r mod 16)): a lane
+// stores its four consecutive columns as 16 bytes, the 16 lanes of a group are 16 rows on equal
+// columns, and the xor on the 16-byte piece index spreads them over the banks; the readers below run
+// along a row).  Then a wave takes 16 of the rows and multiplies
 // every leaf's path, root first (the factors and their order are those of soft_mix_kernel: same bits),
 // writing the mixture weights and the bias columns of the hidden matrix; thread n adds the entropies
 // of node n over the tile's rows in row order into part[row tile][n].
+__device__ __forceinline__ int score_slot(int r, int n) { return 256 * r + (n ^ (4 * (r & 15))); }
+
 __global__ __launch_bounds__(256, 2) void soft_nodes_mix_kernel(const SoftArgs a, float* __restrict__ ent_part) {
     __shared__ BigTileLds tile;
     int64_t t0, n0;
@@ -221,12 +225,13 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_mix_kernel(const SoftArgs a
     const int NL = (int)a.NL, NN = (int)a.NN;
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) {
-        const int n = 128 * wn + 16 * nt + j;
-        const float b = n < NN ? bf16_to_f32(a.node_b[n]) : 0.0f;
+        const int n = 128 * wn + 16 * nt + 4 * kg;                   // this lane's nodes n .. n + 3
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int q = 0; q < 4; ++q) {
+            const float b = n + q < NN ? bf16_to_f32(a.node_b[n + q]) : 0.0f;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) acc[mt][nt][q] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
+            for (int mt = 0; mt < 4; ++mt) acc[mt][nt][q] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
+        }
     }
     float* const S = (float*)&tile;                     // [64][256] scores of one half of the tile's rows
     const int per_log = NL >= 256 ? 2 : NL >= 128 ? 1 : 0;   // leaves per lane: 4, 2 or 1
@@ -235,12 +240,10 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_mix_kernel(const SoftArgs a
     for (int h = 0; h < 2; ++h) {
         if (wm == h) {
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt)
+            for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        S[256 * (16 * mt + 4 * kg + q) + ((128 * wn + 16 * nt + j) ^ (16 * kg))] = acc[mt][nt][q];
+                for (int nt = 0; nt < 8; ++nt)
+                    *(f32x4_t*)(S + score_slot(16 * mt + j, 128 * wn + 16 * nt + 4 * kg)) = acc[mt][nt];
         }
         __syncthreads();
         for (int rr = 0; rr < 16; ++rr) {
@@ -248,7 +251,7 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_mix_kernel(const SoftArgs a
             const int64_t t = t0 + 64 * h + r;
             if (t >= a.T) break;
             const float* Sr = S + 256 * r;
-            const int sw = 16 * ((r >> 2) & 3);
+            const int sw = 4 * (r & 15);
             // a lane takes `per` consecutive leaves (4 for 256 leaves): their paths share all but the last
             // log2(per) levels, so the shared factors are multiplied once, root first, and the product
             // then splits level by level -- every leaf still sees its factors in root-to-leaf order
@@ -296,13 +299,16 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_mix_kernel(const SoftArgs a
         }
         if (ent_part != nullptr && tid < NN) {
             for (int r = 0; r < 64 && t0 + 64 * h + r < a.T; ++r)
-                ent += bernoulli_entropy(S[256 * r + (tid ^ (16 * ((r >> 2) & 3)))]);
+                ent += bernoulli_entropy(S[score_slot(r, tid)]);
         }
         __syncthreads();
     }
     if (ent_part != nullptr && tid < NN) ent_part[(t0 / kBigM) * a.NN + tid] = ent;
 }
 
+// GELU: the activation is a template parameter -- chosen per element at run time it puts a branch around
+// every one of a lane's 128 evaluations, which then run one after the other
+template <bool GELU>
 __global__ __launch_bounds__(256, 2) void soft_hidden_big_kernel(const SoftArgs a) {
     __shared__ BigTileLds tile;
     const int64_t NH = a.NL * a.L;
@@ -311,31 +317,57 @@ __global__ __launch_bounds__(256, 2) void soft_hidden_big_kernel(const SoftArgs 
     if (!big_tile_of_block(ncb, a.T, t0, n0)) return;
     f32x4_t acc[4][8];
     mfma_tile_128x256(a.x, a.D, a.T, a.w1, a.D, NH, a.D, t0, n0, tile, acc);
-    // bias, activation and the mixture weight of the column's leaf, straight from the mixture matrix
-    // (a lane's 16 columns of a row are consecutive neurons: a handful of leaves, L2 hits)
+    // bias, activation and the mixture weight of the neuron's leaf.  A lane holds four consecutive
+    // neurons of a token per accumulator: one 8-byte load of biases and, where the four belong to one
+    // leaf (leaf widths that are multiples of 4), one mixture weight serve all four.
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, j = lane & 15, kg = lane >> 4;
     const int wm = wv >> 1, wn = wv & 1;
-    int leaf[8];
-    float bias[8];
+    const float* mrow[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int64_t t = t0 + 64 * wm + 16 * mt + j;
+        mrow[mt] = a.mix + (t < a.T ? t : a.T - 1) * a.NL;
+    }
+    const bool one_leaf = a.L % 4 == 0;
+    const bool bias_vec = (reinterpret_cast<uintptr_t>(a.b1) & 7u) == 0;
+    const uint32_t L32 = (uint32_t)a.L, last = (uint32_t)(NH - 1);       // the width fits 32 bits (soft_shape_ok)
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) {
-        const int64_t n = n0 + 128 * wn + 16 * nt + j;
-        bias[nt] = n < NH ? bf16_to_f32(a.b1[n]) : 0.0f;
-        leaf[nt] = n < NH ? (int)(n / a.L) : -1;
-    }
+        const uint32_t n = (uint32_t)(n0 + 128 * wn + 16 * nt + 4 * kg);   // this lane's neurons n .. n + 3
+        // columns past the last neuron are dropped by the store: their look-ups are clamped, not skipped
+        const uint32_t nc = n < last ? n : last;
+        float bias[4];
+        if (bias_vec && n + 3 <= last) {
+            const uint2 b = *(const uint2*)(a.b1 + n);
+            bias[0] = bf16_to_f32((uint16_t)b.x); bias[1] = bf16_to_f32((uint16_t)(b.x >> 16));
+            bias[2] = bf16_to_f32((uint16_t)b.y); bias[3] = bf16_to_f32((uint16_t)(b.y >> 16));
+        } else {
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+            for (int q = 0; q < 4; ++q) bias[q] = bf16_to_f32(a.b1[nc + q < last ? nc + q : last]);
+        }
+        // one division per group of four: the leaf of neuron n + q is that of n plus the number of leaf
+        // boundaries crossed, at most three (q <= 3)
+        const uint32_t leaf0 = nc / L32, rem = nc - leaf0 * L32;
+        uint32_t leaf[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int64_t t = t0 + 64 * wm + 16 * mt + 4 * kg + q;
-            const float* __restrict__ mrow = a.mix + (t < a.T ? t : a.T - 1) * a.NL;
-#pragma unroll
-            for (int nt = 0; nt < 8; ++nt) {
-                const float m = leaf[nt] >= 0 ? mrow[leaf[nt]] : 0.0f;
-                acc[mt][nt][q] = activate_bulk(acc[mt][nt][q] + bias[nt], a.act) * m;
-            }
+            const uint32_t o = rem + q;
+            uint32_t lf = leaf0 + (o >= L32) + (o >= 2 * L32) + (o >= 3 * L32);
+            leaf[q] = lf < (uint32_t)a.NL ? lf : (uint32_t)a.NL - 1;
         }
-    big_tile_store_bf16(tile, acc, a.hid, a.K2, a.T, NH, t0, n0, [](int, int, float v) { return v; });
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            float m[4];
+            m[0] = mrow[mt][leaf[0]];
+#pragma unroll
+            for (int q = 1; q < 4; ++q) m[q] = one_leaf ? m[0] : mrow[mt][leaf[q]];
+            f32x4_t v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = activate_bulk(acc[mt][nt][q] + bias[q], GELU ? 1 : 0) * m[q];
+            big_tile_stage(tile, mt, nt, v);         // finished, packed and staged at once: nothing is held back
+        }
+    }
+    big_tile_flush(tile, a.hid, a.K2, a.T, NH, t0, n0);
 }
 
 __global__ __launch_bounds__(256, 2) void soft_out_big_kernel(const SoftArgs a) {
@@ -345,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void soft_out_big_kernel(const SoftArgs a) 
     if (!big_tile_of_block(ncb, a.T, t0, n0)) return;
     f32x4_t acc[4][8];
     mfma_tile_128x256(a.hid, a.K2, a.T, a.w2x, a.K2, a.O, (int)a.K2, t0, n0, tile, acc);
-    big_tile_store_bf16(tile, acc, a.out, a.O, a.T, a.O, t0, n0, [](int, int, float v) { return v; });
+    big_tile_store_bf16(tile, acc, a.out, a.O, a.T, a.O, t0, n0);
 }
 
 // W2x[o][k] = W2[k][o] for k < NL * L, b2[k - NL * L][o] for the next NL, zeros up to K2.
@@ -421,7 +453,8 @@ __global__ __launch_bounds__(256) void soft_entropy_sum_kernel(const float* __re
 // bf16, D a multiple of 8, 16-byte aligned rows of x, node_w, leaf_w1
 bool soft_shape_ok(const Problem& p) {
     return p.bf16 && vec_ok(p.x, p.D, true) && (p.depth == 0 || vec_ok(p.node_w, p.D, true)) &&
-           vec_ok(p.leaf_w1, p.D, true) && p.D < (1 << 30) && p.O < (1 << 30);
+           vec_ok(p.leaf_w1, p.D, true) && p.D < (1 << 30) && p.O < (1 << 30) &&
+           (((int64_t)p.L + 1) << p.depth) < ((int64_t)1 << 30);        // the hidden matrix's width fits 32 bits
 }
 
 static int64_t soft_k2(const Problem& p) {
@@ -509,8 +542,10 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    if (big_hidden)
-        soft_hidden_big_kernel<<<dim3(big_grid(p.T, (a.NL * a.L + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
+    if (big_hidden && a.act != 0)
+        soft_hidden_big_kernel<true><<<dim3(big_grid(p.T, (a.NL * a.L + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
+    else if (big_hidden)
+        soft_hidden_big_kernel<false><<<dim3(big_grid(p.T, (a.NL * a.L + kBigN - 1) / kBigN)), dim3(256), 0, s>>>(a);
     else
         soft_hidden_kernel<<<dim3((unsigned)(mb * ((a.NL * a.L + kTileN - 1) / kTileN))), dim3(256), 0, s>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
