@@ -169,12 +169,15 @@ __device__ __forceinline__ void tile_store_bf16(TileLds& lds, const f32x4_t (&ac
 
 // ---- the 128 x 256 tile of the large dense contractions (soft forward pass) -------------------
 //
-// A compute unit's LDS delivers 128 bytes a clock, its four matrix cores together 4096 bf16 flops
-// a clock: a tile has to do at least 32 flops per byte that passes through LDS or LDS is what
-// bounds it.  For a block tile of M x N with four waves in a 2 x 2 arrangement every chunk of K
-// is written once ((M + N) K 2 bytes) and read once per wave ((M/2 + N/2) K 2 bytes, four waves),
-// 2 M N K flops in all: M N / (3 (M + N)) flops per byte -- 14 for the 64 x 128 tile above (its
-// waves each hold all 64 rows, which makes it 12 reads for 16 MFMAs), 28 for 128 x 256.  So:
+// Per clock a compute unit's LDS takes 128 bytes of stores and gives 256 bytes of 16-byte reads
+// (conflict-free ones), its address unit moves 64 bytes of global loads, and its four matrix cores do
+// 4096 bf16 flops: a chunk of K of a 64 x 128 tile costs the matrix cores 256 clocks, the LDS 288
+// and the address unit 384 -- the small tile is bound by the traffic around the matrix cores.  For a
+// block tile of M x N with four waves in a 2 x 2 arrangement every chunk is loaded and stored once
+// ((M + N) K 2 bytes) and read once per wave ((M/2 + N/2) K 2 bytes, four waves) for 2 M N K flops:
+// all three kinds of traffic per flop fall as M N / (M + N) grows.  128 x 256 (1024 matrix-core clocks
+// per chunk against 768 of the LDS and 768 of the address unit) is the largest tile of which two
+// blocks fit a compute unit with accumulators in ordinary registers.  So:
 // 256 threads, wave (wm, wn) owns rows 64 wm .. + 63 and columns 128 wn .. + 127 as 4 x 8
 // accumulators of v_mfma_f32_16x16x32_bf16 (128 registers).  The B rows go in as the instruction's
 // first operand, so acc[mt][nt] of lane (j, kg) holds row 64 wm + 16 mt + j against the FOUR
