@@ -171,7 +171,7 @@ __device__ __forceinline__ void tile_store_bf16(TileLds& lds, const f32x4_t (&ac
 //
 // Per clock a compute unit's LDS takes 128 bytes of stores and gives 256 bytes of 16-byte reads
 // (conflict-free ones), its address unit moves 64 bytes of global loads, and its four matrix cores do
-// 4096 bf16 flops: a chunk of K of a 64 x 128 tile costs the matrix cores 256 clocks, the LDS 288
+// 4096 bf16 flops: a chunk of K of a 64 x 128 tile costs the matrix cores 256 clocks, the LDS 384
 // and the address unit 384 -- the small tile is bound by the traffic around the matrix cores.  For a
 // block tile of M x N with four waves in a 2 x 2 arrangement every chunk is loaded and stored once
 // ((M + N) K 2 bytes) and read once per wave ((M/2 + N/2) K 2 bytes, four waves) for 2 M N K flops:
