@@ -29,7 +29,7 @@ struct SoftArgs {
     const uint16_t* b1;
     const uint16_t* w2;
     const uint16_t* b2;
-    float* choice;        // [T][NN]
+    float* choice;        // [T][NL]: NN scores per row, pitch NL so that rows start 16-byte aligned
     float* mix;           // [T][NL]
     uint16_t* hid;        // [T][K2]
     uint16_t* w2x;        // [O][K2]
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void soft_nodes_kernel(const SoftArgs a) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int64_t t = t0 + 16 * mt + 4 * kg + q;
-                if (t < a.T) a.choice[t * a.NN + n] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
+                if (t < a.T) a.choice[t * a.NL + n] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
             }
     }
 }
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void soft_mix_kernel(const SoftArgs a) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= a.T * a.NL) return;
     const int64_t t = i / a.NL, leaf = i % a.NL;
-    const float* c = a.choice + t * a.NN;
+    const float* c = a.choice + t * a.NL;
     float m = 1.0f;
     for (int lvl = 0; lvl < a.depth; ++lvl) {
         const int64_t pos = leaf >> (a.depth - lvl);                  // the path's node at this level
@@ -92,24 +92,43 @@ __global__ __launch_bounds__(256) void soft_mix_kernel(const SoftArgs a) {
         for (int64_t k = a.NL * (a.L + 1); k < a.K2; ++k) a.hid[t * a.K2 + k] = 0;
 }
 
-// The same for trees of up to 1024 leaves, a wave per token: the products grow level by level in a
+// The same for trees of up to 2048 leaves, a wave per token: the products grow level by level in a
 // wave-private LDS row (entry n of level m = entry n / 2 of level m - 1 times c or 1 - c of that
-// node), so a token's scores are read once, along the row, instead of once per leaf and level; the
-// factors are multiplied in the same order as above (root first): same bits.
-constexpr int kMixMaxLeaves = 1024;
+// node), so a token's scores are read once instead of once per leaf and level; the factors are
+// multiplied in the same order as above (root first): same bits.  The scores themselves come in
+// through registers, all of a token's loads in flight at once and the next token's requested before
+// this token's levels are walked (a load inside the level loop is a trip to memory per iteration),
+// and are parked in a third LDS row for the levels to index.  LDS: 3 NL floats per wave; blocks of
+// four waves, or of two for 2048 leaves (48 KB either way at most).
+constexpr int kMixMaxLeaves = 2048;
+constexpr int kMixRegs = kMixMaxLeaves / kWave;          // scores a lane holds for one token
 __global__ __launch_bounds__(256) void soft_mix_rows_kernel(const SoftArgs a) {
-    extern __shared__ float mix_lds[];                       // per wave: two rows of NL products
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int NL = (int)a.NL;
-    float* cur = mix_lds + (size_t)wv * 2 * NL;
+    extern __shared__ float mix_lds[];                       // per wave: the scores, then two rows of NL products
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int NL = (int)a.NL, NN = (int)a.NN;
+    float* sc = mix_lds + (size_t)wv * 3 * NL;
+    float* cur = sc + NL;
     float* nxt = cur + NL;
-    for (int64_t t = (int64_t)blockIdx.x * 4 + wv; t < a.T; t += (int64_t)gridDim.x * 4) {
-        const float* c = a.choice + t * a.NN;
+    const int per_lane = (NN + kWave - 1) / kWave;           // <= kMixRegs
+    float creg[kMixRegs];
+    const auto request = [&](int64_t t) {
+        const float* c = a.choice + t * a.NL;
+#pragma unroll
+        for (int i = 0; i < kMixRegs; ++i)
+            if (i < per_lane) creg[i] = lane + kWave * i < NN ? c[lane + kWave * i] : 0.0f;
+    };
+    const int64_t first = (int64_t)blockIdx.x * waves + wv, step = (int64_t)gridDim.x * waves;
+    if (first < a.T) request(first);
+    for (int64_t t = first; t < a.T; t += step) {
+#pragma unroll
+        for (int i = 0; i < kMixRegs; ++i)
+            if (i < per_lane && lane + kWave * i < NN) sc[lane + kWave * i] = creg[i];
+        if (t + step < a.T) request(t + step);               // travels while this token's levels are walked
         if (lane == 0) cur[0] = 1.0f;
         __builtin_amdgcn_wave_barrier();
         for (int lvl = 0; lvl < a.depth; ++lvl) {
             const int n_nodes = 1 << lvl;                    // nodes of this level; 2 n_nodes entries come out
-            const float* cl = c + (n_nodes - 1);
+            const float* cl = sc + (n_nodes - 1);
             for (int e = lane; e < 2 * n_nodes; e += kWave) {
                 const float cs = cl[e >> 1];
                 nxt[e] = cur[e >> 1] * ((e & 1) ? cs : 1.0f - cs);
@@ -190,15 +209,20 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_big_kernel(const SoftArgs a
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) {
         const int64_t n = n0 + 128 * wn + 16 * nt + 4 * kg;          // this lane's nodes n .. n + 3
+        if (n >= a.NL) continue;                                     // (the row's last float, past the NN scores, is padding)
+        float b[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (n + q >= a.NN) continue;
-            const float b = bf16_to_f32(a.node_b[n + q]);
+        for (int q = 0; q < 4; ++q) b[q] = n + q < a.NN ? bf16_to_f32(a.node_b[n + q]) : 0.0f;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                const int64_t t = t0 + 64 * wm + 16 * mt + j;
-                if (t < a.T) a.choice[t * a.NN + n + q] = 1.0f / (1.0f + __expf(-(acc[mt][nt][q] + b)));
-            }
+        for (int mt = 0; mt < 4; ++mt) {
+            const int64_t t = t0 + 64 * wm + 16 * mt + j;
+            if (t >= a.T) continue;
+            float4 c;
+            c.x = 1.0f / (1.0f + __expf(-(acc[mt][nt][0] + b[0])));
+            c.y = 1.0f / (1.0f + __expf(-(acc[mt][nt][1] + b[1])));
+            c.z = 1.0f / (1.0f + __expf(-(acc[mt][nt][2] + b[2])));
+            c.w = 1.0f / (1.0f + __expf(-(acc[mt][nt][3] + b[3])));
+            *(float4*)(a.choice + t * a.NL + n) = c;                 // NL >= 256 here: a multiple of 4, rows 16-byte aligned
         }
     }
 }
@@ -421,13 +445,13 @@ __global__ __launch_bounds__(256) void soft_out_kernel(const SoftArgs a) {
 constexpr int kEntTokens = 32;
 
 __global__ __launch_bounds__(256) void soft_entropy_part_kernel(const float* __restrict__ choice, int64_t T, int64_t NN,
-                                                                float* __restrict__ part) {
+                                                                int64_t pitch, float* __restrict__ part) {
     const int64_t t0 = (int64_t)blockIdx.x * kEntTokens;
     const int64_t t1 = t0 + kEntTokens < T ? t0 + kEntTokens : T;
     for (int64_t n = threadIdx.x; n < NN; n += 256) {
         float s = 0.0f;
         for (int64_t t = t0; t < t1; ++t) {
-            s += bernoulli_entropy(choice[t * NN + n]);
+            s += bernoulli_entropy(choice[t * pitch + n]);
         }
         part[(int64_t)blockIdx.x * NN + n] = s;
     }
@@ -466,7 +490,7 @@ static int64_t soft_k2(const Problem& p) {
 int64_t soft_scratch_words(const Problem& p) {
     const int64_t NL = (int64_t)1 << p.depth, NN = NL - 1, K2 = soft_k2(p);
     auto up = [](int64_t w) { return (w + 63) / 64 * 64; };
-    return up(p.T * (NN > 0 ? NN : 1)) + up(p.T * NL) + up((p.T * K2 + 1) / 2) + up((p.O * K2 + 1) / 2) +
+    return up(p.T * NL) + up(p.T * NL) + up((p.T * K2 + 1) / 2) + up((p.O * K2 + 1) / 2) +
            up((p.T + kEntTokens - 1) / kEntTokens * (NN > 0 ? NN : 1));
 }
 
@@ -495,7 +519,7 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
     a.act = p.act;
     int32_t* w = scratch;
     a.choice = (float*)w;
-    w += up(p.T * (a.NN > 0 ? a.NN : 1));
+    w += up(p.T * a.NL);
     a.mix = mix_out ? mix_out : (float*)w;
     w += up(p.T * a.NL);
     a.hid = (uint16_t*)w;
@@ -533,10 +557,12 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
         if (a.NL <= kMixMaxLeaves) {
-            int64_t blocks = (p.T + 3) / 4;
+            const int waves = a.NL > 1024 ? 2 : 4;
+            int64_t blocks = (p.T + waves - 1) / waves;
             const int64_t cap = (int64_t)device_info().cus * 8;
             if (blocks > cap) blocks = cap;
-            soft_mix_rows_kernel<<<dim3((unsigned)blocks), dim3(256), sizeof(float) * 8 * (size_t)a.NL, s>>>(a);
+            const size_t lds_bytes = sizeof(float) * 3 * waves * (size_t)a.NL;      // at most 48 KB
+            soft_mix_rows_kernel<<<dim3((unsigned)blocks), dim3(64 * waves), lds_bytes, s>>>(a);
         } else {
             soft_mix_kernel<<<dim3((unsigned)((p.T * a.NL + 255) / 256)), dim3(256), 0, s>>>(a);
         }
@@ -560,7 +586,7 @@ hipError_t launch_forward_soft(const Problem& p, int32_t* scratch, float* mix_ou
         int64_t n_parts = (p.T + kBigM - 1) / kBigM;        // the fused launch leaves one partial sum per row tile
         if (!fused_nodes) {
             n_parts = (p.T + kEntTokens - 1) / kEntTokens;
-            soft_entropy_part_kernel<<<dim3((unsigned)n_parts), dim3(256), 0, s>>>(a.choice, p.T, a.NN, ent_part);
+            soft_entropy_part_kernel<<<dim3((unsigned)n_parts), dim3(256), 0, s>>>(a.choice, p.T, a.NN, a.NL, ent_part);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
         soft_entropy_sum_kernel<<<dim3((unsigned)a.NN), dim3(256), 0, s>>>(ent_part, n_parts, p.T, a.NN, entropy_out);

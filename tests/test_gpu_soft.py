@@ -24,7 +24,8 @@ CASES = [
     ("big_whole",    2304, 128, 256, 8, 1,  W.ACT_RELU),
     ("big_shallow",  2200, 96,  24,  2, 4,  W.ACT_GELU),      # three nodes in the fused nodes + mixture launch
     ("big_deep",     2050, 64,  40,  9, 1,  W.ACT_RELU),      # 511 nodes: two column tiles, separate mixture kernel
-    ("big_deeper",   2048, 64,  16,  11, 1, W.ACT_GELU),      # 2048 leaves: the per-leaf mixture kernel
+    ("big_deeper",   2048, 64,  16,  11, 1, W.ACT_GELU),      # 2048 leaves: 64 KB of LDS in the mixture kernel
+    ("per_leaf_mix", 300,  64,  16,  12, 1, W.ACT_RELU),      # 4096 leaves: the per-leaf mixture kernel
 ]
 
 
