@@ -326,7 +326,7 @@ __device__ __forceinline__ void big_tile_flush(BigTileLds& lds, uint16_t* __rest
         if (t >= M || n >= N) continue;
         const uint4 v = sp[r * 32 + (pc ^ (r & 31))];
         if (vec && n + 8 <= N) {
-            *(uint4*)(C + t * ldc + n) = v;
+            store_stream((uint4*)(C + t * ldc + n), v);      // results are not read again by this launch: keep the L2 for operands
         } else {
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
             for (int e = 0; e < 8 && n + e < N; ++e) C[t * ldc + n + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));

@@ -138,8 +138,8 @@ __global__ __launch_bounds__(256) void soft_mix_rows_kernel(const SoftArgs a) {
         }
         for (int leaf = lane; leaf < NL; leaf += kWave) {
             const float m = cur[leaf];
-            a.mix[t * a.NL + leaf] = m;
-            a.hid[t * a.K2 + a.NL * a.L + leaf] = f32_to_bf16(m);
+            __builtin_nontemporal_store(m, a.mix + t * a.NL + leaf);
+            __builtin_nontemporal_store(f32_to_bf16(m), a.hid + t * a.K2 + a.NL * a.L + leaf);
         }
         for (int64_t k = a.NL * (a.L + 1) + lane; k < a.K2; k += kWave) a.hid[t * a.K2 + k] = 0;
         __builtin_amdgcn_wave_barrier();
@@ -222,7 +222,8 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_big_kernel(const SoftArgs a
             c.y = 1.0f / (1.0f + __expf(-(acc[mt][nt][1] + b[1])));
             c.z = 1.0f / (1.0f + __expf(-(acc[mt][nt][2] + b[2])));
             c.w = 1.0f / (1.0f + __expf(-(acc[mt][nt][3] + b[3])));
-            *(float4*)(a.choice + t * a.NL + n) = c;                 // NL >= 256 here: a multiple of 4, rows 16-byte aligned
+            // NL >= 256 here: a multiple of 4, rows 16-byte aligned; read once by the mixture launch
+            __builtin_nontemporal_store(f32x4_t{c.x, c.y, c.z, c.w}, (f32x4_t*)(a.choice + t * a.NL + n));
         }
     }
 }
@@ -300,13 +301,16 @@ __global__ __launch_bounds__(256, 2) void soft_nodes_mix_kernel(const SoftArgs a
                     // (the hidden matrix is the library's, K2 a multiple of 8)
                     float* mp = a.mix + t * a.NL + first;
                     if (mix_vec) {
-                        *(float4*)mp = make_float4(m[0], m[1], m[2], m[3]);
+                        __builtin_nontemporal_store(f32x4_t{m[0], m[1], m[2], m[3]}, (f32x4_t*)mp);     // written once, read by a later launch
                     } else {
                         mp[0] = m[0]; mp[1] = m[1]; mp[2] = m[2]; mp[3] = m[3];
                     }
-                    *(uint2*)(a.hid + t * a.K2 + a.NL * a.L + first) =
-                        make_uint2((uint32_t)f32_to_bf16(m[0]) | ((uint32_t)f32_to_bf16(m[1]) << 16),
-                                   (uint32_t)f32_to_bf16(m[2]) | ((uint32_t)f32_to_bf16(m[3]) << 16));
+                    {
+                        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+                        const u32x2_t packed = {(uint32_t)f32_to_bf16(m[0]) | ((uint32_t)f32_to_bf16(m[1]) << 16),
+                                                (uint32_t)f32_to_bf16(m[2]) | ((uint32_t)f32_to_bf16(m[3]) << 16)};
+                        __builtin_nontemporal_store(packed, (u32x2_t*)(a.hid + t * a.K2 + a.NL * a.L + first));
+                    }
                 } else if (per_log == 1) {
                     const float c7 = Sr[(((1 << shared) - 1) + lane) ^ sw];
                     m[1] = m[0] * c7; m[0] = m[0] * (1.0f - c7);
